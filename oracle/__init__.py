@@ -1,0 +1,22 @@
+"""CPU oracle for the sparse-gradient encode + aggregate path (TEST INFRASTRUCTURE ONLY).
+
+`zen_ref.c` is the plain single-threaded definition; this module compiles it with gcc and wraps it
+with ctypes + numpy.  Nothing here imports or is imported by the HIP package.  Only the tests, the
+smoke check and the benchmark's cpu_baseline leg may use it.
+"""
+from .zen_ref import (  # noqa: F401
+    build,
+    lib,
+    hash32,
+    hash_many,
+    owner_table,
+    nonzero,
+    partition,
+    gather,
+    encode,
+    bitmap_layout,
+    bitmap_encode,
+    bitmap_decode,
+    aggregate,
+    imbalance,
+)

@@ -1,0 +1,305 @@
+/*
+ * zen_ref.c -- CPU oracle for the sparse-gradient encode + aggregate path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, single-threaded
+ * definition of what the GPU library must compute.  It shares no code, header,
+ * table or constant generator with the HIP sources, and only the test-suite,
+ * the smoke check and the benchmark's cpu_baseline leg may load it.
+ *
+ * Every function states the passage of the paper (arXiv 2309.13254, "Zen")
+ * it follows.  The paper's hierarchical hashing (Algorithm 1) is lossless: its
+ * output is, for each partition, exactly the set of non-zero indices owned by
+ * that partition together with their values (Algorithm 1, output loop; section
+ * "Data-independent Hierarchical Hashing", paragraph "Negligible extraction
+ * overhead").  The oracle is therefore that plain definition written out, not
+ * the hash-memory mechanism.
+ *
+ * Readings taken where the paper is silent (each is pinned by a CPU test):
+ *   - indices are 0-based row ids (the paper counts from 1);
+ *   - a row is "non-zero" iff any of its D fp32 words has a non-zero magnitude
+ *     field, i.e. (bits & 0x7fffffff) != 0, so +0 and -0 are zero while NaN,
+ *     Inf and denormals are non-zero;
+ *   - inside a partition indices ascend (the paper leaves the order free
+ *     because it does not change the aggregate);
+ *   - h0(idx) = MurmurHash3_x86_32(4-byte little-endian idx, seed) mod n
+ *     (section "Implementation" names MurmurHash with seeds, nothing more);
+ *   - hash bitmap: bit j of partition p tells whether the j-th smallest row of
+ *     the partition's domain is non-zero; bits are packed LSB-first into
+ *     32-bit words and every partition starts on a word boundary;
+ *   - aggregation sums every occurrence of an index in fp64, in input order,
+ *     and keeps an index even when its sum is exactly zero.
+ *
+ * Parity status: every function below is pinned by tests/test_oracle_*.py
+ * (published MurmurHash3 vectors and an independent library implementation,
+ * the paper's worked hash-bitmap example, closed forms, brute force).  The
+ * one thing that cannot be pinned is that h0 equals the hash the paper's own
+ * (unpublished) code used: "parity unpinned" for the paper's hash outputs.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+#define ZEN_REF_OK 0
+#define ZEN_REF_ERR_INVALID 1
+#define ZEN_REF_ERR_CAPACITY 2
+#define ZEN_REF_ERR_NOMEM 3
+
+static uint32_t rotl32(uint32_t x, int r) { return (x << r) | (x >> (32 - r)); }
+
+/*
+ * MurmurHash3, x86 32-bit variant, of one 4-byte key (the index stored little
+ * endian) -- the hash family section "Implementation" names.  One body block,
+ * no tail, length 4, then the finaliser.
+ */
+uint32_t zen_ref_hash(uint32_t idx, uint32_t seed)
+{
+    uint32_t k = idx;
+    uint32_t h = seed;
+    k *= 0xcc9e2d51u;
+    k = rotl32(k, 15);
+    k *= 0x1b873593u;
+    h ^= k;
+    h = rotl32(h, 13);
+    h = h * 5u + 0xe6546b64u;
+    h ^= 4u; /* key length in bytes */
+    h ^= h >> 16;
+    h *= 0x85ebca6bu;
+    h ^= h >> 13;
+    h *= 0xc2b2ae35u;
+    h ^= h >> 16;
+    return h;
+}
+
+void zen_ref_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out)
+{
+    for (uint64_t i = 0; i < count; ++i) out[i] = zen_ref_hash(idx[i], seed);
+}
+
+/* h0 : index -> [n]  (Algorithm 1, "p <- h0(idx)"). */
+uint32_t zen_ref_owner(uint32_t idx, uint32_t seed, uint32_t n)
+{
+    return zen_ref_hash(idx, seed) % n;
+}
+
+/* owner[r] = h0(r) for every row of the dense tensor; n <= 65535. */
+int zen_ref_owner_table(uint64_t n_rows, uint32_t n, uint32_t seed, uint16_t *owner)
+{
+    if (n == 0 || n > 65535u || n_rows > 0xfffffffeull) return ZEN_REF_ERR_INVALID;
+    for (uint64_t r = 0; r < n_rows; ++r) owner[r] = (uint16_t)zen_ref_owner((uint32_t)r, seed, n);
+    return ZEN_REF_OK;
+}
+
+/*
+ * I = ascending indices of the non-zero rows of G (Algorithm 1, input "I is the
+ * indices of its non-zero gradients").  Returns |I|; `I` may be NULL to count.
+ */
+int64_t zen_ref_nonzero(const float *grad, uint64_t n_rows, uint32_t row_dim, uint32_t *I)
+{
+    int64_t nnz = 0;
+    for (uint64_t r = 0; r < n_rows; ++r) {
+        const float *row = grad + r * (uint64_t)row_dim;
+        int nz = 0;
+        for (uint32_t c = 0; c < row_dim; ++c) {
+            uint32_t bits;
+            memcpy(&bits, &row[c], 4);
+            if ((bits & 0x7fffffffu) != 0) { nz = 1; break; }
+        }
+        if (nz) {
+            if (I) I[nnz] = (uint32_t)r;
+            ++nnz;
+        }
+    }
+    return nnz;
+}
+
+/*
+ * Partition an ascending index list by owner (Algorithm 1: every idx goes to
+ * partition h0(idx); output loop: one (indices, values) pair per partition).
+ * `owner_of_I[k]` is the owner of I[k].  offsets has n+1 entries.
+ */
+int zen_ref_partition(const uint32_t *I, const uint16_t *owner_of_I, uint64_t nnz, uint32_t n,
+                      uint32_t *offsets, uint32_t *indices)
+{
+    if (n == 0) return ZEN_REF_ERR_INVALID;
+    uint64_t pos = 0;
+    offsets[0] = 0;
+    for (uint32_t p = 0; p < n; ++p) {
+        for (uint64_t k = 0; k < nnz; ++k)
+            if (owner_of_I[k] == p) indices[pos++] = I[k];
+        offsets[p + 1] = (uint32_t)pos;
+    }
+    return pos == nnz ? ZEN_REF_OK : ZEN_REF_ERR_INVALID; /* an owner >= n would lose an index */
+}
+
+/* values = G[indices] (Algorithm 1, output loop), whole rows, bit-exact. */
+void zen_ref_gather(const float *grad, uint32_t row_dim, const uint32_t *indices, uint64_t count,
+                    float *values)
+{
+    for (uint64_t k = 0; k < count; ++k)
+        memcpy(values + k * (uint64_t)row_dim, grad + (uint64_t)indices[k] * row_dim,
+               (size_t)row_dim * 4);
+}
+
+/*
+ * The whole encode of one worker's gradient: non-zero rows -> owner by h0 ->
+ * per-partition ascending indices and their rows, concatenated partition-major
+ * with an exclusive prefix `offsets` (Problem 1: worker i sends partition j to
+ * server j; Algorithm 1 output).  On ZEN_REF_ERR_CAPACITY *nnz_out still holds
+ * the number of rows needed.
+ */
+int zen_ref_encode(const float *grad, uint64_t n_rows, uint32_t row_dim, uint32_t n, uint32_t seed,
+                   uint32_t *offsets, uint32_t *indices, float *values, uint64_t cap_rows,
+                   uint64_t *nnz_out)
+{
+    if (!grad || n == 0 || n > 65535u || row_dim == 0 || n_rows > 0xfffffffeull)
+        return ZEN_REF_ERR_INVALID;
+    int64_t nnz = zen_ref_nonzero(grad, n_rows, row_dim, NULL);
+    if (nnz_out) *nnz_out = (uint64_t)nnz;
+    if ((uint64_t)nnz > cap_rows) return ZEN_REF_ERR_CAPACITY;
+    uint32_t *I = (uint32_t *)malloc(((size_t)nnz + 1) * 4);
+    uint16_t *own = (uint16_t *)malloc(((size_t)nnz + 1) * 2);
+    if (!I || !own) { free(I); free(own); return ZEN_REF_ERR_NOMEM; }
+    zen_ref_nonzero(grad, n_rows, row_dim, I);
+    for (int64_t k = 0; k < nnz; ++k) own[k] = (uint16_t)zen_ref_owner(I[k], seed, n);
+    int rc = zen_ref_partition(I, own, (uint64_t)nnz, n, offsets, indices);
+    if (rc == ZEN_REF_OK && values) zen_ref_gather(grad, row_dim, indices, (uint64_t)nnz, values);
+    free(I);
+    free(own);
+    return rc;
+}
+
+/*
+ * Hash-bitmap layout (section "Hash Bitmap"): the domain of partition p is
+ * II_p = { r in [0,R) : owner[r] = p } in ascending order; its bitmap has
+ * |II_p| bits.  dom_count[p] = |II_p|; word_off[p] = first 32-bit word of
+ * partition p when every partition starts on a word boundary; word_off[n] is
+ * the total number of words (the appendix "Proof of The Property of Hash
+ * Bitmap" gives sum |II_p| = |G| bits, i.e. |G|/32 words before padding).
+ */
+int zen_ref_bitmap_layout(const uint16_t *owner, uint64_t n_rows, uint32_t n, uint64_t *dom_count,
+                          uint64_t *word_off)
+{
+    if (n == 0) return ZEN_REF_ERR_INVALID;
+    for (uint32_t p = 0; p < n; ++p) dom_count[p] = 0;
+    for (uint64_t r = 0; r < n_rows; ++r) {
+        if (owner[r] >= n) return ZEN_REF_ERR_INVALID;
+        dom_count[owner[r]]++;
+    }
+    word_off[0] = 0;
+    for (uint32_t p = 0; p < n; ++p) word_off[p + 1] = word_off[p] + (dom_count[p] + 31) / 32;
+    return ZEN_REF_OK;
+}
+
+/*
+ * hash_bitmap_encode (Algorithm 2): local = G[II_p]; bit j = [local[j] != 0].
+ * `nz[r]` is 1 iff row r is non-zero.  All partitions are written, partition p
+ * starting at word_off[p]; padding bits are 0.
+ */
+int zen_ref_bitmap_encode(const uint16_t *owner, uint64_t n_rows, uint32_t n, const uint8_t *nz,
+                          const uint64_t *word_off, uint32_t *bitmap)
+{
+    memset(bitmap, 0, (size_t)word_off[n] * 4);
+    for (uint32_t p = 0; p < n; ++p) {
+        uint64_t j = 0; /* position inside II_p */
+        for (uint64_t r = 0; r < n_rows; ++r) {
+            if (owner[r] != p) continue;
+            if (nz[r]) bitmap[word_off[p] + (j >> 5)] |= 1u << (j & 31);
+            ++j;
+        }
+    }
+    return ZEN_REF_OK;
+}
+
+/*
+ * hash_bitmap_decode (Algorithm 2): bitmap indices = positions of the 1 bits;
+ * indices = II_p[bitmap indices].  `bitmap_p` points at partition p's first
+ * word.  Returns the number of indices written (ascending).
+ */
+int64_t zen_ref_bitmap_decode(const uint16_t *owner, uint64_t n_rows, uint32_t p,
+                              const uint32_t *bitmap_p, uint32_t *indices)
+{
+    int64_t count = 0;
+    uint64_t j = 0;
+    for (uint64_t r = 0; r < n_rows; ++r) {
+        if (owner[r] != p) continue;
+        if ((bitmap_p[j >> 5] >> (j & 31)) & 1u) indices[count++] = (uint32_t)r;
+        ++j;
+    }
+    return count;
+}
+
+/*
+ * Aggregation at a server (section "Elemental Dimensions for Synchronization":
+ * gradients with the same indices are aggregated; Definition "imbalance
+ * ratio": II_i is the index set at server i after aggregation).
+ *
+ * Inputs: n_in parts, part w = idx[w][0..counts[w]) with rows val[w][k][0..D).
+ * Output: out_idx = ascending union of all indices (kept even if the sum is 0);
+ * for every output row u and column c
+ *     out_sum[u][c] = sum over every occurrence, in input order (w, then k), fp64
+ *     out_abs[u][c] = sum of |x| over the same occurrences (for the test tolerance)
+ *     out_val[u][c] = (float)out_sum[u][c]
+ * out_ncontrib[u] = number of occurrences.  out_sum/out_abs/out_ncontrib may be
+ * NULL.  Returns U (>= 0), or -(needed rows) if U > cap_rows, or INT64_MIN on a
+ * bad argument / allocation failure.
+ */
+int64_t zen_ref_aggregate(uint32_t n_in, const uint32_t *const *idx, const float *const *val,
+                          const uint64_t *counts, uint64_t n_rows, uint32_t row_dim,
+                          uint32_t *out_idx, float *out_val, double *out_sum, double *out_abs,
+                          uint32_t *out_ncontrib, uint64_t cap_rows)
+{
+    if (row_dim == 0 || n_rows > 0xfffffffeull) return INT64_MIN;
+    uint32_t *occ = (uint32_t *)calloc((size_t)n_rows + 1, 4); /* occurrences per row id */
+    if (!occ) return INT64_MIN;
+    for (uint32_t w = 0; w < n_in; ++w)
+        for (uint64_t k = 0; k < counts[w]; ++k) {
+            if (idx[w][k] >= n_rows) { free(occ); return INT64_MIN; }
+            occ[idx[w][k]]++;
+        }
+    int64_t U = 0;
+    for (uint64_t r = 0; r < n_rows; ++r) if (occ[r]) ++U;
+    if ((uint64_t)U > cap_rows) { free(occ); return -U; }
+
+    /* pos[r] = place of row r in the ascending union */
+    uint32_t *pos = (uint32_t *)malloc(((size_t)n_rows + 1) * 4);
+    double *sum = (double *)calloc((size_t)U * row_dim + 1, 8);
+    double *abs_ = (double *)calloc((size_t)U * row_dim + 1, 8);
+    if (!pos || !sum || !abs_) { free(occ); free(pos); free(sum); free(abs_); return INT64_MIN; }
+    int64_t u = 0;
+    for (uint64_t r = 0; r < n_rows; ++r)
+        if (occ[r]) {
+            out_idx[u] = (uint32_t)r;
+            if (out_ncontrib) out_ncontrib[u] = occ[r];
+            pos[r] = (uint32_t)u++;
+        }
+    for (uint32_t w = 0; w < n_in; ++w)
+        for (uint64_t k = 0; k < counts[w]; ++k) {
+            uint64_t o = (uint64_t)pos[idx[w][k]] * row_dim;
+            const float *row = val[w] + k * (uint64_t)row_dim;
+            for (uint32_t c = 0; c < row_dim; ++c) {
+                sum[o + c] += (double)row[c];
+                abs_[o + c] += fabs((double)row[c]);
+            }
+        }
+    for (uint64_t e = 0; e < (uint64_t)U * row_dim; ++e) {
+        out_val[e] = (float)sum[e];
+        if (out_sum) out_sum[e] = sum[e];
+        if (out_abs) out_abs[e] = abs_[e];
+    }
+    free(occ); free(pos); free(sum); free(abs_);
+    return U;
+}
+
+/*
+ * Imbalance ratio (Definition "The imbalance ratio"): max_j n*|part_j| / total.
+ * Push uses one worker's partition sizes; Pull uses the servers' set sizes
+ * after aggregation.  Returns 1.0 for an empty input (nothing to balance).
+ */
+double zen_ref_imbalance(const uint64_t *sizes, uint32_t n)
+{
+    uint64_t total = 0, mx = 0;
+    for (uint32_t j = 0; j < n; ++j) { total += sizes[j]; if (sizes[j] > mx) mx = sizes[j]; }
+    if (total == 0) return 1.0;
+    return (double)n * (double)mx / (double)total;
+}
