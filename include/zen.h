@@ -1,0 +1,175 @@
+/*
+ * zen.h -- C ABI of the MI355X (gfx950) sparse-gradient encode + aggregate library.
+ *
+ * The library implements the per-GPU hot path of Zen's Balanced Parallelism (arXiv 2309.13254):
+ *   zen_encode     one worker's dense gradient -> n hash partitions of (indices, values)
+ *                  [Algorithm 1 "Hierarchical Hashing Algorithm": input G and its non-zero index set
+ *                  I, p <- h0(idx), output one (indices, values) pair per partition; Problem 1]
+ *   zen_aggregate  the n incoming partitions of one server -> one summed sparse tensor
+ *                  [section "Elemental Dimensions for Synchronization": gradients with the same
+ *                  indices are aggregated; Definition "imbalance ratio": index set II_i at server i]
+ *   hash bitmap    optional index encoding of a partition over its hash domain
+ *                  [section "Hash Bitmap", Algorithm 2 hash_bitmap_encode / hash_bitmap_decode]
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with host_ or the comment says "host".
+ *     Structs (zen_encoded, zen_part, zen_aggregated) live on the host and hold device pointers.
+ *   - The caller owns every buffer, including workspaces; the library allocates device memory only
+ *     inside zen_ctx_create (immutable hash-domain tables) and frees it in zen_ctx_destroy.
+ *   - All work is enqueued on the given HIP stream (hipStream_t passed as void*; NULL = default
+ *     stream) and nothing synchronises except zen_ctx_create and zen_status_fetch.  Counts stay on
+ *     the device: offsets[n_parts] is a worker's nnz, *count a server's number of unique rows.
+ *   - Errors are integer statuses; nothing is thrown across the ABI.  Argument errors are detected
+ *     on the host before anything is launched.  Overflow of a caller-given capacity is detected on
+ *     the device: nothing is written past a capacity, a flag is raised in the workspace, and
+ *     zen_status_fetch turns it into ZEN_ERR_CAPACITY together with the number of rows needed.
+ *   - Rows are indexed from 0 with 32-bit ids; 0xFFFFFFFF is reserved, so n_rows <= 2^32 - 2.
+ *     A row is non-zero iff any of its row_dim fp32 words has (bits & 0x7fffffff) != 0.
+ *   - h0(idx) = MurmurHash3_x86_32(idx as 4 little-endian bytes, hash_seed) mod n_parts -- the same
+ *     on every worker, so an index always reaches the same server [Technique #3].
+ *   - Inside every partition indices ascend; values follow the same order, whole rows, bit-exact.
+ */
+#ifndef ZEN_H
+#define ZEN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZEN_MAX_PARTS 1024u /* n_parts limit (per-block LDS histograms) */
+#define ZEN_MAX_BATCH 64u   /* workers / servers / incoming parts per launch group */
+
+typedef enum {
+    ZEN_OK = 0,
+    ZEN_ERR_INVALID = 1,  /* bad argument (null, misaligned, out of range, mismatch with the context) */
+    ZEN_ERR_CAPACITY = 2, /* an output or table capacity was too small (see zen_status_fetch) */
+    ZEN_ERR_NOMEM = 3,    /* device allocation failed / workspace too small */
+    ZEN_ERR_DEVICE = 4    /* a HIP call failed */
+} zen_status;
+
+typedef enum {
+    ZEN_INDEX_COO = 0,   /* indices as a list of row ids (the paper's Push format) */
+    ZEN_INDEX_BITMAP = 1 /* indices as a hash bitmap over each partition's domain (Algorithm 2) */
+} zen_index_format;
+
+typedef struct zen_ctx zen_ctx; /* immutable function of (n_rows, row_dim, n_parts, hash_seed, fmt) */
+
+/* One encoded gradient = n_parts partitions stored partition-major. */
+typedef struct {
+    uint32_t *offsets;   /* [n_parts+1] rows; offsets[0]=0, offsets[p+1]-offsets[p] = size of partition p */
+    uint32_t *indices;   /* [cap_rows] ascending inside each partition; may be NULL in BITMAP mode */
+    float    *values;    /* [cap_rows][row_dim], same order as indices */
+    uint32_t *bitmap;    /* BITMAP mode: [zen_bitmap_words()] words, partition p at zen_bitmap_offsets()[p],
+                            bit j (LSB-first) = 1 iff the j-th smallest row of partition p's domain is
+                            non-zero; padding bits 0.  NULL in COO mode. */
+    uint64_t  cap_rows;  /* capacity of indices and values, in rows */
+} zen_encoded;
+
+/* One incoming partition at a server (zen_aggregate). */
+typedef struct {
+    const uint32_t *indices; /* [*count] row ids, any order, duplicates allowed (they are summed);
+                                NULL if `bitmap` is given */
+    const uint32_t *bitmap;  /* hash bitmap of partition part_id (first word of that partition), or NULL */
+    const float    *values;  /* [*count][row_dim]; with a bitmap the k-th row belongs to the k-th set bit */
+    const uint32_t *count;   /* device scalar: number of rows */
+} zen_part;
+
+/* Aggregated partition of one server. */
+typedef struct {
+    uint32_t *indices;  /* [cap_rows] ascending union of the incoming indices */
+    float    *values;   /* [cap_rows][row_dim] fp32 sums */
+    uint32_t *count;    /* device scalar: number of unique rows U */
+    uint64_t  cap_rows;
+} zen_aggregated;
+
+/* Status block fetched from a workspace. */
+typedef struct {
+    uint32_t flags;        /* bit 0: output capacity overflow, bit 1: table/bound overflow */
+    uint32_t reserved;
+    uint64_t needed_rows;  /* largest number of rows any overflowing output / table needed */
+} zen_status_info;
+
+/*
+ * Create a context.  Synchronous.  For ZEN_INDEX_BITMAP it builds, on the device, the sorted hash
+ * domains II_p = { r : h0(r) = p } ("computed and sorted offline", section "Hash Bitmap") and their
+ * per-tile rank bases: 4*n_rows bytes + small tables.  Limits: 1 <= n_rows <= 2^32-2,
+ * row_dim >= 1, 1 <= n_parts <= ZEN_MAX_PARTS.
+ */
+zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts,
+                          uint32_t hash_seed, zen_index_format fmt);
+zen_status zen_ctx_destroy(zen_ctx *ctx);
+
+/* Hash-bitmap layout (host outputs).  total words = sum_p ceil(|II_p|/32) <= n_rows/32 + n_parts
+ * (appendix "Proof of The Property of Hash Bitmap").  host_word_offsets has n_parts+1 entries and
+ * host_domain_sizes n_parts entries; either may be NULL.  ZEN_ERR_INVALID for a COO context. */
+zen_status zen_bitmap_layout(const zen_ctx *ctx, uint64_t *host_total_words, uint64_t *host_word_offsets,
+                             uint64_t *host_domain_sizes);
+
+/* Workspace sizes in bytes.  `batch` = number of workers (encode) or servers (aggregate) handled by
+ * one call; max_in_rows = upper bound on the total rows entering ONE server (sum over its parts). */
+zen_status zen_encode_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uint64_t *host_bytes);
+zen_status zen_aggregate_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_rows,
+                                         uint64_t *host_bytes);
+
+/*
+ * Encode one worker's gradient (Algorithm 1's result).  grad: [n_rows][row_dim] fp32 row-major,
+ * 16-byte aligned.  n_parts and hash_seed must equal the context's.  Fills out->offsets, and
+ * out->indices + out->values (COO) or out->bitmap + out->values (BITMAP; indices also written if
+ * out->indices != NULL).  If nnz > out->cap_rows nothing is written past the capacity, offsets are
+ * still complete, and the capacity flag is raised with needed_rows = nnz.
+ */
+zen_status zen_encode(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_t hash_seed,
+                      const zen_encoded *host_out, void *workspace, uint64_t workspace_bytes,
+                      void *hip_stream);
+
+/* The same for n_workers gradients per launch sequence.  host_grads / host_outs: host arrays. */
+zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                            const zen_encoded *host_outs, void *workspace, uint64_t workspace_bytes,
+                            void *hip_stream);
+
+/*
+ * Ascending list of the non-zero rows of grad (Algorithm 1's input I) -- detection and compaction
+ * only.  indices: [cap_rows]; count: device scalar.
+ */
+zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint64_t cap_rows,
+                       uint32_t *count, void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * Aggregate n_in incoming parts at server part_id: out_indices = ascending union of the parts'
+ * indices (kept even if a sum cancels to 0), out_values = fp32 sums over every occurrence (fp32
+ * atomic adds: the summation order is not fixed, results agree with an fp64 sum to ~1e-7 relative
+ * to sum|x|).  max_in_rows bounds sum of *count over the parts; it sizes the open-addressing table
+ * (power of two >= 2*max_in_rows).  A larger actual total raises the table flag and leaves
+ * *out_count = 0.  U > out_cap_rows raises the capacity flag, writes the first out_cap_rows rows
+ * and sets *out_count = U.
+ */
+zen_status zen_aggregate(zen_ctx *ctx, const zen_part *host_parts, uint32_t n_in, uint32_t part_id,
+                         uint32_t *out_indices, float *out_values, uint64_t out_cap_rows,
+                         uint32_t *out_count, uint64_t max_in_rows, void *workspace,
+                         uint64_t workspace_bytes, void *hip_stream);
+
+/* All n_parts servers in one launch sequence: server j merges partition j of every worker's
+ * encoded gradient.  host_encs: n_workers entries (as filled by zen_encode*); host_outs: n_parts
+ * entries. */
+zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint32_t n_workers,
+                               const zen_aggregated *host_outs, uint64_t max_in_rows, void *workspace,
+                               uint64_t workspace_bytes, void *hip_stream);
+
+/* Synchronous: waits for the stream, reads the status block of a workspace last used by an encode
+ * or aggregate call, returns ZEN_OK / ZEN_ERR_CAPACITY and fills *host_info (may be NULL). */
+zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream,
+                            zen_status_info *host_info);
+
+/* h0's underlying 32-bit hash for `count` indices: out[i] = MurmurHash3_x86_32(idx[i], seed)
+ * (section "Implementation").  Exposed so the hash can be checked on its own. */
+zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out,
+                         void *hip_stream);
+
+const char *zen_status_str(zen_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZEN_H */

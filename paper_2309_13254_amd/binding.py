@@ -1,0 +1,266 @@
+"""ctypes binding of include/zen.h: argument marshalling only.
+
+The functions carry the C names.  Tensors are torch CUDA(ROCm) tensors used purely as device
+buffers; the HIP stream is torch's current stream unless one is given.  There is no CPU fallback:
+loading fails loudly if the HIP library has not been built (`python -m paper_2309_13254_amd.build`).
+"""
+import ctypes as C
+import os
+
+import torch
+
+__all__ = [
+    "ZEN_OK", "ZEN_ERR_INVALID", "ZEN_ERR_CAPACITY", "ZEN_ERR_NOMEM", "ZEN_ERR_DEVICE",
+    "ZEN_INDEX_COO", "ZEN_INDEX_BITMAP", "ZEN_MAX_BATCH", "ZEN_MAX_PARTS",
+    "ZenError", "ZenContext", "Encoded", "Aggregated", "library_path", "load_library",
+    "zen_ctx_create", "zen_ctx_destroy", "zen_bitmap_layout", "zen_encode_workspace_bytes",
+    "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
+    "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
+    "alloc_encoded", "alloc_aggregated", "alloc_workspace",
+]
+
+ZEN_OK, ZEN_ERR_INVALID, ZEN_ERR_CAPACITY, ZEN_ERR_NOMEM, ZEN_ERR_DEVICE = 0, 1, 2, 3, 4
+ZEN_INDEX_COO, ZEN_INDEX_BITMAP = 0, 1
+ZEN_MAX_BATCH, ZEN_MAX_PARTS = 64, 1024
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libzen_hip.so")
+_lib = None
+
+
+class ZenError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, zen_status_str(status), status))
+
+
+class _Encoded(C.Structure):
+    _fields_ = [("offsets", C.c_void_p), ("indices", C.c_void_p), ("values", C.c_void_p),
+                ("bitmap", C.c_void_p), ("cap_rows", C.c_uint64)]
+
+
+class _Part(C.Structure):
+    _fields_ = [("indices", C.c_void_p), ("bitmap", C.c_void_p), ("values", C.c_void_p), ("count", C.c_void_p)]
+
+
+class _Aggregated(C.Structure):
+    _fields_ = [("indices", C.c_void_p), ("values", C.c_void_p), ("count", C.c_void_p), ("cap_rows", C.c_uint64)]
+
+
+class _StatusInfo(C.Structure):
+    _fields_ = [("flags", C.c_uint32), ("reserved", C.c_uint32), ("needed_rows", C.c_uint64)]
+
+
+def library_path():
+    return _SO
+
+
+def load_library():
+    """Load the C-ABI library; raises if it has not been built (no fallback of any kind)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_SO):
+        raise ImportError("HIP library %s is missing: run `python -m paper_2309_13254_amd.build`" % _SO)
+    L = C.CDLL(_SO)
+    vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
+    sig = {
+        "zen_ctx_create": [C.POINTER(vp), u64, u32, u32, u32, C.c_int],
+        "zen_ctx_destroy": [vp],
+        "zen_bitmap_layout": [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)],
+        "zen_encode_workspace_bytes": [vp, u32, C.POINTER(u64)],
+        "zen_aggregate_workspace_bytes": [vp, u32, u64, C.POINTER(u64)],
+        "zen_encode": [vp, vp, u32, u32, C.POINTER(_Encoded), vp, u64, vp],
+        "zen_encode_batch": [vp, C.POINTER(vp), u32, C.POINTER(_Encoded), vp, u64, vp],
+        "zen_nonzero": [vp, vp, vp, u64, vp, vp, u64, vp],
+        "zen_aggregate": [vp, C.POINTER(_Part), u32, u32, vp, vp, u64, vp, u64, vp, u64, vp],
+        "zen_aggregate_batch": [vp, C.POINTER(_Encoded), u32, C.POINTER(_Aggregated), u64, vp, u64, vp],
+        "zen_status_fetch": [vp, vp, vp, C.POINTER(_StatusInfo)],
+        "zen_hash_many": [vp, u64, u32, vp, vp],
+    }
+    for name, args in sig.items():
+        f = getattr(L, name)
+        f.argtypes = args
+        f.restype = C.c_int
+    L.zen_status_str.argtypes = [C.c_int]
+    L.zen_status_str.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def zen_status_str(status):
+    try:
+        return load_library().zen_status_str(int(status)).decode()
+    except ImportError:
+        return "status %d" % status
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _check(status, where, allow=()):
+    if status != ZEN_OK and status not in allow:
+        raise ZenError(status, where)
+    return status
+
+
+class ZenContext:
+    """Owns a zen_ctx*: immutable function of (n_rows, row_dim, n_parts, hash_seed, fmt)."""
+
+    def __init__(self, n_rows, row_dim, n_parts, hash_seed, fmt=ZEN_INDEX_COO):
+        self.n_rows, self.row_dim, self.n_parts = int(n_rows), int(row_dim), int(n_parts)
+        self.hash_seed, self.fmt = int(hash_seed) & 0xFFFFFFFF, int(fmt)
+        h = C.c_void_p()
+        _check(load_library().zen_ctx_create(C.byref(h), self.n_rows, self.row_dim, self.n_parts,
+                                             self.hash_seed, self.fmt), "zen_ctx_create")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().zen_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def zen_ctx_create(n_rows, row_dim, n_parts, hash_seed, fmt=ZEN_INDEX_COO):
+    return ZenContext(n_rows, row_dim, n_parts, hash_seed, fmt)
+
+
+def zen_ctx_destroy(ctx):
+    ctx.close()
+
+
+def zen_bitmap_layout(ctx):
+    """-> (total_words, word_offsets[n+1], domain_sizes[n]) as Python ints / lists."""
+    n = ctx.n_parts
+    total = C.c_uint64()
+    woff = (C.c_uint64 * (n + 1))()
+    dsz = (C.c_uint64 * n)()
+    _check(load_library().zen_bitmap_layout(ctx.handle, C.byref(total), woff, dsz), "zen_bitmap_layout")
+    return int(total.value), list(woff), list(dsz)
+
+
+def zen_encode_workspace_bytes(ctx, batch):
+    b = C.c_uint64()
+    _check(load_library().zen_encode_workspace_bytes(ctx.handle, int(batch), C.byref(b)), "zen_encode_workspace_bytes")
+    return int(b.value)
+
+
+def zen_aggregate_workspace_bytes(ctx, batch, max_in_rows):
+    b = C.c_uint64()
+    _check(load_library().zen_aggregate_workspace_bytes(ctx.handle, int(batch), int(max_in_rows), C.byref(b)),
+           "zen_aggregate_workspace_bytes")
+    return int(b.value)
+
+
+class Encoded:
+    """Device buffers of one encoded gradient (a zen_encoded)."""
+
+    def __init__(self, offsets, indices, values, bitmap, cap_rows):
+        self.offsets, self.indices, self.values, self.bitmap, self.cap_rows = offsets, indices, values, bitmap, int(cap_rows)
+
+    def struct(self):
+        return _Encoded(_ptr(self.offsets), _ptr(self.indices), _ptr(self.values), _ptr(self.bitmap), self.cap_rows)
+
+
+class Aggregated:
+    """Device buffers of one server's aggregated partition (a zen_aggregated)."""
+
+    def __init__(self, indices, values, count, cap_rows):
+        self.indices, self.values, self.count, self.cap_rows = indices, values, count, int(cap_rows)
+
+    def struct(self):
+        return _Aggregated(_ptr(self.indices), _ptr(self.values), _ptr(self.count), self.cap_rows)
+
+
+def alloc_encoded(ctx, cap_rows, device="cuda", with_indices=True):
+    cap = max(int(cap_rows), 1)
+    offsets = torch.empty(ctx.n_parts + 1, dtype=torch.int32, device=device)
+    indices = torch.empty(cap, dtype=torch.int32, device=device) if (with_indices or ctx.fmt == ZEN_INDEX_COO) else None
+    values = torch.empty((cap, ctx.row_dim), dtype=torch.float32, device=device)
+    bitmap = None
+    if ctx.fmt == ZEN_INDEX_BITMAP:
+        total, _, _ = zen_bitmap_layout(ctx)
+        bitmap = torch.empty(max(total, 1), dtype=torch.int32, device=device)
+    return Encoded(offsets, indices, values, bitmap, int(cap_rows))
+
+
+def alloc_aggregated(ctx, cap_rows, device="cuda"):
+    cap = max(int(cap_rows), 1)
+    return Aggregated(torch.empty(cap, dtype=torch.int32, device=device),
+                      torch.empty((cap, ctx.row_dim), dtype=torch.float32, device=device),
+                      torch.zeros(1, dtype=torch.int32, device=device), int(cap_rows))
+
+
+def alloc_workspace(nbytes, device="cuda"):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def zen_encode(ctx, grad, n_parts, hash_seed, out, workspace, stream=None):
+    st = out.struct()
+    return _check(load_library().zen_encode(ctx.handle, grad.data_ptr(), int(n_parts), int(hash_seed) & 0xFFFFFFFF,
+                                            C.byref(st), workspace.data_ptr(), workspace.numel(), _stream(stream)),
+                  "zen_encode")
+
+
+def zen_encode_batch(ctx, grads, outs, workspace, stream=None):
+    n = len(grads)
+    assert len(outs) == n
+    gp = (C.c_void_p * n)(*[g.data_ptr() for g in grads])
+    es = (_Encoded * n)(*[o.struct() for o in outs])
+    return _check(load_library().zen_encode_batch(ctx.handle, gp, n, es, workspace.data_ptr(), workspace.numel(),
+                                                  _stream(stream)), "zen_encode_batch")
+
+
+def zen_nonzero(ctx, grad, indices, count, workspace, stream=None):
+    return _check(load_library().zen_nonzero(ctx.handle, grad.data_ptr(), indices.data_ptr(), indices.numel(),
+                                             count.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                             _stream(stream)), "zen_nonzero")
+
+
+def zen_aggregate(ctx, parts, part_id, out, max_in_rows, workspace, stream=None):
+    """parts: list of (indices|None, bitmap|None, values, count) device tensors."""
+    n = len(parts)
+    ps = (_Part * max(n, 1))(*[_Part(_ptr(p[0]), _ptr(p[1]), _ptr(p[2]), _ptr(p[3])) for p in parts])
+    return _check(load_library().zen_aggregate(ctx.handle, ps, n, int(part_id), out.indices.data_ptr(),
+                                               out.values.data_ptr(), out.cap_rows, out.count.data_ptr(),
+                                               int(max_in_rows), workspace.data_ptr(), workspace.numel(),
+                                               _stream(stream)), "zen_aggregate")
+
+
+def zen_aggregate_batch(ctx, encs, outs, max_in_rows, workspace, stream=None):
+    n = len(encs)
+    assert len(outs) == ctx.n_parts
+    es = (_Encoded * n)(*[e.struct() for e in encs])
+    os_ = (_Aggregated * len(outs))(*[o.struct() for o in outs])
+    return _check(load_library().zen_aggregate_batch(ctx.handle, es, n, os_, int(max_in_rows), workspace.data_ptr(),
+                                                     workspace.numel(), _stream(stream)), "zen_aggregate_batch")
+
+
+def zen_status_fetch(ctx, workspace, stream=None):
+    """Synchronous. -> (status, flags, needed_rows)"""
+    info = _StatusInfo()
+    st = load_library().zen_status_fetch(ctx.handle, workspace.data_ptr(), _stream(stream), C.byref(info))
+    return st, int(info.flags), int(info.needed_rows)
+
+
+def zen_hash_many(idx, seed, out=None, stream=None):
+    if out is None:
+        out = torch.empty_like(idx)
+    _check(load_library().zen_hash_many(idx.data_ptr(), idx.numel(), int(seed) & 0xFFFFFFFF, out.data_ptr(),
+                                        _stream(stream)), "zen_hash_many")
+    return out

@@ -1,0 +1,509 @@
+// Aggregation kernels for gfx950: open-addressing key table (atomicCAS, linear probing), compaction
+// and sort of the unique keys, and fp32 atomic accumulation of the incoming rows.
+//
+// One launch covers every server of a batch: blockIdx.z = server, blockIdx.y = incoming part.
+//   clear  -> insert (keys only) -> sort unique keys (LDS bitonic, or segmented LSB radix sort)
+//          -> write each key's output rank into its slot -> zero the output rows
+//          -> accumulate: every incoming row looks its rank up and atomically adds into the output.
+#include "zen_device.h"
+#include "zen_internal.h"
+
+namespace zen {
+
+static constexpr int AGG_THREADS = 256;
+static constexpr int SORT_SMALL_THREADS = 1024;
+static constexpr uint32_t SMALL_MAX_KEYS = 8192;   // unique keys one block sorts in LDS (32 KB)
+static constexpr int RS_ITEMS = 8;                 // radix sort: keys per thread per block
+static constexpr int RS_BLOCK_KEYS = AGG_THREADS * RS_ITEMS;
+
+enum : uint32_t { CNT_UNIQUE = 0, CNT_TOTAL_IN = 1, CNT_SKIP = 2 };
+
+struct PartRange { const uint32_t *idx; uint32_t begin, count; };
+
+__device__ __forceinline__ PartRange part_range(const PartIdx &src, uint32_t w, uint32_t server)
+{
+    PartRange r;
+    if (src.single) {
+        r.begin = 0;
+        r.count = src.bounds[w][0];
+    } else {
+        r.begin = src.bounds[w][src.server0 + server];
+        r.count = src.bounds[w][src.server0 + server + 1] - r.begin;
+    }
+    r.idx = src.indices[w];
+    return r;
+}
+
+__device__ __forceinline__ uint32_t probe_find(const uint32_t *__restrict__ keys, uint32_t cap_mask,
+                                               uint32_t key, uint32_t seed)
+{
+    uint32_t slot = table_hash(key, seed) & cap_mask;
+    for (uint32_t i = 0; i <= cap_mask; ++i) {
+        const uint32_t k = keys[slot];
+        if (k == key) return slot;
+        if (k == ZEN_EMPTY_KEY) break;
+        slot = (slot + 1) & cap_mask;
+    }
+    return 0xFFFFFFFFu;
+}
+
+// A1: keys = EMPTY for every server, counters and status zeroed.
+__global__ void agg_clear_kernel(uint32_t *keys, uint64_t n_keys, uint32_t *counters, uint32_t n_counters,
+                                 zen_status_info *status)
+{
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, nt = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = tid; i < n_keys; i += nt) keys[i] = ZEN_EMPTY_KEY;
+    for (uint64_t i = tid; i < n_counters; i += nt) counters[i] = 0;
+    if (tid == 0) { status->flags = 0; status->reserved = 0; status->needed_rows = 0; }
+}
+
+// A2 (keys): claim a slot for every distinct incoming index.
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base, uint64_t table_cap,
+                  uint32_t *counters_base, uint64_t max_in_rows, zen_status_info *status)
+{
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t server = blockIdx.z, w = blockIdx.y;
+    uint32_t *keys = keys_base + (uint64_t)server * table_cap;
+    uint32_t *counters = counters_base + server * 16;
+    const uint32_t cap_mask = (uint32_t)(table_cap - 1);
+
+    // bound check: the table holds at most max_in_rows keys at load factor <= 1/2
+    uint32_t mine = 0;
+    if (threadIdx.x < n_in) mine = part_range(src, threadIdx.x, server).count;
+    uint32_t total_in;
+    block_exclusive_scan(mine, s_tmp, &total_in);
+    if ((uint64_t)total_in > max_in_rows) {
+        if (blockIdx.x == 0 && w == 0 && threadIdx.x == 0) {
+            atomicOr(&status->flags, 2u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)total_in);
+            counters[CNT_SKIP] = 1;
+        }
+        return;
+    }
+    if (blockIdx.x == 0 && w == 0 && threadIdx.x == 0) counters[CNT_TOTAL_IN] = total_in;
+
+    const PartRange r = part_range(src, w, server);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < r.count; i += gridDim.x * blockDim.x) {
+        const uint32_t key = r.idx[r.begin + i];
+        if (key == ZEN_EMPTY_KEY) { atomicOr(&status->flags, 4u); continue; }
+        uint32_t slot = table_hash(key, seed) & cap_mask;
+        for (uint32_t t = 0; t <= cap_mask; ++t) {
+            const uint32_t prev = atomicCAS(&keys[slot], ZEN_EMPTY_KEY, key);
+            if (prev == ZEN_EMPTY_KEY || prev == key) break;
+            slot = (slot + 1) & cap_mask;
+        }
+    }
+}
+
+// A3, small tables: one block per server.  Compacts the occupied slots into LDS, sorts them with a
+// bitonic network, writes out_indices / *count, and stores every key's rank into its slot.
+__global__ void __launch_bounds__(SORT_SMALL_THREADS)
+agg_sort_small_kernel(uint32_t seed, const uint32_t *keys_base, uint32_t *rank_base, uint64_t table_cap,
+                      uint32_t *counters_base, AggOut outs, zen_status_info *status)
+{
+    __shared__ uint32_t s_keys[SMALL_MAX_KEYS];
+    __shared__ uint32_t s_n;
+    const uint32_t server = blockIdx.x;
+    const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
+    uint32_t *rank = rank_base + (uint64_t)server * table_cap;
+    uint32_t *counters = counters_base + server * 16;
+    const uint32_t cap_mask = (uint32_t)(table_cap - 1);
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    if (counters[CNT_SKIP]) {
+        if (threadIdx.x == 0) *outs.count[server] = 0;
+        return;
+    }
+    for (uint32_t i = threadIdx.x; i < table_cap; i += blockDim.x) {
+        const uint32_t k = keys[i];
+        if (k != ZEN_EMPTY_KEY) {
+            const uint32_t at = atomicAdd(&s_n, 1u);
+            if (at < SMALL_MAX_KEYS) s_keys[at] = k;   // cannot overflow: cap <= 2*SMALL_MAX_KEYS at load <= 1/2
+        }
+    }
+    __syncthreads();
+    const uint32_t U = min(s_n, SMALL_MAX_KEYS);
+    uint32_t P = 1;
+    while (P < U) P <<= 1;
+    for (uint32_t i = U + threadIdx.x; i < P; i += blockDim.x) s_keys[i] = ZEN_EMPTY_KEY;   // pad high
+    __syncthreads();
+    for (uint32_t k = 2; k <= P; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
+                const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));   // index with bit j clear
+                const uint32_t hi = lo | j;
+                const bool up = (lo & k) == 0;
+                const uint32_t a = s_keys[lo], b = s_keys[hi];
+                if ((a > b) == up) { s_keys[lo] = b; s_keys[hi] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    const uint64_t cap_rows = outs.cap_rows[server];
+    uint32_t *out_idx = outs.indices[server];
+    for (uint32_t u = threadIdx.x; u < U; u += blockDim.x) {
+        const uint32_t key = s_keys[u];
+        if (u < cap_rows) out_idx[u] = key;
+        const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+        if (slot != 0xFFFFFFFFu) rank[slot] = u;
+    }
+    if (threadIdx.x == 0) {
+        *outs.count[server] = U;
+        counters[CNT_UNIQUE] = U;
+        if ((uint64_t)U > cap_rows) {
+            atomicOr(&status->flags, 1u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)U);
+        }
+    }
+}
+
+// A3, large tables, step 1: compact the occupied slots (any order) into uniq[server][0..U).
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_compact_kernel(const uint32_t *keys_base, uint64_t table_cap, uint32_t *uniq_base, uint64_t uniq_stride,
+                   uint32_t *counters_base)
+{
+    const uint32_t server = blockIdx.y;
+    const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
+    uint32_t *uniq = uniq_base + (uint64_t)server * uniq_stride;
+    uint32_t *counters = counters_base + server * 16;
+    if (counters[CNT_SKIP]) return;
+    // table_cap is a multiple of the block size: every wave runs the same number of iterations
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < table_cap;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t k = keys[i];
+        const bool occ = k != ZEN_EMPTY_KEY;
+        const uint64_t m = ballot(occ);
+        uint32_t base = 0;
+        if (lane_id() == 0 && m) base = atomicAdd(&counters[CNT_UNIQUE], (uint32_t)__popcll(m));
+        base = __shfl(base, 0, ZEN_WAVE);
+        if (occ) uniq[base + mbcnt(m)] = k;
+    }
+}
+
+// Segmented LSB radix sort, one 8-bit digit per pass.  Segment = server, length = counters[UNIQUE].
+__global__ void __launch_bounds__(AGG_THREADS)
+rs_hist_kernel(const uint32_t *in_base, uint64_t uniq_stride, const uint32_t *counters_base, uint32_t shift,
+               uint32_t *hist_base, uint64_t hist_stride)
+{
+    __shared__ uint32_t s_h[256];
+    const uint32_t server = blockIdx.y;
+    const uint32_t U = counters_base[server * 16 + CNT_UNIQUE];
+    const uint32_t n_blocks = (U + RS_BLOCK_KEYS - 1) / RS_BLOCK_KEYS;
+    uint32_t *hist = hist_base + (uint64_t)server * hist_stride + (uint64_t)blockIdx.x * 256;
+    if (blockIdx.x >= n_blocks) return;   // the scan only reads blocks < n_blocks
+    const uint32_t *in = in_base + (uint64_t)server * uniq_stride;
+    s_h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t k0 = blockIdx.x * RS_BLOCK_KEYS;
+#pragma unroll
+    for (int it = 0; it < RS_ITEMS; ++it) {
+        const uint32_t i = k0 + it * AGG_THREADS + threadIdx.x;
+        if (i < U) atomicAdd(&s_h[(in[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[threadIdx.x] = s_h[threadIdx.x];
+}
+
+// hist[block][digit] -> output position of the first key of (block, digit); one block per server.
+__global__ void __launch_bounds__(1024)
+rs_scan_kernel(const uint32_t *counters_base, uint32_t *hist_base, uint64_t hist_stride)
+{
+    __shared__ uint32_t s_part[1024];
+    __shared__ uint32_t s_off[257];
+    const uint32_t server = blockIdx.x;
+    const uint32_t U = counters_base[server * 16 + CNT_UNIQUE];
+    const uint32_t n_blocks = (U + RS_BLOCK_KEYS - 1) / RS_BLOCK_KEYS;
+    uint32_t *hist = hist_base + (uint64_t)server * hist_stride;
+    const uint32_t d = threadIdx.x & 255u, grp = threadIdx.x >> 8;   // 4 groups x 256 digits
+    const uint32_t per = (n_blocks + 3) / 4;
+    const uint32_t b0 = min(grp * per, n_blocks), b1 = min(b0 + per, n_blocks);
+    uint32_t sum = 0;
+    for (uint32_t b = b0; b < b1; ++b) sum += hist[(uint64_t)b * 256 + d];
+    s_part[grp * 256 + d] = sum;
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        uint32_t run = 0;
+        for (uint32_t gI = 0; gI < 4; ++gI) {
+            const uint32_t t = s_part[gI * 256 + threadIdx.x];
+            s_part[gI * 256 + threadIdx.x] = run;
+            run += t;
+        }
+        s_off[threadIdx.x + 1] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        s_off[0] = 0;
+        uint32_t run = 0;
+        for (uint32_t q = 0; q < 256; ++q) { run += s_off[q + 1]; s_off[q + 1] = run; }
+    }
+    __syncthreads();
+    uint32_t run = s_off[d] + s_part[grp * 256 + d];
+    for (uint32_t b = b0; b < b1; ++b) {
+        const uint64_t a = (uint64_t)b * 256 + d;
+        const uint32_t h = hist[a];
+        hist[a] = run;
+        run += h;
+    }
+}
+
+__global__ void __launch_bounds__(AGG_THREADS)
+rs_scatter_kernel(const uint32_t *in_base, uint32_t *out_base, uint64_t uniq_stride,
+                  const uint32_t *counters_base, uint32_t shift, const uint32_t *hist_base, uint64_t hist_stride)
+{
+    __shared__ uint32_t s_run[256];
+    __shared__ uint32_t s_cnt[4 * 256];
+    const uint32_t server = blockIdx.y;
+    const uint32_t U = counters_base[server * 16 + CNT_UNIQUE];
+    const uint32_t n_blocks = (U + RS_BLOCK_KEYS - 1) / RS_BLOCK_KEYS;
+    if (blockIdx.x >= n_blocks) return;
+    const uint32_t *in = in_base + (uint64_t)server * uniq_stride;
+    uint32_t *out = out_base + (uint64_t)server * uniq_stride;
+    const uint32_t *hist = hist_base + (uint64_t)server * hist_stride + (uint64_t)blockIdx.x * 256;
+    s_run[threadIdx.x] = hist[threadIdx.x];
+    for (uint32_t i = threadIdx.x; i < 4 * 256; i += blockDim.x) s_cnt[i] = 0;
+    __syncthreads();
+    const uint32_t k0 = blockIdx.x * RS_BLOCK_KEYS;
+    for (int it = 0; it < RS_ITEMS; ++it) {
+        const uint32_t i = k0 + it * AGG_THREADS + threadIdx.x;
+        const bool valid = i < U;
+        const uint32_t key = valid ? in[i] : 0u;
+        const uint32_t pos = block_stable_rank(valid, (key >> shift) & 255u, 8, 256, s_run, s_cnt);
+        if (valid) out[pos] = key;
+    }
+}
+
+// A3, large tables, last step: sorted unique keys -> out_indices, *count, and each key's rank.
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_stride, const uint32_t *keys_base,
+                    uint32_t *rank_base, uint64_t table_cap, const uint32_t *counters_base, AggOut outs,
+                    zen_status_info *status)
+{
+    const uint32_t server = blockIdx.y;
+    const uint32_t *counters = counters_base + server * 16;
+    const uint32_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
+    const uint32_t *sorted = sorted_base + (uint64_t)server * uniq_stride;
+    const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
+    uint32_t *rank = rank_base + (uint64_t)server * table_cap;
+    const uint32_t cap_mask = (uint32_t)(table_cap - 1);
+    const uint64_t cap_rows = outs.cap_rows[server];
+    uint32_t *out_idx = outs.indices[server];
+    for (uint32_t u = blockIdx.x * blockDim.x + threadIdx.x; u < U; u += gridDim.x * blockDim.x) {
+        const uint32_t key = sorted[u];
+        if (u < cap_rows) out_idx[u] = key;
+        const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+        if (slot != 0xFFFFFFFFu) rank[slot] = u;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *outs.count[server] = U;
+        if ((uint64_t)U > cap_rows) {
+            atomicOr(&status->flags, 1u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)U);
+        }
+    }
+}
+
+// Zero the output rows that will receive atomic adds.
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_zero_kernel(Arr64<float *> out_values, AggOut outs, uint32_t row_dim, const uint32_t *counters_base)
+{
+    const uint32_t server = blockIdx.y;
+    const uint32_t *counters = counters_base + server * 16;
+    const uint64_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
+    const uint64_t rows = U < outs.cap_rows[server] ? U : outs.cap_rows[server];
+    const uint64_t n = rows * row_dim;
+    float *out = out_values.v[server];
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, nt = (uint64_t)gridDim.x * blockDim.x;
+    if ((row_dim & 3u) == 0) {
+        f32x4 *o4 = (f32x4 *)out;
+        for (uint64_t i = tid; i < (n >> 2); i += nt) o4[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    } else {
+        for (uint64_t i = tid; i < n; i += nt) out[i] = 0.f;
+    }
+}
+
+__device__ __forceinline__ void add_f32(float *p, float v) { unsafeAtomicAdd(p, v); }
+
+// A2 (values): every incoming row finds its key's rank and adds itself into out_values[rank].
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_accum_kernel(PartIdx src, Arr64<const float *> src_values, uint32_t seed, uint32_t row_dim,
+                 const uint32_t *keys_base, const uint32_t *rank_base, uint64_t table_cap,
+                 const uint32_t *counters_base, Arr64<float *> out_values, AggOut outs)
+{
+    const uint32_t server = blockIdx.z, w = blockIdx.y;
+    const uint32_t *counters = counters_base + server * 16;
+    if (counters[CNT_SKIP]) return;
+    const uint32_t *__restrict__ keys = keys_base + (uint64_t)server * table_cap;
+    const uint32_t *__restrict__ rank = rank_base + (uint64_t)server * table_cap;
+    const uint32_t cap_mask = (uint32_t)(table_cap - 1);
+    const uint64_t cap_rows = outs.cap_rows[server];
+    float *__restrict__ out = out_values.v[server];
+    const PartRange r = part_range(src, w, server);
+    const float *__restrict__ vals = src_values.v[w] + (uint64_t)r.begin * row_dim;
+    const uint32_t D = row_dim;
+
+    if (D == 1) {
+        for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < r.count; i += gridDim.x * blockDim.x) {
+            const uint32_t key = r.idx[r.begin + i];
+            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+            if (slot == 0xFFFFFFFFu) continue;
+            const uint32_t u = rank[slot];
+            if (u < cap_rows) add_f32(out + u, vals[i]);
+        }
+    } else if ((D & 3u) == 0 && D >= 256) {
+        const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
+        for (uint32_t i = blockIdx.x * nw + (threadIdx.x >> 6); i < r.count; i += gridDim.x * nw) {
+            const uint32_t key = r.idx[r.begin + i];
+            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+            if (slot == 0xFFFFFFFFu) continue;
+            const uint32_t u = rank[slot];
+            if (u >= cap_rows) continue;
+            const f32x4 *s4 = (const f32x4 *)(vals + (uint64_t)i * D);
+            float *o = out + (uint64_t)u * D;
+            for (uint32_t v = lane; v < V; v += 64) {
+                const f32x4 x = s4[v];
+                add_f32(o + 4 * v + 0, x.x);
+                add_f32(o + 4 * v + 1, x.y);
+                add_f32(o + 4 * v + 2, x.z);
+                add_f32(o + 4 * v + 3, x.w);
+            }
+        }
+    } else {
+        // flat (row, element) space; consecutive threads share a row, so the probes coalesce
+        const uint64_t n_el = (uint64_t)r.count * D;
+        for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_el;
+             f += (uint64_t)gridDim.x * blockDim.x) {
+            const uint32_t i = (uint32_t)(f / D), c = (uint32_t)(f - (uint64_t)i * D);
+            const uint32_t key = r.idx[r.begin + i];
+            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+            if (slot == 0xFFFFFFFFu) continue;
+            const uint32_t u = rank[slot];
+            if (u < cap_rows) add_f32(out + (uint64_t)u * D + c, vals[f]);
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// layout + launcher
+// ----------------------------------------------------------------------------------------------
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows)
+{
+    AggLayout L{};
+    uint64_t cap = 1024;
+    while (cap < 2 * max_in_rows) cap <<= 1;
+    L.table_cap = cap;
+    L.small_path = cap <= 2 * (uint64_t)SMALL_MAX_KEYS ? 1u : 0u;
+    uint64_t off = 0;
+    L.status_off = off; off += 256;
+    L.counters_off = off; off += align_up((uint64_t)batch * 16 * 4, 256);
+    L.keys_off = off; off += align_up((uint64_t)batch * cap * 4, 256);
+    L.rank_off = off; off += align_up((uint64_t)batch * cap * 4, 256);
+    L.uniq_cap = align_up(max_in_rows > 0 ? max_in_rows : 1, 64);
+    L.sort_blocks = (L.uniq_cap + RS_BLOCK_KEYS - 1) / RS_BLOCK_KEYS;
+    if (!L.small_path) {
+        L.uniq_off = off; off += align_up((uint64_t)batch * 2 * L.uniq_cap * 4, 256);
+        L.sorthist_off = off; off += align_up((uint64_t)batch * L.sort_blocks * 256 * 4, 256);
+    }
+    L.decode_off = off;
+    L.decode_stride = 0;
+    (void)g;
+    L.total = off;
+    return L;
+}
+
+#define ZEN_LAUNCH_CHECK()                         \
+    do {                                           \
+        hipError_t e_ = hipGetLastError();         \
+        if (e_ != hipSuccess) return e_;           \
+    } while (0)
+
+hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx &src,
+                            const Arr64<const float *> &src_values, const Arr64<const uint32_t *> &src_bitmap,
+                            uint32_t n_in, uint32_t n_servers, uint32_t first_part_id, const AggOut &outs,
+                            const Arr64<float *> &out_values, uint64_t max_in_rows, char *ws,
+                            const AggLayout &L, hipStream_t s)
+{
+    (void)ctx; (void)src_bitmap; (void)first_part_id;
+    zen_status_info *status = (zen_status_info *)(ws + L.status_off);
+    uint32_t *counters = (uint32_t *)(ws + L.counters_off);
+    uint32_t *keys = (uint32_t *)(ws + L.keys_off);
+    uint32_t *rank = (uint32_t *)(ws + L.rank_off);
+    const uint64_t cap = L.table_cap;
+    const uint64_t n_keys = (uint64_t)n_servers * cap;
+
+    {
+        uint64_t blocks = (n_keys + 1023) / 1024;
+        if (blocks > 16384) blocks = 16384;
+        agg_clear_kernel<<<(uint32_t)blocks, 256, 0, s>>>(keys, n_keys, counters, n_servers * 16, status);
+        ZEN_LAUNCH_CHECK();
+    }
+    // rows per (part, server) are unknown on the host; size the x dimension for an even split of
+    // max_in_rows over the parts, grid-stride loops cover any skew
+    uint64_t per_part = (max_in_rows + n_in - 1) / (n_in ? n_in : 1);
+    uint32_t gx = (uint32_t)((per_part + AGG_THREADS - 1) / AGG_THREADS);
+    if (gx < 1) gx = 1;
+    if (gx > 4096) gx = 4096;
+    agg_insert_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, n_in, g.seed, keys, cap, counters,
+                                                                        max_in_rows, status);
+    ZEN_LAUNCH_CHECK();
+
+    if (L.small_path) {
+        agg_sort_small_kernel<<<n_servers, SORT_SMALL_THREADS, 0, s>>>(g.seed, keys, rank, cap, counters, outs,
+                                                                       status);
+        ZEN_LAUNCH_CHECK();
+    } else {
+        uint32_t *uniq = (uint32_t *)(ws + L.uniq_off);
+        uint32_t *hist = (uint32_t *)(ws + L.sorthist_off);
+        const uint64_t ustride = 2 * L.uniq_cap, hstride = L.sort_blocks * 256;
+        uint64_t cblocks = cap / AGG_THREADS;
+        if (cblocks > 2048) cblocks = 2048;
+        agg_compact_kernel<<<dim3((uint32_t)cblocks, n_servers), AGG_THREADS, 0, s>>>(keys, cap, uniq, ustride,
+                                                                                     counters);
+        ZEN_LAUNCH_CHECK();
+        uint32_t key_bits = 1;
+        while (key_bits < 32 && (1ull << key_bits) < g.n_rows) ++key_bits;
+        uint32_t *a = uniq, *b = uniq + L.uniq_cap;
+        for (uint32_t shift = 0; shift < key_bits; shift += 8) {
+            rs_hist_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(a, ustride, counters, shift,
+                                                                                          hist, hstride);
+            ZEN_LAUNCH_CHECK();
+            rs_scan_kernel<<<n_servers, 1024, 0, s>>>(counters, hist, hstride);
+            ZEN_LAUNCH_CHECK();
+            rs_scatter_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(
+                a, b, ustride, counters, shift, hist, hstride);
+            ZEN_LAUNCH_CHECK();
+            uint32_t *t = a; a = b; b = t;
+        }
+        uint64_t fblocks = (L.uniq_cap + AGG_THREADS - 1) / AGG_THREADS;
+        if (fblocks > 4096) fblocks = 4096;
+        agg_finalize_kernel<<<dim3((uint32_t)fblocks, n_servers), AGG_THREADS, 0, s>>>(
+            g.seed, a, ustride, keys, rank, cap, counters, outs, status);
+        ZEN_LAUNCH_CHECK();
+    }
+
+    {
+        // zero: rows <= min(max_in_rows, cap_rows) per server
+        uint64_t n_el = max_in_rows * (uint64_t)g.row_dim;
+        uint64_t zb = (n_el / 4 + AGG_THREADS - 1) / AGG_THREADS;
+        if (zb < 1) zb = 1;
+        if (zb > 2048) zb = 2048;
+        agg_zero_kernel<<<dim3((uint32_t)zb, n_servers), AGG_THREADS, 0, s>>>(out_values, outs, g.row_dim, counters);
+        ZEN_LAUNCH_CHECK();
+    }
+    {
+        uint64_t units;   // work units per part: rows (wave per row), rows (D==1), or elements
+        if (g.row_dim == 1) units = (per_part + AGG_THREADS - 1) / AGG_THREADS;
+        else if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) units = (per_part + 3) / 4;
+        else units = (per_part * g.row_dim + AGG_THREADS - 1) / AGG_THREADS;
+        if (units < 1) units = 1;
+        if (units > 8192) units = 8192;
+        agg_accum_kernel<<<dim3((uint32_t)units, n_in, n_servers), AGG_THREADS, 0, s>>>(
+            src, src_values, g.seed, g.row_dim, keys, rank, cap, counters, out_values, outs);
+        ZEN_LAUNCH_CHECK();
+    }
+    return hipSuccess;
+}
+
+} // namespace zen

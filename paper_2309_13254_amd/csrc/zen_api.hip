@@ -1,0 +1,347 @@
+// The C ABI (include/zen.h): argument checks, workspace layouts and launch sequences.
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+#include "zen_internal.h"
+
+namespace zen {
+
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+static bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
+
+// Tile geometry.  A tile is the unit of one detect / scatter block and of the per-partition
+// histogram; sized for ~128 KB of dense data so that every launch has far more blocks than CUs.
+static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts, uint32_t seed,
+                          bool bitmap)
+{
+    memset(&g, 0, sizeof(g));
+    g.n_rows = n_rows;
+    g.row_dim = row_dim;
+    g.n_parts = n_parts;
+    g.seed = seed;
+    g.pow2_mask = is_pow2(n_parts) ? n_parts - 1 : 0;
+    g.part_bits = 0;
+    while ((1u << g.part_bits) < n_parts) ++g.part_bits;
+    g.bitmap = bitmap ? 1u : 0u;
+    const uint64_t target_bytes = 128 * 1024;
+    if (row_dim == 1) {
+        g.mode = MODE_ELEM;
+        uint64_t t = 32768;                      // 128 KB
+        while (t > 2048 && n_rows / t < 1024) t >>= 1;   // small tensors: keep >= ~1024 tiles
+        g.tile_rows = (uint32_t)t;
+    } else if ((row_dim & 3u) == 0 && row_dim <= 128 && is_pow2(row_dim / 4)) {
+        g.mode = MODE_SUB;
+        uint64_t t = target_bytes / (4ull * row_dim);
+        while (t > 64 && n_rows / t < 1024) t >>= 1;
+        g.tile_rows = (uint32_t)align_up(t < 64 ? 64 : t, 64);
+    } else {
+        g.mode = MODE_ROW;
+        uint64_t t = target_bytes / (4ull * row_dim);
+        g.tile_rows = (uint32_t)align_up(t < 32 ? 32 : t, 32);
+        if (g.tile_rows > 2048) g.tile_rows = 2048;
+    }
+    g.tile_words = g.tile_rows / 32;
+    g.n_tiles = (uint32_t)((n_rows + g.tile_rows - 1) / g.tile_rows);
+}
+
+EncodeLayout encode_layout(const Geometry &g, uint32_t batch)
+{
+    EncodeLayout L{};
+    uint64_t off = 0;
+    L.status_off = off; off += 256;
+    L.mask_stride = align_up((uint64_t)g.n_tiles * g.tile_words * 4, 256);
+    L.mask_off = off; off += L.mask_stride * batch;
+    L.hist_stride = align_up((uint64_t)g.n_tiles * g.n_parts * 4, 256);
+    L.hist_off = off; off += L.hist_stride * batch;
+    L.total = off;
+    return L;
+}
+
+} // namespace zen
+
+using namespace zen;
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return ZEN_ERR_DEVICE;    \
+    } while (0)
+
+extern "C" {
+
+const char *zen_status_str(zen_status s)
+{
+    switch (s) {
+    case ZEN_OK: return "ok";
+    case ZEN_ERR_INVALID: return "invalid argument";
+    case ZEN_ERR_CAPACITY: return "capacity exceeded";
+    case ZEN_ERR_NOMEM: return "out of memory / workspace too small";
+    case ZEN_ERR_DEVICE: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts,
+                          uint32_t hash_seed, zen_index_format fmt)
+{
+    if (!out) return ZEN_ERR_INVALID;
+    *out = nullptr;
+    if (n_rows == 0 || n_rows > 0xFFFFFFFEull || row_dim == 0 || row_dim > (1u << 20) || n_parts == 0 ||
+        n_parts > ZEN_MAX_PARTS || (fmt != ZEN_INDEX_COO && fmt != ZEN_INDEX_BITMAP))
+        return ZEN_ERR_INVALID;
+    zen_ctx *ctx = new (std::nothrow) zen_ctx();
+    if (!ctx) return ZEN_ERR_NOMEM;
+    memset(ctx, 0, sizeof(*ctx));
+    make_geometry(ctx->geo, n_rows, row_dim, n_parts, hash_seed, fmt == ZEN_INDEX_BITMAP);
+    ctx->fmt = fmt;
+    if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return ZEN_ERR_DEVICE; }
+    if (fmt == ZEN_INDEX_BITMAP) {
+        delete ctx;
+        return ZEN_ERR_INVALID;   // hash-bitmap tables: not built yet
+    }
+    *out = ctx;
+    return ZEN_OK;
+}
+
+zen_status zen_ctx_destroy(zen_ctx *ctx)
+{
+    if (!ctx) return ZEN_OK;
+    if (ctx->d_domain) (void)hipFree(ctx->d_domain);
+    if (ctx->d_dom_offsets) (void)hipFree(ctx->d_dom_offsets);
+    if (ctx->d_dom_tile_base) (void)hipFree(ctx->d_dom_tile_base);
+    if (ctx->d_bm_word_off) (void)hipFree(ctx->d_bm_word_off);
+    free(ctx->h_bm_word_off);
+    free(ctx->h_dom_sizes);
+    delete ctx;
+    return ZEN_OK;
+}
+
+zen_status zen_bitmap_layout(const zen_ctx *ctx, uint64_t *host_total_words, uint64_t *host_word_offsets,
+                             uint64_t *host_domain_sizes)
+{
+    if (!ctx || ctx->fmt != ZEN_INDEX_BITMAP) return ZEN_ERR_INVALID;
+    if (host_total_words) *host_total_words = ctx->bm_total_words;
+    if (host_word_offsets) memcpy(host_word_offsets, ctx->h_bm_word_off, (ctx->geo.n_parts + 1) * sizeof(uint64_t));
+    if (host_domain_sizes) memcpy(host_domain_sizes, ctx->h_dom_sizes, ctx->geo.n_parts * sizeof(uint64_t));
+    return ZEN_OK;
+}
+
+zen_status zen_encode_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uint64_t *host_bytes)
+{
+    if (!ctx || !host_bytes || batch == 0) return ZEN_ERR_INVALID;
+    const uint32_t b = batch > ZEN_MAX_BATCH ? ZEN_MAX_BATCH : batch;
+    *host_bytes = encode_layout(ctx->geo, b).total;
+    return ZEN_OK;
+}
+
+zen_status zen_aggregate_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_rows,
+                                         uint64_t *host_bytes)
+{
+    if (!ctx || !host_bytes || batch == 0 || max_in_rows > 0x7FFFFFFFull) return ZEN_ERR_INVALID;
+    const uint32_t b = batch > ZEN_MAX_BATCH ? ZEN_MAX_BATCH : batch;
+    *host_bytes = aggregate_layout(ctx->geo, b, max_in_rows).total;
+    return ZEN_OK;
+}
+
+static zen_status check_encoded(const zen_ctx *ctx, const zen_encoded &e)
+{
+    if (!e.offsets || !e.values) return ZEN_ERR_INVALID;
+    if (ctx->fmt == ZEN_INDEX_COO && !e.indices) return ZEN_ERR_INVALID;
+    if (ctx->fmt == ZEN_INDEX_BITMAP && !e.bitmap) return ZEN_ERR_INVALID;
+    if (((uintptr_t)e.values & 15u) || ((uintptr_t)e.offsets & 3u) || ((uintptr_t)e.indices & 3u) ||
+        ((uintptr_t)e.bitmap & 3u))
+        return ZEN_ERR_INVALID;
+    if (e.cap_rows > 0xFFFFFFFEull) return ZEN_ERR_INVALID;
+    return ZEN_OK;
+}
+
+zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                            const zen_encoded *host_outs, void *workspace, uint64_t workspace_bytes,
+                            void *hip_stream)
+{
+    if (!ctx || !host_grads || !host_outs || n_workers == 0 || !workspace) return ZEN_ERR_INVALID;
+    if ((uintptr_t)workspace & 255u) return ZEN_ERR_INVALID;
+    const Geometry &g = ctx->geo;
+    for (uint32_t w = 0; w < n_workers; ++w) {
+        if (!host_grads[w] || ((uintptr_t)host_grads[w] & 15u)) return ZEN_ERR_INVALID;
+        zen_status st = check_encoded(ctx, host_outs[w]);
+        if (st != ZEN_OK) return st;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    const uint32_t group = n_workers < ZEN_MAX_BATCH ? n_workers : ZEN_MAX_BATCH;
+    const EncodeLayout L = encode_layout(g, group);
+    if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
+    char *ws = (char *)workspace;
+    HIP_TRY(launch_fill_u32((uint32_t *)(ws + L.status_off), sizeof(zen_status_info) / 4, 0u, s));
+    for (uint32_t w0 = 0; w0 < n_workers; w0 += group) {
+        const uint32_t nb = n_workers - w0 < group ? n_workers - w0 : group;
+        GradPtrs grads;
+        EncodedPtrs outs;
+        memset(&grads, 0, sizeof(grads));
+        memset(&outs, 0, sizeof(outs));
+        for (uint32_t i = 0; i < nb; ++i) {
+            grads.p[i] = host_grads[w0 + i];
+            outs.offsets[i] = host_outs[w0 + i].offsets;
+            outs.indices[i] = host_outs[w0 + i].indices;
+            outs.values[i] = host_outs[w0 + i].values;
+            outs.bitmap[i] = host_outs[w0 + i].bitmap;
+            outs.cap_rows[i] = host_outs[w0 + i].cap_rows;
+        }
+        HIP_TRY(launch_detect(g, grads, nb, ws, L, s));
+        HIP_TRY(launch_partition_scan(g, outs, nb, ws, L, s));
+        HIP_TRY(launch_scatter(g, ctx, grads, outs, nb, ws, L, s));
+    }
+    return ZEN_OK;
+}
+
+zen_status zen_encode(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_t hash_seed,
+                      const zen_encoded *host_out, void *workspace, uint64_t workspace_bytes,
+                      void *hip_stream)
+{
+    if (!ctx || !host_out) return ZEN_ERR_INVALID;
+    if (n_parts != ctx->geo.n_parts || hash_seed != ctx->geo.seed) return ZEN_ERR_INVALID;
+    const float *grads[1] = {grad};
+    return zen_encode_batch(ctx, grads, 1, host_out, workspace, workspace_bytes, hip_stream);
+}
+
+zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint64_t cap_rows,
+                       uint32_t *count, void *workspace, uint64_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx || !grad || !indices || !count || !workspace) return ZEN_ERR_INVALID;
+    if (((uintptr_t)grad & 15u) || ((uintptr_t)workspace & 255u) || cap_rows > 0xFFFFFFFEull) return ZEN_ERR_INVALID;
+    const Geometry &g = ctx->geo;
+    const EncodeLayout L = encode_layout(g, 1);
+    if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    GradPtrs grads;
+    memset(&grads, 0, sizeof(grads));
+    grads.p[0] = grad;
+    HIP_TRY(launch_fill_u32((uint32_t *)(ws + L.status_off), sizeof(zen_status_info) / 4, 0u, s));
+    HIP_TRY(launch_detect(g, grads, 1, ws, L, s));
+    HIP_TRY(launch_nonzero_list(g, indices, cap_rows, count, ws, L, s));
+    return ZEN_OK;
+}
+
+static zen_status run_aggregate(zen_ctx *ctx, const PartIdx &src, const Arr64<const float *> &src_values,
+                                const Arr64<const uint32_t *> &src_bitmap, uint32_t n_in, uint32_t n_servers,
+                                uint32_t first_part, const AggOut &outs, const Arr64<float *> &out_values,
+                                uint64_t max_in_rows, char *ws, const AggLayout &L, hipStream_t s)
+{
+    HIP_TRY(launch_aggregate(ctx->geo, ctx, src, src_values, src_bitmap, n_in, n_servers, first_part, outs,
+                             out_values, max_in_rows, ws, L, s));
+    return ZEN_OK;
+}
+
+zen_status zen_aggregate(zen_ctx *ctx, const zen_part *host_parts, uint32_t n_in, uint32_t part_id,
+                         uint32_t *out_indices, float *out_values, uint64_t out_cap_rows,
+                         uint32_t *out_count, uint64_t max_in_rows, void *workspace,
+                         uint64_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx || (!host_parts && n_in) || !out_indices || !out_values || !out_count || !workspace)
+        return ZEN_ERR_INVALID;
+    if (n_in > ZEN_MAX_BATCH || part_id >= ctx->geo.n_parts || max_in_rows > 0x7FFFFFFFull ||
+        out_cap_rows > 0xFFFFFFFEull)
+        return ZEN_ERR_INVALID;
+    if (((uintptr_t)workspace & 255u) || ((uintptr_t)out_values & 15u)) return ZEN_ERR_INVALID;
+    PartIdx src;
+    Arr64<const float *> sv;
+    Arr64<const uint32_t *> sb;
+    memset(&src, 0, sizeof(src));
+    memset(&sv, 0, sizeof(sv));
+    memset(&sb, 0, sizeof(sb));
+    src.single = 1;
+    bool any_bitmap = false;
+    for (uint32_t w = 0; w < n_in; ++w) {
+        const zen_part &p = host_parts[w];
+        if (!p.count || !p.values || (!p.indices && !p.bitmap)) return ZEN_ERR_INVALID;
+        if ((uintptr_t)p.values & 15u) return ZEN_ERR_INVALID;
+        if (p.bitmap && !p.indices) any_bitmap = true;
+        src.indices[w] = p.indices;
+        src.bounds[w] = p.count;
+        sv.v[w] = p.values;
+        sb.v[w] = p.indices ? nullptr : p.bitmap;
+    }
+    if (any_bitmap) return ZEN_ERR_INVALID;   // bitmap parts: not built yet
+    const AggLayout L = aggregate_layout(ctx->geo, 1, max_in_rows);
+    if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
+    AggOut outs;
+    Arr64<float *> ov;
+    memset(&outs, 0, sizeof(outs));
+    memset(&ov, 0, sizeof(ov));
+    outs.indices[0] = out_indices;
+    outs.count[0] = out_count;
+    outs.cap_rows[0] = out_cap_rows;
+    ov.v[0] = out_values;
+    return run_aggregate(ctx, src, sv, sb, n_in, 1, part_id, outs, ov, max_in_rows, (char *)workspace, L,
+                         (hipStream_t)hip_stream);
+}
+
+zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint32_t n_workers,
+                               const zen_aggregated *host_outs, uint64_t max_in_rows, void *workspace,
+                               uint64_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx || !host_encs || !host_outs || n_workers == 0 || !workspace) return ZEN_ERR_INVALID;
+    if (n_workers > ZEN_MAX_BATCH || max_in_rows > 0x7FFFFFFFull || ((uintptr_t)workspace & 255u))
+        return ZEN_ERR_INVALID;
+    const Geometry &g = ctx->geo;
+    if (ctx->fmt == ZEN_INDEX_BITMAP) return ZEN_ERR_INVALID;   // bitmap parts: not built yet
+    PartIdx src;
+    Arr64<const float *> sv;
+    Arr64<const uint32_t *> sb;
+    memset(&src, 0, sizeof(src));
+    memset(&sv, 0, sizeof(sv));
+    memset(&sb, 0, sizeof(sb));
+    for (uint32_t w = 0; w < n_workers; ++w) {
+        zen_status st = check_encoded(ctx, host_encs[w]);
+        if (st != ZEN_OK) return st;
+        src.indices[w] = host_encs[w].indices;
+        src.bounds[w] = host_encs[w].offsets;
+        sv.v[w] = host_encs[w].values;
+        sb.v[w] = host_encs[w].bitmap;
+    }
+    for (uint32_t j = 0; j < g.n_parts; ++j) {
+        const zen_aggregated &o = host_outs[j];
+        if (!o.indices || !o.values || !o.count || ((uintptr_t)o.values & 15u) || o.cap_rows > 0xFFFFFFFEull)
+            return ZEN_ERR_INVALID;
+    }
+    const uint32_t group = g.n_parts < ZEN_MAX_BATCH ? g.n_parts : ZEN_MAX_BATCH;
+    const AggLayout L = aggregate_layout(g, group, max_in_rows);
+    if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
+    if (g.n_parts > ZEN_MAX_BATCH) return ZEN_ERR_INVALID;   // one launch group per call for now
+    AggOut outs;
+    Arr64<float *> ov;
+    memset(&outs, 0, sizeof(outs));
+    memset(&ov, 0, sizeof(ov));
+    for (uint32_t j = 0; j < g.n_parts; ++j) {
+        outs.indices[j] = host_outs[j].indices;
+        outs.count[j] = host_outs[j].count;
+        outs.cap_rows[j] = host_outs[j].cap_rows;
+        ov.v[j] = host_outs[j].values;
+    }
+    src.single = 0;
+    src.server0 = 0;
+    return run_aggregate(ctx, src, sv, sb, n_workers, g.n_parts, 0, outs, ov, max_in_rows, (char *)workspace, L,
+                         (hipStream_t)hip_stream);
+}
+
+zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream, zen_status_info *host_info)
+{
+    if (!ctx || !workspace) return ZEN_ERR_INVALID;
+    zen_status_info info;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipMemcpyAsync(&info, workspace, sizeof(info), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (host_info) *host_info = info;
+    return (info.flags & 3u) ? ZEN_ERR_CAPACITY : (info.flags ? ZEN_ERR_INVALID : ZEN_OK);
+}
+
+zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, void *hip_stream)
+{
+    if (count && (!idx || !out)) return ZEN_ERR_INVALID;
+    HIP_TRY(launch_hash_many(idx, count, seed, out, (hipStream_t)hip_stream));
+    return ZEN_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,522 @@
+// Encode kernels for gfx950: non-zero detection + per-tile owner histogram, the partition scan,
+// and the stable scatter with value gather (and hash-bitmap assembly).
+//
+// One launch covers every worker of a batch: blockIdx.y = worker, blockIdx.x = tile of consecutive
+// rows.  The dense gradient is read exactly once, by the detect kernel, with 16-byte loads; all
+// later steps work from the 1-bit-per-row mask and touch the dense data only to copy non-zero rows.
+#include "zen_device.h"
+#include "zen_internal.h"
+
+namespace zen {
+
+static constexpr int DETECT_THREADS = 256;
+static constexpr int SCATTER_THREADS = 256;
+static constexpr int SCAN_THREADS = 1024;
+static constexpr int SEG_WORDS = 64;              // mask words expanded per scatter segment
+static constexpr int SEG_ROWS = SEG_WORDS * 32;   // 2048
+
+__device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+// ----------------------------------------------------------------------------------------------
+// E1: detection.  Each variant fills s_mask[tile_words] (bit r%32 of word r/32, tile-relative).
+// ----------------------------------------------------------------------------------------------
+
+// row_dim == 1.  A wave-load of 64 x 16 B covers 256 rows = 8 mask words.
+template <int UNROLL>
+__device__ __forceinline__ void detect_elem(const float *__restrict__ g, uint64_t n_rows, uint64_t row0,
+                                            uint32_t tile_rows, uint32_t *s_mask)
+{
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const uint32_t n_chunks = tile_rows >> 8;
+    for (uint32_t c0 = wave * UNROLL; c0 < n_chunks; c0 += nw * UNROLL) {
+        u32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t c = c0 + u;
+            const uint64_t e = row0 + ((uint64_t)c << 8) + lane * 4;
+            v[u] = (u32x4){0u, 0u, 0u, 0u};
+            if (c < n_chunks) {
+                if (row0 + ((uint64_t)(c + 1) << 8) <= n_rows) {
+                    v[u] = load_stream((const u32x4 *)(g + e));
+                } else {
+                    const uint32_t *gu = (const uint32_t *)g;
+                    if (e + 0 < n_rows) v[u].x = gu[e + 0];
+                    if (e + 1 < n_rows) v[u].y = gu[e + 1];
+                    if (e + 2 < n_rows) v[u].z = gu[e + 2];
+                    if (e + 3 < n_rows) v[u].w = gu[e + 3];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t c = c0 + u;
+            if (c < n_chunks) {
+                uint32_t nib = ((v[u].x & 0x7fffffffu) ? 1u : 0u) | ((v[u].y & 0x7fffffffu) ? 2u : 0u) |
+                               ((v[u].z & 0x7fffffffu) ? 4u : 0u) | ((v[u].w & 0x7fffffffu) ? 8u : 0u);
+                uint32_t word = nib << (4 * (lane & 7));
+                word |= __shfl_xor(word, 1, ZEN_WAVE);
+                word |= __shfl_xor(word, 2, ZEN_WAVE);
+                word |= __shfl_xor(word, 4, ZEN_WAVE);
+                if ((lane & 7) == 0) s_mask[c * 8 + (lane >> 3)] = word;
+            }
+        }
+    }
+}
+
+// row_dim = 4*L, L a power of two <= 32: L lanes per row, 64/L rows per wave-load, 64 rows per unit.
+template <int L>
+__device__ __forceinline__ void detect_sub(const float *__restrict__ g, uint64_t n_rows, uint64_t row0,
+                                           uint32_t tile_rows, uint32_t *s_mask)
+{
+    constexpr int RPL = 64 / L;               // rows per wave-load
+    constexpr int BATCH = L < 16 ? L : 16;    // loads kept in flight
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const uint32_t n_units = tile_rows >> 6;
+    for (uint32_t unit = wave; unit < n_units; unit += nw) {
+        const uint64_t urow = row0 + ((uint64_t)unit << 6);
+        const u32x4 *base = (const u32x4 *)(g + urow * (uint64_t)(4 * L));
+        uint64_t unit_mask = 0;
+#pragma unroll
+        for (int j0 = 0; j0 < L; j0 += BATCH) {
+            u32x4 v[BATCH];
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const uint32_t vi = (uint32_t)(j0 + j) * 64 + lane;   // 16-byte vector inside the unit
+                const uint64_t row = urow + vi / L;
+                v[j] = (u32x4){0u, 0u, 0u, 0u};
+                if (row < n_rows) v[j] = load_stream(base + vi);
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const uint64_t b = ballot(nonzero_mag(v[j]) != 0);
+                uint64_t rows_bits;
+                if (L == 1) {
+                    rows_bits = b;
+                } else {
+                    const uint64_t lmask = (1ull << L) - 1ull;
+                    const bool mine = lane < RPL && ((b >> (lane * L)) & lmask) != 0;
+                    rows_bits = ballot(mine);
+                }
+                unit_mask |= rows_bits << (((j0 + j) * RPL) & 63);
+            }
+        }
+        if (lane == 0) {
+            s_mask[unit * 2 + 0] = (uint32_t)unit_mask;
+            s_mask[unit * 2 + 1] = (uint32_t)(unit_mask >> 32);
+        }
+    }
+}
+
+// Any row_dim: one wave per row, two rows in flight.  VEC = 4 (16-byte loads) or 1.
+template <int VEC>
+__device__ __forceinline__ uint32_t row_or(const float *__restrict__ row, uint32_t nvec, uint32_t lane)
+{
+    constexpr int U = 4;
+    uint32_t acc = 0;
+    for (uint32_t k = lane; k < nvec; k += 64 * U) {
+        if (VEC == 4) {
+            u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                v[u] = (u32x4){0u, 0u, 0u, 0u};
+                if (k + 64 * u < nvec) v[u] = load_stream((const u32x4 *)row + k + 64 * u);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc |= v[u].x | v[u].y | v[u].z | v[u].w;
+        } else {
+            uint32_t v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                v[u] = 0;
+                if (k + 64 * u < nvec) v[u] = __builtin_nontemporal_load((const uint32_t *)row + k + 64 * u);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc |= v[u];
+        }
+    }
+    return acc & 0x7fffffffu;
+}
+
+template <int VEC>
+__device__ __forceinline__ void detect_row(const float *__restrict__ g, uint64_t n_rows, uint32_t row_dim,
+                                           uint64_t row0, uint32_t tile_rows, uint32_t *s_mask)
+{
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const uint32_t nvec = row_dim / VEC;
+    // s_mask was zeroed by the caller
+    for (uint32_t r = wave; r < tile_rows; r += 2 * nw) {
+        const uint32_t r2 = r + nw;
+        const uint64_t ga = row0 + r, gb = row0 + r2;
+        uint32_t a = 0, b = 0;
+        if (ga < n_rows) a = row_or<VEC>(g + ga * (uint64_t)row_dim, nvec, lane);
+        if (r2 < tile_rows && gb < n_rows) b = row_or<VEC>(g + gb * (uint64_t)row_dim, nvec, lane);
+        const bool nza = ballot(a != 0) != 0, nzb = ballot(b != 0) != 0;
+        if (lane == 0) {
+            if (nza) atomicOr(&s_mask[r >> 5], 1u << (r & 31));
+            if (nzb) atomicOr(&s_mask[r2 >> 5], 1u << (r2 & 31));
+        }
+    }
+}
+
+// E1 + E3: one block per (tile, worker).  Writes the tile's mask words and its owner histogram
+// hist[tile][0..n_parts).
+__global__ void __launch_bounds__(DETECT_THREADS)
+detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
+              uint32_t *hist_base, uint64_t hist_stride_words)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *s_mask = smem;                  // [tile_words]
+    uint32_t *s_hist = smem + g.tile_words;   // [n_parts]
+    const uint32_t tile = blockIdx.x, worker = blockIdx.y;
+    const float *__restrict__ grad = grads.p[worker];
+    const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+
+    for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) s_hist[i] = 0;
+    if (g.mode == MODE_ROW) {
+        for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) s_mask[i] = 0;
+        __syncthreads();
+    }
+
+    switch (g.mode) {
+    case MODE_ELEM: detect_elem<8>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+    case MODE_SUB:
+        switch (g.row_dim) {
+        case 4: detect_sub<1>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+        case 8: detect_sub<2>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+        case 16: detect_sub<4>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+        case 32: detect_sub<8>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+        case 64: detect_sub<16>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+        default: detect_sub<32>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
+        }
+        break;
+    default:
+        if ((g.row_dim & 3u) == 0) detect_row<4>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
+        else detect_row<1>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
+        break;
+    }
+    __syncthreads();
+
+    uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
+    for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) gmask[i] = s_mask[i];
+
+    // owner histogram of the tile's non-zero rows
+    for (uint32_t r = threadIdx.x; r < g.tile_rows; r += blockDim.x) {
+        if ((s_mask[r >> 5] >> (r & 31)) & 1u) {
+            const uint32_t p = owner_of((uint32_t)(row0 + r), g.seed, g.n_parts, g.pow2_mask);
+            atomicAdd(&s_hist[p], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * g.n_parts;
+    for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) ghist[i] = s_hist[i];
+}
+
+// ----------------------------------------------------------------------------------------------
+// E4: per worker, turn hist[tile][p] into the output position of the first row of (tile, p):
+//     base[tile][p] = offsets[p] + sum_{t < tile} hist[t][p],  offsets = exclusive scan of totals.
+// One block per worker; thread (grp, p) walks a contiguous range of tiles.
+// ----------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(SCAN_THREADS)
+partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_t hist_stride_words,
+                      zen_status_info *status)
+{
+    __shared__ uint32_t s_part[SCAN_THREADS];   // [grp][p] partial sums, later group prefixes
+    __shared__ uint32_t s_off[ZEN_MAX_PARTS + 1];
+    const uint32_t worker = blockIdx.x;
+    uint32_t *hist = hist_base + worker * hist_stride_words;
+    const uint32_t n = g.n_parts;
+    const uint32_t n_groups = SCAN_THREADS / n;   // >= 1 since n <= 1024
+    const uint32_t p = threadIdx.x % n, grp = threadIdx.x / n;
+    const bool active = grp < n_groups;
+    const uint32_t per = (g.n_tiles + n_groups - 1) / n_groups;
+    const uint32_t t0 = active ? min(grp * per, g.n_tiles) : 0;
+    const uint32_t t1 = active ? min(t0 + per, g.n_tiles) : 0;
+
+    uint32_t sum = 0;
+    for (uint32_t t = t0; t < t1; ++t) sum += hist[(uint64_t)t * n + p];
+    if (active) s_part[grp * n + p] = sum;
+    __syncthreads();
+    // exclusive scan over groups for each p; total per p
+    if (threadIdx.x < n) {
+        uint32_t run = 0;
+        for (uint32_t gI = 0; gI < n_groups; ++gI) {
+            const uint32_t t = s_part[gI * n + threadIdx.x];
+            s_part[gI * n + threadIdx.x] = run;
+            run += t;
+        }
+        s_off[threadIdx.x + 1] = run;   // totals, shifted by one
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        s_off[0] = 0;
+        uint32_t run = 0;
+        for (uint32_t q = 0; q < n; ++q) { run += s_off[q + 1]; s_off[q + 1] = run; }
+        if ((uint64_t)run > outs.cap_rows[worker]) {
+            atomicOr(&status->flags, 1u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)run);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) outs.offsets[worker][i] = s_off[i];
+    if (active) {
+        uint32_t run = s_off[p] + s_part[grp * n + p];
+        for (uint32_t t = t0; t < t1; ++t) {
+            const uint64_t a = (uint64_t)t * n + p;
+            const uint32_t h = hist[a];
+            hist[a] = run;
+            run += h;
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// E5 + E6 (+E7): one block per (tile, worker).  Walks the tile's mask in segments, expands the set
+// bits to an ascending row list in LDS, ranks every row stably inside its partition, writes the
+// index, and copies the row's values.
+// ----------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(SCATTER_THREADS)
+scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
+               uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *s_run = smem;                          // [n_parts]
+    uint32_t *s_cnt = s_run + g.n_parts;             // [4][n_parts]
+    uint32_t *s_list = s_cnt + 4 * g.n_parts;        // [SEG_ROWS] tile-relative... absolute row ids
+    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS]
+    uint32_t *s_tmp = s_pos + SEG_ROWS;              // [32]
+    const uint32_t tile = blockIdx.x, worker = blockIdx.y;
+    const uint32_t n = g.n_parts, D = g.row_dim;
+    const float *__restrict__ grad = grads.p[worker];
+    const uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
+    const uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * n;
+    uint32_t *__restrict__ out_idx = outs.indices[worker];
+    float *__restrict__ out_val = outs.values[worker];
+    const uint64_t cap = outs.cap_rows[worker];
+    const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_run[i] = ghist[i];
+    for (uint32_t i = threadIdx.x; i < 4 * n; i += blockDim.x) s_cnt[i] = 0;
+
+    for (uint32_t w0 = 0; w0 < g.tile_words; w0 += SEG_WORDS) {
+        // (a) expand up to 64 mask words into the ascending row list
+        uint32_t word = 0;
+        if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words) word = gmask[w0 + threadIdx.x];
+        uint32_t total;
+        const uint32_t pre = block_exclusive_scan(threadIdx.x < SEG_WORDS ? __popc(word) : 0u, s_tmp, &total);
+        if (total == 0) continue;   // uniform: total comes from LDS
+        if (threadIdx.x < SEG_WORDS) {
+            uint32_t k = pre;
+            const uint32_t rbase = (uint32_t)(row0 + (uint64_t)(w0 + threadIdx.x) * 32);
+            while (word) {
+                const uint32_t b = __ffs(word) - 1;
+                word &= word - 1;
+                s_list[k++] = rbase + b;
+            }
+        }
+        __syncthreads();
+        // (b) rank and write indices
+        for (uint32_t c = 0; c < total; c += blockDim.x) {
+            const uint32_t i = c + threadIdx.x;
+            const bool valid = i < total;
+            const uint32_t row = valid ? s_list[i] : 0u;
+            const uint32_t p = valid ? owner_of(row, g.seed, n, g.pow2_mask) : 0u;
+            const uint32_t pos = block_stable_rank(valid, p, g.part_bits, n, s_run, s_cnt);
+            if (valid) {
+                if (pos < cap) {
+                    if (out_idx) out_idx[pos] = row;
+                    if (D == 1) out_val[pos] = grad[row];
+                    s_pos[i] = pos;
+                } else {
+                    s_pos[i] = 0xFFFFFFFFu;
+                }
+            }
+        }
+        // (c) copy rows (row_dim > 1)
+        if (D > 1) {
+            __syncthreads();
+            if ((D & 3u) == 0 && D >= 256) {
+                // one wave per row, 16-byte vectors
+                const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
+                for (uint32_t i = threadIdx.x >> 6; i < total; i += nw) {
+                    const uint32_t pos = s_pos[i];
+                    if (pos == 0xFFFFFFFFu) continue;
+                    const u32x4 *src = (const u32x4 *)(grad + (uint64_t)s_list[i] * D);
+                    u32x4 *dst = (u32x4 *)(out_val + (uint64_t)pos * D);
+                    for (uint32_t v = lane; v < V; v += 64 * 4) {
+                        u32x4 x[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            if (v + 64 * u < V) x[u] = src[v + 64 * u];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            if (v + 64 * u < V) dst[v + 64 * u] = x[u];
+                    }
+                }
+            } else if ((D & 3u) == 0) {
+                const uint32_t V = D >> 2;
+                const uint32_t n_vec = total * V;           // total <= 2048, V < 64
+                for (uint32_t f = threadIdx.x; f < n_vec; f += blockDim.x) {
+                    const uint32_t i = f / V, v = f - i * V;
+                    const uint32_t pos = s_pos[i];
+                    if (pos != 0xFFFFFFFFu) {
+                        const u32x4 x = ((const u32x4 *)(grad + (uint64_t)s_list[i] * D))[v];
+                        ((u32x4 *)(out_val + (uint64_t)pos * D))[v] = x;
+                    }
+                }
+            } else {
+                const uint32_t n_el = total * D;            // total <= 2048, row_dim <= 2^20
+                for (uint32_t f = threadIdx.x; f < n_el; f += blockDim.x) {
+                    const uint32_t i = f / D, v = f - i * D;
+                    const uint32_t pos = s_pos[i];
+                    if (pos != 0xFFFFFFFFu) out_val[(uint64_t)pos * D + v] = grad[(uint64_t)s_list[i] * D + v];
+                }
+            }
+        }
+        __syncthreads();   // s_list / s_pos are rewritten by the next segment
+    }
+}
+
+// E2 on its own: ascending list of non-zero rows from the mask (zen_nonzero).  The scan kernel has
+// turned hist into bases, so with n_parts = 1 geometry hist[tile][0] is the tile's output position.
+__global__ void __launch_bounds__(SCATTER_THREADS)
+nonzero_list_kernel(Geometry g, const uint32_t *gmask_base, const uint32_t *tile_base, uint32_t *indices,
+                    uint64_t cap_rows)
+{
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t tile = blockIdx.x;
+    const uint32_t *gmask = gmask_base + (uint64_t)tile * g.tile_words;
+    uint32_t run = tile_base[tile];
+    const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+    for (uint32_t w0 = 0; w0 < g.tile_words; w0 += blockDim.x) {
+        const uint32_t wi = w0 + threadIdx.x;
+        uint32_t word = wi < g.tile_words ? gmask[wi] : 0u;
+        uint32_t total;
+        const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &total);
+        uint64_t k = (uint64_t)run + pre;
+        const uint32_t rbase = (uint32_t)(row0 + (uint64_t)wi * 32);
+        while (word) {
+            const uint32_t b = __ffs(word) - 1;
+            word &= word - 1;
+            if (k < cap_rows) indices[k] = rbase + b;
+            ++k;
+        }
+        run += total;
+    }
+}
+
+// Sum of per-tile counts for the non-zero list: one block, hist[tile] (n_parts = 1 view) -> bases.
+__global__ void __launch_bounds__(SCAN_THREADS)
+tile_scan_kernel(uint32_t *tile_cnt, uint32_t n_tiles, uint32_t *count, uint64_t cap_rows,
+                 zen_status_info *status)
+{
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t per = (n_tiles + blockDim.x - 1) / blockDim.x;
+    const uint32_t t0 = min(threadIdx.x * per, n_tiles), t1 = min(t0 + per, n_tiles);
+    uint32_t sum = 0;
+    for (uint32_t t = t0; t < t1; ++t) sum += tile_cnt[t];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(sum, s_tmp, &total);
+    for (uint32_t t = t0; t < t1; ++t) { const uint32_t h = tile_cnt[t]; tile_cnt[t] = run; run += h; }
+    if (threadIdx.x == 0) {
+        *count = total;
+        if ((uint64_t)total > cap_rows) {
+            atomicOr(&status->flags, 1u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)total);
+        }
+    }
+}
+
+// Per-tile popcount of the mask (n_parts-independent), used by zen_nonzero.
+__global__ void __launch_bounds__(256)
+tile_popcount_kernel(Geometry g, const uint32_t *gmask_base, uint32_t *tile_cnt)
+{
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t tile = blockIdx.x;
+    const uint32_t *gmask = gmask_base + (uint64_t)tile * g.tile_words;
+    uint32_t c = 0;
+    for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) c += __popc(gmask[i]);
+    uint32_t total;
+    block_exclusive_scan(c, s_tmp, &total);
+    if (threadIdx.x == 0) tile_cnt[tile] = total;
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+__global__ void hash_many_kernel(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        out[i] = murmur3_u32(idx[i], seed);
+}
+
+// ----------------------------------------------------------------------------------------------
+// launchers
+// ----------------------------------------------------------------------------------------------
+hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + 1023) / 1024;
+    fill_u32_kernel<<<(uint32_t)(blocks > 65536 ? 65536 : blocks), 256, 0, s>>>(p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    const uint64_t blocks = (count + 255) / 256;
+    hash_many_kernel<<<(uint32_t)(blocks > 65536 ? 65536 : blocks), 256, 0, s>>>(idx, count, seed, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_detect(const Geometry &g, const GradPtrs &grads, uint32_t batch, char *ws,
+                         const EncodeLayout &L, hipStream_t s)
+{
+    const size_t lds = (size_t)(g.tile_words + g.n_parts) * 4;
+    detect_kernel<<<dim3(g.n_tiles, batch), DETECT_THREADS, lds, s>>>(
+        g, grads, (uint32_t *)(ws + L.mask_off), L.mask_stride / 4, (uint32_t *)(ws + L.hist_off),
+        L.hist_stride / 4);
+    return hipGetLastError();
+}
+
+hipError_t launch_partition_scan(const Geometry &g, const EncodedPtrs &outs, uint32_t batch, char *ws,
+                                 const EncodeLayout &L, hipStream_t s)
+{
+    partition_scan_kernel<<<batch, SCAN_THREADS, 0, s>>>(g, outs, (uint32_t *)(ws + L.hist_off),
+                                                         L.hist_stride / 4,
+                                                         (zen_status_info *)(ws + L.status_off));
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter(const Geometry &g, const zen_ctx *ctx, const GradPtrs &grads,
+                          const EncodedPtrs &outs, uint32_t batch, char *ws, const EncodeLayout &L,
+                          hipStream_t s)
+{
+    (void)ctx;
+    const size_t lds = (size_t)(5 * g.n_parts + 2 * SEG_ROWS + 32) * 4;
+    scatter_kernel<<<dim3(g.n_tiles, batch), SCATTER_THREADS, lds, s>>>(
+        g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+        (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4);
+    return hipGetLastError();
+}
+
+hipError_t launch_nonzero_list(const Geometry &g, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
+                               char *ws, const EncodeLayout &L, hipStream_t s)
+{
+    uint32_t *mask = (uint32_t *)(ws + L.mask_off);
+    uint32_t *tile_cnt = (uint32_t *)(ws + L.hist_off);   // reused: n_tiles words fit (n_parts >= 1)
+    tile_popcount_kernel<<<g.n_tiles, 256, 0, s>>>(g, mask, tile_cnt);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    tile_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(tile_cnt, g.n_tiles, count, cap_rows,
+                                                (zen_status_info *)(ws + L.status_off));
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    nonzero_list_kernel<<<g.n_tiles, SCATTER_THREADS, 0, s>>>(g, mask, tile_cnt, indices, cap_rows);
+    return hipGetLastError();
+}
+
+} // namespace zen

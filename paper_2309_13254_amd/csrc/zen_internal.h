@@ -1,0 +1,122 @@
+// Host-side internals shared by the C-ABI translation units: the context, launch geometry and
+// the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/zen.h"
+
+namespace zen {
+
+enum DetectMode : uint32_t {
+    MODE_ELEM = 0, // row_dim == 1: one 16-byte load covers four rows
+    MODE_SUB = 1,  // row_dim in {4,8,...,128} with row_dim/4 a power of two: row_dim/4 lanes per row
+    MODE_ROW = 2   // anything else: one wave per row (16-byte loads if row_dim % 4 == 0)
+};
+
+// Everything the kernels need to know about one (n_rows, row_dim, n_parts, seed) problem.
+struct Geometry {
+    uint64_t n_rows;
+    uint32_t row_dim;
+    uint32_t n_parts;
+    uint32_t seed;
+    uint32_t pow2_mask;      // n_parts-1 if power of two else 0
+    uint32_t part_bits;      // ceil(log2(n_parts))
+    uint32_t mode;           // DetectMode
+    uint32_t tile_rows;      // rows per tile (multiple of 256 / 64 / 32 by mode)
+    uint32_t tile_words;     // tile_rows / 32
+    uint32_t n_tiles;        // ceil(n_rows / tile_rows)
+    uint32_t bitmap;         // 1 = hash-bitmap index format
+};
+
+// Per-call encode workspace layout (bytes from the workspace base).
+struct EncodeLayout {
+    uint64_t status_off;     // zen_status_info
+    uint64_t mask_off;       // per worker: n_tiles*tile_words u32
+    uint64_t mask_stride;
+    uint64_t hist_off;       // per worker: n_tiles*n_parts u32 (tile-major)
+    uint64_t hist_stride;
+    uint64_t total;
+};
+
+struct GradPtrs { const float *p[ZEN_MAX_BATCH]; };
+struct EncodedPtrs {
+    uint32_t *offsets[ZEN_MAX_BATCH];
+    uint32_t *indices[ZEN_MAX_BATCH];
+    float *values[ZEN_MAX_BATCH];
+    uint32_t *bitmap[ZEN_MAX_BATCH];
+    uint64_t cap_rows[ZEN_MAX_BATCH];
+};
+
+template <class T> struct Arr64 { T v[ZEN_MAX_BATCH]; };
+
+// Sources of the aggregation: part (w, server j) = rows [bounds[w][j], bounds[w][j+1]) of
+// indices[w] / values[w] (batch form), or rows [0, bounds[w][0]) when `single` is set.
+struct PartIdx {
+    const uint32_t *indices[ZEN_MAX_BATCH];
+    const uint32_t *bounds[ZEN_MAX_BATCH];
+    uint32_t single;
+    uint32_t server0;   // batch form: first server (partition id) handled by this launch group
+};
+struct AggOut {
+    uint32_t *indices[ZEN_MAX_BATCH];
+    uint32_t *count[ZEN_MAX_BATCH];
+    uint64_t cap_rows[ZEN_MAX_BATCH];
+};
+
+struct AggLayout {
+    uint64_t status_off;     // zen_status_info
+    uint64_t counters_off;   // per server: 16 u32 (0: unique count, 1: total rows in)
+    uint64_t keys_off;       // per server: table_cap u32 keys
+    uint64_t rank_off;       // per server: table_cap u32 output rank of the slot's key
+    uint64_t uniq_off;       // large path: per server 2 x uniq_cap u32 (ping-pong)
+    uint64_t uniq_cap;       // = max_in_rows rounded up
+    uint64_t sorthist_off;   // large path: per server sort_blocks x 256 u32
+    uint64_t sort_blocks;    // radix-sort blocks per server
+    uint64_t decode_off;     // bitmap parts: per (server, part) decoded indices
+    uint64_t decode_stride;
+    uint64_t table_cap;      // slots per server (power of two)
+    uint32_t small_path;     // 1: one block per server sorts in LDS
+    uint64_t total;
+};
+
+} // namespace zen
+
+struct zen_ctx {
+    zen::Geometry geo;
+    zen_index_format fmt;
+    int device;
+    // hash-bitmap tables (BITMAP contexts only)
+    uint32_t *d_domain;        // [n_rows] sorted domains, partition-major
+    uint32_t *d_dom_offsets;   // [n_parts+1] start of each domain in d_domain
+    uint32_t *d_dom_tile_base; // [n_tiles][n_parts] rank of the first row of each tile in each domain
+    uint32_t *d_bm_word_off;   // [n_parts+1] first bitmap word of each partition
+    uint64_t *h_bm_word_off;   // host copy
+    uint64_t *h_dom_sizes;     // host copy
+    uint64_t bm_total_words;
+};
+
+namespace zen {
+
+EncodeLayout encode_layout(const Geometry &g, uint32_t batch);
+AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows);
+
+// encode launchers (zen_encode.hip)
+hipError_t launch_detect(const Geometry &g, const GradPtrs &grads, uint32_t batch, char *ws,
+                         const EncodeLayout &L, hipStream_t s);
+hipError_t launch_partition_scan(const Geometry &g, const EncodedPtrs &outs, uint32_t batch, char *ws,
+                                 const EncodeLayout &L, hipStream_t s);
+hipError_t launch_scatter(const Geometry &g, const zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs,
+                          uint32_t batch, char *ws, const EncodeLayout &L, hipStream_t s);
+hipError_t launch_nonzero_list(const Geometry &g, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
+                               char *ws, const EncodeLayout &L, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s);
+hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s);
+
+// aggregate launchers (zen_aggregate.hip)
+hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx &src,
+                            const Arr64<const float *> &src_values, const Arr64<const uint32_t *> &src_bitmap,
+                            uint32_t n_in, uint32_t n_servers, uint32_t first_part_id, const AggOut &outs,
+                            const Arr64<float *> &out_values, uint64_t max_in_rows, char *ws,
+                            const AggLayout &L, hipStream_t s);
+
+} // namespace zen

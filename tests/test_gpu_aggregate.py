@@ -1,0 +1,156 @@
+"""GPU parity: zen_aggregate / zen_aggregate_batch against the CPU oracle.
+
+Indices and counts bit-exact; fp32 sums within 1e-6 * sum|x| of the oracle's fp64 sum (the atomic
+summation order is not fixed), and bit-exact where a row has a single contributor.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import MINI_WORKLOADS, dense_from_sparse
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def zen():
+    import paper_2309_13254_amd as z
+
+    z.load_library()
+    return z
+
+
+def _oracle_parts(oracle, wl, sparse):
+    encs = []
+    for rows, vals in sparse:
+        encs.append(oracle.encode(dense_from_sparse(wl, rows, vals), wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed))
+    return encs
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+@pytest.mark.parametrize("big_table", [False, True])
+def test_encode_then_aggregate_batch(oracle, zen, cid, big_table):
+    import gpu_util as G
+
+    wl = MINI_WORKLOADS[cid]
+    sparse, grads = G.workload_inputs(wl)
+    ctx = zen.ZenContext(wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed)
+    encs, (st, _, _) = G.run_encode_batch(ctx, grads, [r.size for r, _ in sparse])
+    assert st == 0
+    ref_encs = _oracle_parts(oracle, wl, sparse)
+    per_server = [sum(int(e.offsets[j + 1]) - int(e.offsets[j]) for e in ref_encs) for j in range(wl.n_parts)]
+    # big_table forces the multi-kernel (radix sort) path, the other the one-block LDS path when it fits
+    max_in = max(per_server) if not big_table else max(max(per_server), 20000)
+    outs, (st, flags, needed) = G.run_aggregate_batch(ctx, encs, [max(p, 1) for p in per_server], max_in)
+    assert st == 0 and flags == 0
+    total_u = 0
+    for j in range(wl.n_parts):
+        parts = [(e.indices[e.offsets[j]:e.offsets[j + 1]], e.values[e.offsets[j]:e.offsets[j + 1]]) for e in ref_encs]
+        ref = oracle.aggregate(parts, wl.n_rows, wl.row_dim)
+        U, idx, val = G.aggregated_to_host(outs[j])
+        assert U == ref.U
+        assert np.array_equal(idx, ref.indices)
+        G.check_sums(val, ref)
+        total_u += U
+    union = set()
+    for rows, _ in sparse:
+        union.update(rows.tolist())
+    assert total_u == len(union)
+
+
+@pytest.mark.parametrize("D", [1, 3, 4, 64, 256, 1024])
+@pytest.mark.parametrize("max_in_scale", [1, 40])
+def test_single_server_explicit_parts(oracle, zen, D, max_in_scale):
+    import gpu_util as G
+
+    rng = np.random.default_rng(D + max_in_scale)
+    R, n_in = 50000, 7
+    ctx = zen.ZenContext(R, D, 4, 123)
+    parts_h = []
+    for w in range(n_in):
+        c = int(rng.integers(0, 600)) if w != 3 else 0               # one empty part
+        idx = rng.integers(0, R, size=c).astype(np.uint32)            # unsorted, duplicates inside a part
+        val = rng.standard_normal((c, D)).astype(np.float32)
+        parts_h.append((idx, val))
+    total = sum(i.size for i, _ in parts_h)
+    ref = oracle.aggregate(parts_h, R, D)
+    parts_d = []
+    for idx, val in parts_h:
+        parts_d.append((G.to_dev(idx) if idx.size else torch.empty(1, dtype=torch.int32, device="cuda"), None,
+                        torch.from_numpy(val).cuda() if idx.size else torch.empty((1, D), device="cuda"),
+                        torch.tensor([idx.size], dtype=torch.int32, device="cuda")))
+    max_in = total * max_in_scale
+    out = zen.alloc_aggregated(ctx, total)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, max_in))
+    zen.zen_aggregate(ctx, parts_d, 2, out, max_in, ws)
+    st, flags, _ = zen.zen_status_fetch(ctx, ws)
+    assert st == 0 and flags == 0
+    U, idx, val = G.aggregated_to_host(out)
+    assert U == ref.U and np.array_equal(idx, ref.indices)
+    G.check_sums(val, ref)
+
+
+def test_disjoint_and_identical_inputs(oracle, zen):
+    import gpu_util as G
+
+    R, D = 4000, 8
+    ctx = zen.ZenContext(R, D, 2, 5)
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(R).astype(np.uint32)[:900]
+    vals = rng.standard_normal((900, D)).astype(np.float32)
+    cnt = lambda k: torch.tensor([k], dtype=torch.int32, device="cuda")
+    # disjoint: output = sorted concatenation, bit-exact
+    parts = [(G.to_dev(perm[i * 300:(i + 1) * 300]), None, torch.from_numpy(vals[i * 300:(i + 1) * 300]).cuda(), cnt(300))
+             for i in range(3)]
+    out = zen.alloc_aggregated(ctx, 900)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, 900))
+    zen.zen_aggregate(ctx, parts, 0, out, 900, ws)
+    assert zen.zen_status_fetch(ctx, ws)[0] == 0
+    U, idx, val = G.aggregated_to_host(out)
+    order = np.argsort(perm)
+    assert U == 900 and np.array_equal(idx, perm[order])
+    assert np.array_equal(val.view(np.uint32), vals[order].view(np.uint32))
+    # the same part four times: values x4 exactly (power of two)
+    p0 = (G.to_dev(perm[:300]), None, torch.from_numpy(vals[:300]).cuda(), cnt(300))
+    zen.zen_aggregate(ctx, [p0] * 4, 1, out, 1200, zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, 1200)))
+    torch.cuda.synchronize()
+    U, idx, val = G.aggregated_to_host(out)
+    o = np.argsort(perm[:300])
+    assert U == 300 and np.array_equal(idx, perm[:300][o])
+    assert np.array_equal(val, vals[:300][o] * np.float32(4))
+    # cancellation keeps the index
+    a = (G.to_dev(np.array([7, 9], np.uint32)), None, torch.tensor([[1.5] * D, [2.0] * D], device="cuda"), cnt(2))
+    b = (G.to_dev(np.array([7], np.uint32)), None, torch.tensor([[-1.5] * D], device="cuda"), cnt(1))
+    zen.zen_aggregate(ctx, [a, b], 0, out, 900, ws)
+    assert zen.zen_status_fetch(ctx, ws)[0] == 0
+    U, idx, val = G.aggregated_to_host(out)
+    assert U == 2 and idx.tolist() == [7, 9] and np.all(val[0] == 0) and np.all(val[1] == 2.0)
+
+
+def test_overflow_flags(oracle, zen):
+    import gpu_util as G
+
+    R, D = 10000, 4
+    ctx = zen.ZenContext(R, D, 2, 5)
+    idx = np.arange(0, 3000, 3, dtype=np.uint32)
+    val = np.ones((idx.size, D), np.float32)
+    part = (G.to_dev(idx), None, torch.from_numpy(val).cuda(), torch.tensor([idx.size], dtype=torch.int32, device="cuda"))
+    # bound on incoming rows too small: table flag, count 0, needed = actual total
+    out = zen.alloc_aggregated(ctx, 2000)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, 500))
+    zen.zen_aggregate(ctx, [part, part], 0, out, 500, ws)
+    st, flags, needed = zen.zen_status_fetch(ctx, ws)
+    assert st == zen.ZEN_ERR_CAPACITY and (flags & 2) and needed == 2 * idx.size
+    assert int(out.count.item()) == 0
+    # output capacity too small: capacity flag, count = U, first rows correct, nothing past the capacity
+    guard_idx = torch.full((1000,), -2, dtype=torch.int32, device="cuda")
+    guard_val = torch.full((1000, D), 7.0, device="cuda")
+    out2 = zen.Aggregated(guard_idx, guard_val, torch.zeros(1, dtype=torch.int32, device="cuda"), 600)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, 2000))
+    zen.zen_aggregate(ctx, [part, part], 0, out2, 2000, ws)
+    st, flags, needed = zen.zen_status_fetch(ctx, ws)
+    assert st == zen.ZEN_ERR_CAPACITY and (flags & 1) and needed == idx.size
+    assert int(out2.count.item()) == idx.size
+    assert np.array_equal(G.u32(guard_idx[:600]), idx[:600])
+    assert torch.all(guard_val[:600] == 2.0)
+    assert torch.all(guard_idx[600:] == -2) and torch.all(guard_val[600:] == 7.0)
