@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the encode + aggregate hot path on one MI355X.
+
+One step = zen_encode_batch over all n workers' dense gradients + zen_aggregate_batch over all n
+servers, inputs resident in HBM.  Prints ONE JSON line with the whole-job gradient throughput, the
+roofline of the dominant kernel (the dense scan) measured with HIP events on the launch stream, and
+the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E vendor peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_inputs(wl, torch):
+    from workloads import worker_sparse
+
+    sparse, grads = [], []
+    for w in range(wl.n_workers):
+        rows, vals = worker_sparse(wl, w)
+        g = torch.zeros((wl.n_rows, wl.row_dim), dtype=torch.float32, device="cuda")
+        g.index_copy_(0, torch.from_numpy(rows.astype(np.int64)).cuda(), torch.from_numpy(vals).cuda())
+        sparse.append((rows, vals))
+        grads.append(g)
+    torch.cuda.synchronize()
+    return sparse, grads
+
+
+def cpu_baseline(wl, sparse, budget_s=20.0):
+    """The oracle as it stands, single-threaded, on a bounded sample: whole workers' encodes, then as
+    many servers' aggregates as fit the budget.  Returns gradient GB/s over the sampled workers."""
+    import oracle
+    from workloads import dense_from_sparse
+
+    oracle.build()
+    t_enc, n_enc, encs = 0.0, 0, []
+    for w in range(wl.n_workers):
+        rows, vals = sparse[w]
+        g = dense_from_sparse(wl, rows, vals)
+        t0 = time.perf_counter()
+        e = oracle.encode(g, wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed)
+        t_enc += time.perf_counter() - t0
+        del g
+        encs.append(e)
+        n_enc += 1
+        if t_enc > budget_s * 0.7 and n_enc >= 1:
+            break
+    # aggregate: server j merges partition j of the sampled workers
+    t_agg, n_agg = 0.0, 0
+    for j in range(wl.n_parts):
+        parts = [(e.indices[e.offsets[j]:e.offsets[j + 1]], e.values[e.offsets[j]:e.offsets[j + 1]]) for e in encs]
+        t0 = time.perf_counter()
+        oracle.aggregate(parts, wl.n_rows, wl.row_dim, want_f64=False)
+        t_agg += time.perf_counter() - t0
+        n_agg += 1
+        if t_agg > budget_s * 0.3:
+            break
+    t_agg_all = t_agg * wl.n_parts / n_agg          # scale the sampled servers to all n servers
+    t = t_enc + t_agg_all
+    gbytes = n_enc * wl.dense_bytes / 1e9
+    return {
+        "value": round(gbytes / t, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "%d of %d workers encoded (%.2f s), %d of %d servers aggregated over those workers "
+                  "(%.2f s, scaled to %d servers); 1 thread" % (n_enc, wl.n_workers, t_enc, n_agg, wl.n_parts,
+                                                                 t_agg, wl.n_parts),
+        "nnz_per_s": round(sum(e.nnz for e in encs) / t, 1),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-times", action="store_true", help="extra untimed pass timing every kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the n workers are n buffers on that GPU); --gpus %d is not "
+            "supported" % args.gpus)
+        return 2
+
+    import torch
+    import paper_2309_13254_amd as zen
+    from workloads import get_workload
+
+    zen.load_library()
+    wl = get_workload(args.config)
+    log("workload %s: R=%d D=%d n=%d  dense %.3f GB/worker" % (wl.name, wl.n_rows, wl.row_dim, wl.n_workers,
+                                                              wl.dense_bytes / 1e9))
+    t0 = time.time()
+    sparse, grads = make_inputs(wl, torch)
+    log("inputs ready in %.1f s" % (time.time() - t0))
+    fmt = zen.ZEN_INDEX_BITMAP if wl.bitmap else zen.ZEN_INDEX_COO
+    ctx = zen.ZenContext(wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed, fmt)
+    n, D = wl.n_parts, wl.row_dim
+    nnz = [r.size for r, _ in sparse]
+    encs = [zen.alloc_encoded(ctx, c, with_indices=not wl.bitmap) for c in nnz]
+    ws_enc = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, wl.n_workers))
+
+    # sizing pass: partition sizes -> bound on the rows entering one server (host logic only)
+    zen.zen_encode_batch(ctx, grads, encs, ws_enc)
+    st, flags, needed = zen.zen_status_fetch(ctx, ws_enc)
+    assert st == 0, (st, flags, needed)
+    offs = np.stack([e.offsets.cpu().numpy().view(np.uint32).astype(np.int64) for e in encs])
+    assert [int(o[-1]) for o in offs] == nnz
+    per_server = np.diff(offs, axis=1).sum(axis=0)
+    max_in = int(per_server.max() * 1.05) + 16
+    aggs = [zen.alloc_aggregated(ctx, max_in) for _ in range(n)]
+    ws_agg = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, n, max_in))
+
+    def step():
+        zen.zen_encode_batch(ctx, grads, encs, ws_enc)
+        zen.zen_aggregate_batch(ctx, encs, aggs, max_in, ws_agg)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert zen.zen_status_fetch(ctx, ws_enc)[0] == 0 and zen.zen_status_fetch(ctx, ws_agg)[0] == 0
+
+    zen.zen_profile_enable(ctx, 1, args.steps + 8)      # HIP events around the dense-scan kernel only
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t = (time.perf_counter() - t0) / args.steps
+    prof = zen.zen_profile_collect(ctx)
+    zen.zen_profile_enable(ctx, 0, 0)
+    det_ms, det_n = prof.get("detect_kernel", (0.0, 0))
+    det_avg_s = det_ms / max(det_n, 1) / 1e3
+
+    U = [int(a.count.item()) for a in aggs]
+    dense_bytes = wl.n_workers * wl.dense_bytes
+    idx_bytes = (wl.n_rows // 8) if wl.bitmap else None
+    enc_out = sum((idx_bytes if wl.bitmap else 4 * c) + 4 * D * c + 4 * (n + 1) for c in nnz)
+    agg_in = sum((idx_bytes if wl.bitmap else 4 * c) + 4 * D * c for c in nnz)
+    agg_out = sum(u * (4 + 4 * D) for u in U)
+    b_alg = dense_bytes + enc_out + agg_in + agg_out
+
+    kernel_ms = None
+    if args.kernel_times:
+        zen.zen_profile_enable(ctx, 2, 64 * 8)
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        kernel_ms = {k: round(v[0] / 5, 4) for k, v in zen.zen_profile_collect(ctx).items()}
+        zen.zen_profile_enable(ctx, 0, 0)
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(wl.name, {}).get("detect_kernel_bytes_per_launch")
+
+    out = {
+        "metric": "encode+aggregate throughput (dense gradient bytes per second, all workers and servers)",
+        "value": round(dense_bytes / t / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "config_id": wl.config_id, "n_rows": wl.n_rows, "row_dim": D,
+                   "n_workers": wl.n_workers, "n_parts": n, "index_format": "bitmap" if wl.bitmap else "coo",
+                   "nnz_total": int(sum(nnz)), "unique_total": int(sum(U)), "max_in_rows": max_in},
+        "nnz_per_s": round(sum(nnz) / t, 1),
+        "algorithmic_bytes": int(b_alg),
+        "hbm_frac_whole_path": round(b_alg / t / (HBM_PEAK_GBS * 1e9), 4),
+        "roofline": {
+            "kernel": "detect_kernel", "bound": "hbm",
+            "achieved": round(dense_bytes / det_avg_s / 1e9, 1) if det_avg_s > 0 else None,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(dense_bytes / det_avg_s / 1e9 / HBM_PEAK_GBS, 4) if det_avg_s > 0 else None,
+            "traffic": traffic,
+            "avg_launch_ms": round(det_avg_s * 1e3, 4), "launches": det_n,
+            "algorithmic_bytes_per_launch": int(dense_bytes),
+        },
+    }
+    if kernel_ms is not None:
+        out["kernel_ms_per_step"] = kernel_ms
+    if not args.no_cpu_baseline:
+        del grads
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(wl, sparse)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

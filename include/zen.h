@@ -167,6 +167,19 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
 zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out,
                          void *hip_stream);
 
+/*
+ * Optional kernel timing with HIP events recorded on the launch stream (for benchmarks; not part of
+ * the method).  mode 0 = off, 1 = time the dense-scan (detect) kernel only, 2 = time every kernel.
+ * max_records event pairs are created up front; launches beyond that are not timed.
+ * zen_profile_collect waits for the recorded events, adds up milliseconds and launch counts per
+ * kernel into host arrays of at least 16 entries (index = kernel id, name from
+ * zen_profile_kernel_name), and empties the record pool.
+ */
+zen_status zen_profile_enable(zen_ctx *ctx, uint32_t mode, uint32_t max_records);
+zen_status zen_profile_collect(zen_ctx *ctx, uint32_t cap, double *host_ms_sum, uint32_t *host_launches,
+                               uint32_t *host_n_kernels);
+const char *zen_profile_kernel_name(uint32_t kernel);
+
 const char *zen_status_str(zen_status s);
 
 #ifdef __cplusplus

@@ -16,6 +16,7 @@ __all__ = [
     "zen_ctx_create", "zen_ctx_destroy", "zen_bitmap_layout", "zen_encode_workspace_bytes",
     "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
     "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
+    "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "alloc_encoded", "alloc_aggregated", "alloc_workspace",
 ]
 
@@ -77,11 +78,15 @@ def load_library():
         "zen_aggregate_batch": [vp, C.POINTER(_Encoded), u32, C.POINTER(_Aggregated), u64, vp, u64, vp],
         "zen_status_fetch": [vp, vp, vp, C.POINTER(_StatusInfo)],
         "zen_hash_many": [vp, u64, u32, vp, vp],
+        "zen_profile_enable": [vp, u32, u32],
+        "zen_profile_collect": [vp, u32, C.POINTER(C.c_double), C.POINTER(u32), C.POINTER(u32)],
     }
     for name, args in sig.items():
         f = getattr(L, name)
         f.argtypes = args
         f.restype = C.c_int
+    L.zen_profile_kernel_name.argtypes = [u32]
+    L.zen_profile_kernel_name.restype = C.c_char_p
     L.zen_status_str.argtypes = [C.c_int]
     L.zen_status_str.restype = C.c_char_p
     _lib = L
@@ -264,3 +269,20 @@ def zen_hash_many(idx, seed, out=None, stream=None):
     _check(load_library().zen_hash_many(idx.data_ptr(), idx.numel(), int(seed) & 0xFFFFFFFF, out.data_ptr(),
                                         _stream(stream)), "zen_hash_many")
     return out
+
+
+def zen_profile_enable(ctx, mode, max_records=4096):
+    return _check(load_library().zen_profile_enable(ctx.handle, int(mode), int(max_records)), "zen_profile_enable")
+
+
+def zen_profile_kernel_name(kernel):
+    return load_library().zen_profile_kernel_name(int(kernel)).decode()
+
+
+def zen_profile_collect(ctx):
+    """-> {kernel name: (total ms, launches)} for the kernels timed since the last collect."""
+    ms = (C.c_double * 16)()
+    cnt = (C.c_uint32 * 16)()
+    n = C.c_uint32()
+    _check(load_library().zen_profile_collect(ctx.handle, 16, ms, cnt, C.byref(n)), "zen_profile_collect")
+    return {zen_profile_kernel_name(k): (float(ms[k]), int(cnt[k])) for k in range(int(n.value)) if cnt[k]}

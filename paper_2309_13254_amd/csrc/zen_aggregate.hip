@@ -419,13 +419,14 @@ AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_ro
         if (e_ != hipSuccess) return e_;           \
     } while (0)
 
-hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx &src,
+hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
                             const Arr64<const float *> &src_values, const Arr64<const uint32_t *> &src_bitmap,
                             uint32_t n_in, uint32_t n_servers, uint32_t first_part_id, const AggOut &outs,
                             const Arr64<float *> &out_values, uint64_t max_in_rows, char *ws,
                             const AggLayout &L, hipStream_t s)
 {
-    (void)ctx; (void)src_bitmap; (void)first_part_id;
+    (void)src_bitmap; (void)first_part_id;
+    const Geometry &g = ctx->geo;
     zen_status_info *status = (zen_status_info *)(ws + L.status_off);
     uint32_t *counters = (uint32_t *)(ws + L.counters_off);
     uint32_t *keys = (uint32_t *)(ws + L.keys_off);
@@ -436,8 +437,11 @@ hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx
     {
         uint64_t blocks = (n_keys + 1023) / 1024;
         if (blocks > 16384) blocks = 16384;
-        agg_clear_kernel<<<(uint32_t)blocks, 256, 0, s>>>(keys, n_keys, counters, n_servers * 16, status);
-        ZEN_LAUNCH_CHECK();
+        {
+            ProfScope prof(ctx, K_AGG_CLEAR, s);
+            agg_clear_kernel<<<(uint32_t)blocks, 256, 0, s>>>(keys, n_keys, counters, n_servers * 16, status);
+            ZEN_LAUNCH_CHECK();
+        }
     }
     // rows per (part, server) are unknown on the host; size the x dimension for an even split of
     // max_in_rows over the parts, grid-stride loops cover any skew
@@ -445,42 +449,63 @@ hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx
     uint32_t gx = (uint32_t)((per_part + AGG_THREADS - 1) / AGG_THREADS);
     if (gx < 1) gx = 1;
     if (gx > 4096) gx = 4096;
-    agg_insert_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, n_in, g.seed, keys, cap, counters,
-                                                                        max_in_rows, status);
-    ZEN_LAUNCH_CHECK();
+    {
+        ProfScope prof(ctx, K_AGG_INSERT, s);
+        agg_insert_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, n_in, g.seed, keys, cap, counters,
+                                                                            max_in_rows, status);
+        ZEN_LAUNCH_CHECK();
+    }
 
     if (L.small_path) {
-        agg_sort_small_kernel<<<n_servers, SORT_SMALL_THREADS, 0, s>>>(g.seed, keys, rank, cap, counters, outs,
-                                                                       status);
-        ZEN_LAUNCH_CHECK();
+        {
+            ProfScope prof(ctx, K_AGG_SORT_SMALL, s);
+            agg_sort_small_kernel<<<n_servers, SORT_SMALL_THREADS, 0, s>>>(g.seed, keys, rank, cap, counters, outs,
+                                                                           status);
+            ZEN_LAUNCH_CHECK();
+        }
     } else {
         uint32_t *uniq = (uint32_t *)(ws + L.uniq_off);
         uint32_t *hist = (uint32_t *)(ws + L.sorthist_off);
         const uint64_t ustride = 2 * L.uniq_cap, hstride = L.sort_blocks * 256;
         uint64_t cblocks = cap / AGG_THREADS;
         if (cblocks > 2048) cblocks = 2048;
-        agg_compact_kernel<<<dim3((uint32_t)cblocks, n_servers), AGG_THREADS, 0, s>>>(keys, cap, uniq, ustride,
-                                                                                     counters);
-        ZEN_LAUNCH_CHECK();
+        {
+            ProfScope prof(ctx, K_AGG_COMPACT, s);
+            agg_compact_kernel<<<dim3((uint32_t)cblocks, n_servers), AGG_THREADS, 0, s>>>(keys, cap, uniq, ustride,
+                                                                                         counters);
+            ZEN_LAUNCH_CHECK();
+        }
         uint32_t key_bits = 1;
         while (key_bits < 32 && (1ull << key_bits) < g.n_rows) ++key_bits;
         uint32_t *a = uniq, *b = uniq + L.uniq_cap;
         for (uint32_t shift = 0; shift < key_bits; shift += 8) {
-            rs_hist_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(a, ustride, counters, shift,
-                                                                                          hist, hstride);
-            ZEN_LAUNCH_CHECK();
-            rs_scan_kernel<<<n_servers, 1024, 0, s>>>(counters, hist, hstride);
-            ZEN_LAUNCH_CHECK();
-            rs_scatter_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(
-                a, b, ustride, counters, shift, hist, hstride);
-            ZEN_LAUNCH_CHECK();
+            {
+                ProfScope prof(ctx, K_RS_HIST, s);
+                rs_hist_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(a, ustride, counters, shift,
+                                                                                              hist, hstride);
+                ZEN_LAUNCH_CHECK();
+            }
+            {
+                ProfScope prof(ctx, K_RS_SCAN, s);
+                rs_scan_kernel<<<n_servers, 1024, 0, s>>>(counters, hist, hstride);
+                ZEN_LAUNCH_CHECK();
+            }
+            {
+                ProfScope prof(ctx, K_RS_SCATTER, s);
+                rs_scatter_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(
+                    a, b, ustride, counters, shift, hist, hstride);
+                ZEN_LAUNCH_CHECK();
+            }
             uint32_t *t = a; a = b; b = t;
         }
         uint64_t fblocks = (L.uniq_cap + AGG_THREADS - 1) / AGG_THREADS;
         if (fblocks > 4096) fblocks = 4096;
-        agg_finalize_kernel<<<dim3((uint32_t)fblocks, n_servers), AGG_THREADS, 0, s>>>(
-            g.seed, a, ustride, keys, rank, cap, counters, outs, status);
-        ZEN_LAUNCH_CHECK();
+        {
+            ProfScope prof(ctx, K_AGG_FINALIZE, s);
+            agg_finalize_kernel<<<dim3((uint32_t)fblocks, n_servers), AGG_THREADS, 0, s>>>(
+                g.seed, a, ustride, keys, rank, cap, counters, outs, status);
+            ZEN_LAUNCH_CHECK();
+        }
     }
 
     {
@@ -489,8 +514,11 @@ hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx
         uint64_t zb = (n_el / 4 + AGG_THREADS - 1) / AGG_THREADS;
         if (zb < 1) zb = 1;
         if (zb > 2048) zb = 2048;
-        agg_zero_kernel<<<dim3((uint32_t)zb, n_servers), AGG_THREADS, 0, s>>>(out_values, outs, g.row_dim, counters);
-        ZEN_LAUNCH_CHECK();
+        {
+            ProfScope prof(ctx, K_AGG_ZERO, s);
+            agg_zero_kernel<<<dim3((uint32_t)zb, n_servers), AGG_THREADS, 0, s>>>(out_values, outs, g.row_dim, counters);
+            ZEN_LAUNCH_CHECK();
+        }
     }
     {
         uint64_t units;   // work units per part: rows (wave per row), rows (D==1), or elements
@@ -499,9 +527,12 @@ hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx
         else units = (per_part * g.row_dim + AGG_THREADS - 1) / AGG_THREADS;
         if (units < 1) units = 1;
         if (units > 8192) units = 8192;
-        agg_accum_kernel<<<dim3((uint32_t)units, n_in, n_servers), AGG_THREADS, 0, s>>>(
-            src, src_values, g.seed, g.row_dim, keys, rank, cap, counters, out_values, outs);
-        ZEN_LAUNCH_CHECK();
+        {
+            ProfScope prof(ctx, K_AGG_ACCUM, s);
+            agg_accum_kernel<<<dim3((uint32_t)units, n_in, n_servers), AGG_THREADS, 0, s>>>(
+                src, src_values, g.seed, g.row_dim, keys, rank, cap, counters, out_values, outs);
+            ZEN_LAUNCH_CHECK();
+        }
     }
     return hipSuccess;
 }

@@ -68,6 +68,8 @@ using namespace zen;
         if (e_ != hipSuccess) return ZEN_ERR_DEVICE;    \
     } while (0)
 
+static void prof_release(zen_ctx *ctx);
+
 extern "C" {
 
 const char *zen_status_str(zen_status s)
@@ -107,6 +109,7 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
 zen_status zen_ctx_destroy(zen_ctx *ctx)
 {
     if (!ctx) return ZEN_OK;
+    prof_release(ctx);
     if (ctx->d_domain) (void)hipFree(ctx->d_domain);
     if (ctx->d_dom_offsets) (void)hipFree(ctx->d_dom_offsets);
     if (ctx->d_dom_tile_base) (void)hipFree(ctx->d_dom_tile_base);
@@ -173,7 +176,6 @@ zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32
     const EncodeLayout L = encode_layout(g, group);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
     char *ws = (char *)workspace;
-    HIP_TRY(launch_fill_u32((uint32_t *)(ws + L.status_off), sizeof(zen_status_info) / 4, 0u, s));
     for (uint32_t w0 = 0; w0 < n_workers; w0 += group) {
         const uint32_t nb = n_workers - w0 < group ? n_workers - w0 : group;
         GradPtrs grads;
@@ -188,9 +190,9 @@ zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32
             outs.bitmap[i] = host_outs[w0 + i].bitmap;
             outs.cap_rows[i] = host_outs[w0 + i].cap_rows;
         }
-        HIP_TRY(launch_detect(g, grads, nb, ws, L, s));
-        HIP_TRY(launch_partition_scan(g, outs, nb, ws, L, s));
-        HIP_TRY(launch_scatter(g, ctx, grads, outs, nb, ws, L, s));
+        HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, s));
+        HIP_TRY(launch_partition_scan(ctx, outs, nb, ws, L, s));
+        HIP_TRY(launch_scatter(ctx, grads, outs, nb, ws, L, s));
     }
     return ZEN_OK;
 }
@@ -218,9 +220,8 @@ zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint6
     GradPtrs grads;
     memset(&grads, 0, sizeof(grads));
     grads.p[0] = grad;
-    HIP_TRY(launch_fill_u32((uint32_t *)(ws + L.status_off), sizeof(zen_status_info) / 4, 0u, s));
-    HIP_TRY(launch_detect(g, grads, 1, ws, L, s));
-    HIP_TRY(launch_nonzero_list(g, indices, cap_rows, count, ws, L, s));
+    HIP_TRY(launch_detect(ctx, grads, 1, ws, L, true, s));
+    HIP_TRY(launch_nonzero_list(ctx, indices, cap_rows, count, ws, L, s));
     return ZEN_OK;
 }
 
@@ -229,7 +230,7 @@ static zen_status run_aggregate(zen_ctx *ctx, const PartIdx &src, const Arr64<co
                                 uint32_t first_part, const AggOut &outs, const Arr64<float *> &out_values,
                                 uint64_t max_in_rows, char *ws, const AggLayout &L, hipStream_t s)
 {
-    HIP_TRY(launch_aggregate(ctx->geo, ctx, src, src_values, src_bitmap, n_in, n_servers, first_part, outs,
+    HIP_TRY(launch_aggregate(ctx, src, src_values, src_bitmap, n_in, n_servers, first_part, outs,
                              out_values, max_in_rows, ws, L, s));
     return ZEN_OK;
 }
@@ -335,6 +336,65 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
     HIP_TRY(hipStreamSynchronize(s));
     if (host_info) *host_info = info;
     return (info.flags & 3u) ? ZEN_ERR_CAPACITY : (info.flags ? ZEN_ERR_INVALID : ZEN_OK);
+}
+
+static const char *const kKernelNames[K_COUNT] = {
+    "detect_kernel", "partition_scan_kernel", "scatter_kernel", "agg_clear_kernel", "agg_insert_kernel",
+    "agg_sort_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
+    "agg_finalize_kernel", "agg_zero_kernel", "agg_accum_kernel", "nonzero_list_kernels", "bitmap_decode_kernel"};
+
+static void prof_release(zen_ctx *ctx)
+{
+    for (uint32_t i = 0; i < ctx->prof_cap; ++i) {
+        (void)hipEventDestroy(ctx->prof[i].start);
+        (void)hipEventDestroy(ctx->prof[i].stop);
+    }
+    free(ctx->prof);
+    ctx->prof = nullptr;
+    ctx->prof_cap = ctx->prof_used = 0;
+    ctx->prof_mode = 0;
+}
+
+zen_status zen_profile_enable(zen_ctx *ctx, uint32_t mode, uint32_t max_records)
+{
+    if (!ctx || mode > 2) return ZEN_ERR_INVALID;
+    prof_release(ctx);
+    if (mode == 0) return ZEN_OK;
+    if (max_records == 0 || max_records > (1u << 20)) return ZEN_ERR_INVALID;
+    ctx->prof = (ProfRecord *)calloc(max_records, sizeof(ProfRecord));
+    if (!ctx->prof) return ZEN_ERR_NOMEM;
+    for (uint32_t i = 0; i < max_records; ++i) {
+        if (hipEventCreate(&ctx->prof[i].start) != hipSuccess || hipEventCreate(&ctx->prof[i].stop) != hipSuccess) {
+            ctx->prof_cap = i;
+            prof_release(ctx);
+            return ZEN_ERR_DEVICE;
+        }
+        ctx->prof_cap = i + 1;
+    }
+    ctx->prof_mode = mode;
+    return ZEN_OK;
+}
+
+zen_status zen_profile_collect(zen_ctx *ctx, uint32_t cap, double *host_ms_sum, uint32_t *host_launches,
+                               uint32_t *host_n_kernels)
+{
+    if (!ctx || !host_ms_sum || !host_launches || cap < K_COUNT) return ZEN_ERR_INVALID;
+    for (uint32_t k = 0; k < K_COUNT; ++k) { host_ms_sum[k] = 0.0; host_launches[k] = 0; }
+    for (uint32_t i = 0; i < ctx->prof_used; ++i) {
+        float ms = 0.f;
+        HIP_TRY(hipEventSynchronize(ctx->prof[i].stop));
+        HIP_TRY(hipEventElapsedTime(&ms, ctx->prof[i].start, ctx->prof[i].stop));
+        host_ms_sum[ctx->prof[i].kernel] += ms;
+        host_launches[ctx->prof[i].kernel] += 1;
+    }
+    ctx->prof_used = 0;
+    if (host_n_kernels) *host_n_kernels = K_COUNT;
+    return ZEN_OK;
+}
+
+const char *zen_profile_kernel_name(uint32_t kernel)
+{
+    return kernel < K_COUNT ? kKernelNames[kernel] : "";
 }
 
 zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, void *hip_stream)

@@ -162,7 +162,7 @@ __device__ __forceinline__ void detect_row(const float *__restrict__ g, uint64_t
 // hist[tile][0..n_parts).
 __global__ void __launch_bounds__(DETECT_THREADS)
 detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
-              uint32_t *hist_base, uint64_t hist_stride_words)
+              uint32_t *hist_base, uint64_t hist_stride_words, zen_status_info *reset_status)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *s_mask = smem;                  // [tile_words]
@@ -171,6 +171,9 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
     const float *__restrict__ grad = grads.p[worker];
     const uint64_t row0 = (uint64_t)tile * g.tile_rows;
 
+    if (reset_status && tile == 0 && worker == 0 && threadIdx.x == 0) {
+        reset_status->flags = 0; reset_status->reserved = 0; reset_status->needed_rows = 0;
+    }
     for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) s_hist[i] = 0;
     if (g.mode == MODE_ROW) {
         for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) s_mask[i] = 0;
@@ -472,30 +475,35 @@ hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, 
     return hipGetLastError();
 }
 
-hipError_t launch_detect(const Geometry &g, const GradPtrs &grads, uint32_t batch, char *ws,
-                         const EncodeLayout &L, hipStream_t s)
+hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
+                         const EncodeLayout &L, bool reset_status, hipStream_t s)
 {
+    const Geometry &g = ctx->geo;
     const size_t lds = (size_t)(g.tile_words + g.n_parts) * 4;
+    ProfScope prof(ctx, K_DETECT, s);
     detect_kernel<<<dim3(g.n_tiles, batch), DETECT_THREADS, lds, s>>>(
         g, grads, (uint32_t *)(ws + L.mask_off), L.mask_stride / 4, (uint32_t *)(ws + L.hist_off),
-        L.hist_stride / 4);
+        L.hist_stride / 4, reset_status ? (zen_status_info *)(ws + L.status_off) : nullptr);
     return hipGetLastError();
 }
 
-hipError_t launch_partition_scan(const Geometry &g, const EncodedPtrs &outs, uint32_t batch, char *ws,
+hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t batch, char *ws,
                                  const EncodeLayout &L, hipStream_t s)
 {
+    const Geometry &g = ctx->geo;
+    ProfScope prof(ctx, K_PARTITION_SCAN, s);
     partition_scan_kernel<<<batch, SCAN_THREADS, 0, s>>>(g, outs, (uint32_t *)(ws + L.hist_off),
                                                          L.hist_stride / 4,
                                                          (zen_status_info *)(ws + L.status_off));
     return hipGetLastError();
 }
 
-hipError_t launch_scatter(const Geometry &g, const zen_ctx *ctx, const GradPtrs &grads,
+hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
                           const EncodedPtrs &outs, uint32_t batch, char *ws, const EncodeLayout &L,
                           hipStream_t s)
 {
-    (void)ctx;
+    const Geometry &g = ctx->geo;
+    ProfScope prof(ctx, K_SCATTER, s);
     const size_t lds = (size_t)(5 * g.n_parts + 2 * SEG_ROWS + 32) * 4;
     scatter_kernel<<<dim3(g.n_tiles, batch), SCATTER_THREADS, lds, s>>>(
         g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
@@ -503,9 +511,11 @@ hipError_t launch_scatter(const Geometry &g, const zen_ctx *ctx, const GradPtrs 
     return hipGetLastError();
 }
 
-hipError_t launch_nonzero_list(const Geometry &g, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
+hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
                                char *ws, const EncodeLayout &L, hipStream_t s)
 {
+    const Geometry &g = ctx->geo;
+    ProfScope prof(ctx, K_NONZERO_LIST, s);
     uint32_t *mask = (uint32_t *)(ws + L.mask_off);
     uint32_t *tile_cnt = (uint32_t *)(ws + L.hist_off);   // reused: n_tiles words fit (n_parts >= 1)
     tile_popcount_kernel<<<g.n_tiles, 256, 0, s>>>(g, mask, tile_cnt);

@@ -81,8 +81,21 @@ struct AggLayout {
 
 } // namespace zen
 
+namespace zen {
+enum KernelId : uint32_t {
+    K_DETECT = 0, K_PARTITION_SCAN, K_SCATTER, K_AGG_CLEAR, K_AGG_INSERT, K_AGG_SORT_SMALL, K_AGG_COMPACT,
+    K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_ZERO, K_AGG_ACCUM, K_NONZERO_LIST, K_BITMAP_DECODE,
+    K_COUNT
+};
+struct ProfRecord { hipEvent_t start, stop; uint32_t kernel; };
+} // namespace zen
+
 struct zen_ctx {
     zen::Geometry geo;
+    // optional per-kernel timing with HIP events on the launch stream
+    uint32_t prof_mode;               // 0 off, 1 detect kernel only, 2 every kernel
+    zen::ProfRecord *prof;            // pool of event pairs
+    uint32_t prof_cap, prof_used;
     zen_index_format fmt;
     int device;
     // hash-bitmap tables (BITMAP contexts only)
@@ -101,19 +114,32 @@ EncodeLayout encode_layout(const Geometry &g, uint32_t batch);
 AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows);
 
 // encode launchers (zen_encode.hip)
-hipError_t launch_detect(const Geometry &g, const GradPtrs &grads, uint32_t batch, char *ws,
-                         const EncodeLayout &L, hipStream_t s);
-hipError_t launch_partition_scan(const Geometry &g, const EncodedPtrs &outs, uint32_t batch, char *ws,
+// Kernel timing: ProfScope records an event pair around a launch when the context asks for it.
+struct ProfScope {
+    zen_ctx *ctx; hipStream_t s; ProfRecord *rec;
+    ProfScope(zen_ctx *c, uint32_t kernel, hipStream_t st) : ctx(c), s(st), rec(nullptr)
+    {
+        if (!c || !c->prof_mode || (c->prof_mode == 1 && kernel != K_DETECT) || c->prof_used >= c->prof_cap) return;
+        rec = &c->prof[c->prof_used++];
+        rec->kernel = kernel;
+        (void)hipEventRecord(rec->start, s);
+    }
+    ~ProfScope() { if (rec) (void)hipEventRecord(rec->stop, s); }
+};
+
+hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
+                         const EncodeLayout &L, bool reset_status, hipStream_t s);
+hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t batch, char *ws,
                                  const EncodeLayout &L, hipStream_t s);
-hipError_t launch_scatter(const Geometry &g, const zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs,
+hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs,
                           uint32_t batch, char *ws, const EncodeLayout &L, hipStream_t s);
-hipError_t launch_nonzero_list(const Geometry &g, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
+hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
                                char *ws, const EncodeLayout &L, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s);
 hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s);
 
 // aggregate launchers (zen_aggregate.hip)
-hipError_t launch_aggregate(const Geometry &g, const zen_ctx *ctx, const PartIdx &src,
+hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
                             const Arr64<const float *> &src_values, const Arr64<const uint32_t *> &src_bitmap,
                             uint32_t n_in, uint32_t n_servers, uint32_t first_part_id, const AggOut &outs,
                             const Arr64<float *> &out_values, uint64_t max_in_rows, char *ws,
