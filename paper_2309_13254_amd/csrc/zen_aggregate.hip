@@ -18,20 +18,66 @@ static constexpr int RS_BLOCK_KEYS = AGG_THREADS * RS_ITEMS;
 
 enum : uint32_t { CNT_UNIQUE = 0, CNT_TOTAL_IN = 1, CNT_SKIP = 2 };
 
-struct PartRange { const uint32_t *idx; uint32_t begin, count; };
+// rows [begin, begin+count) of idx are the part's indices; its values start at row vbegin
+struct PartRange { const uint32_t *idx; uint32_t begin, count, vbegin; };
+
+__device__ __forceinline__ uint32_t part_count(const PartIdx &src, uint32_t w, uint32_t server)
+{
+    if (src.single) return src.bounds[w][0];
+    return src.bounds[w][src.server0 + server + 1] - src.bounds[w][src.server0 + server];
+}
 
 __device__ __forceinline__ PartRange part_range(const PartIdx &src, uint32_t w, uint32_t server)
 {
     PartRange r;
-    if (src.single) {
-        r.begin = 0;
-        r.count = src.bounds[w][0];
+    r.vbegin = src.single ? 0u : src.bounds[w][src.server0 + server];
+    r.count = part_count(src, w, server);
+    if (src.indices[w]) {
+        r.idx = src.indices[w];
+        r.begin = r.vbegin;
     } else {
-        r.begin = src.bounds[w][src.server0 + server];
-        r.count = src.bounds[w][src.server0 + server + 1] - r.begin;
+        // decoded hash-bitmap part: placed after the parts before it in the server's decode area
+        uint32_t pre = 0;
+        for (uint32_t v = 0; v < w; ++v) pre += part_count(src, v, server);
+        r.idx = src.dec_base + (uint64_t)server * src.dec_stride;
+        r.begin = pre;
     }
-    r.idx = src.indices[w];
     return r;
+}
+
+// A0: hash_bitmap_decode (Algorithm 2) of part (w, server): the k-th set bit j of the partition's
+// bitmap is the row domain[dom_offsets[p] + j]; rows come out ascending.  One block per part.
+__global__ void __launch_bounds__(1024)
+bitmap_decode_kernel(PartIdx src, Arr64<const uint32_t *> src_bitmap, uint32_t first_part,
+                     const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *word_off,
+                     uint32_t *dec_base, uint64_t dec_stride, zen_status_info *status)
+{
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t w = blockIdx.x, server = blockIdx.y;
+    if (src.indices[w] || !src_bitmap.v[w]) return;
+    const uint32_t p = first_part + server;
+    const PartRange r = part_range(src, w, server);
+    const uint32_t *bm = src_bitmap.v[w] + (src.single ? 0u : word_off[p]);
+    const uint32_t d0 = dom_offsets[p], n_dom = dom_offsets[p + 1] - d0;
+    const uint32_t n_words = (n_dom + 31) >> 5;
+    uint32_t *dec = dec_base + (uint64_t)server * dec_stride;
+    uint32_t run = 0;
+    for (uint32_t w0 = 0; w0 < n_words; w0 += blockDim.x) {
+        const uint32_t wi = w0 + threadIdx.x;
+        uint32_t word = wi < n_words ? bm[wi] : 0u;
+        uint32_t total;
+        const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &total);
+        uint32_t k = run + pre;
+        while (word) {
+            const uint32_t b = __ffs(word) - 1;
+            word &= word - 1;
+            const uint32_t j = wi * 32 + b;
+            if (j < n_dom && k < r.count && (uint64_t)r.begin + k < dec_stride) dec[r.begin + k] = domain[d0 + j];
+            ++k;
+        }
+        run += total;
+    }
+    if (threadIdx.x == 0 && run != r.count) atomicOr(&status->flags, 4u);   // bitmap and row count disagree
 }
 
 __device__ __forceinline__ uint32_t probe_find(const uint32_t *__restrict__ keys, uint32_t cap_mask,
@@ -70,7 +116,7 @@ agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base
 
     // bound check: the table holds at most max_in_rows keys at load factor <= 1/2
     uint32_t mine = 0;
-    if (threadIdx.x < n_in) mine = part_range(src, threadIdx.x, server).count;
+    if (threadIdx.x < n_in) mine = part_count(src, threadIdx.x, server);
     uint32_t total_in;
     block_exclusive_scan(mine, s_tmp, &total_in);
     if ((uint64_t)total_in > max_in_rows) {
@@ -339,7 +385,7 @@ agg_accum_kernel(PartIdx src, Arr64<const float *> src_values, uint32_t seed, ui
     const uint64_t cap_rows = outs.cap_rows[server];
     float *__restrict__ out = out_values.v[server];
     const PartRange r = part_range(src, w, server);
-    const float *__restrict__ vals = src_values.v[w] + (uint64_t)r.begin * row_dim;
+    const float *__restrict__ vals = src_values.v[w] + (uint64_t)r.vbegin * row_dim;
     const uint32_t D = row_dim;
 
     if (D == 1) {
@@ -350,22 +396,25 @@ agg_accum_kernel(PartIdx src, Arr64<const float *> src_values, uint32_t seed, ui
             const uint32_t u = rank[slot];
             if (u < cap_rows) add_f32(out + u, vals[i]);
         }
-    } else if ((D & 3u) == 0 && D >= 256) {
-        const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
+    } else if (D >= 64) {
+        // one wave per incoming row; lanes cover consecutive elements so that every atomic
+        // instruction touches 256 contiguous bytes
+        const uint32_t lane = lane_id(), nw = blockDim.x >> 6;
         for (uint32_t i = blockIdx.x * nw + (threadIdx.x >> 6); i < r.count; i += gridDim.x * nw) {
             const uint32_t key = r.idx[r.begin + i];
             const uint32_t slot = probe_find(keys, cap_mask, key, seed);
             if (slot == 0xFFFFFFFFu) continue;
             const uint32_t u = rank[slot];
             if (u >= cap_rows) continue;
-            const f32x4 *s4 = (const f32x4 *)(vals + (uint64_t)i * D);
+            const float *__restrict__ src_row = vals + (uint64_t)i * D;
             float *o = out + (uint64_t)u * D;
-            for (uint32_t v = lane; v < V; v += 64) {
-                const f32x4 x = s4[v];
-                add_f32(o + 4 * v + 0, x.x);
-                add_f32(o + 4 * v + 1, x.y);
-                add_f32(o + 4 * v + 2, x.z);
-                add_f32(o + 4 * v + 3, x.w);
+            for (uint32_t e = lane; e < D; e += 64 * 4) {
+                float x[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) x[k] = (e + 64 * k < D) ? src_row[e + 64 * k] : 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (e + 64 * k < D) add_f32(o + e + 64 * k, x[k]);
             }
         }
     } else {
@@ -388,7 +437,7 @@ agg_accum_kernel(PartIdx src, Arr64<const float *> src_values, uint32_t seed, ui
 // ----------------------------------------------------------------------------------------------
 static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
-AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows)
+AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows, bool decode)
 {
     AggLayout L{};
     uint64_t cap = 1024;
@@ -408,6 +457,10 @@ AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_ro
     }
     L.decode_off = off;
     L.decode_stride = 0;
+    if (decode) {
+        L.decode_stride = L.uniq_cap;
+        off += align_up((uint64_t)batch * L.decode_stride * 4, 256);
+    }
     (void)g;
     L.total = off;
     return L;
@@ -425,7 +478,6 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
                             const Arr64<float *> &out_values, uint64_t max_in_rows, char *ws,
                             const AggLayout &L, hipStream_t s)
 {
-    (void)src_bitmap; (void)first_part_id;
     const Geometry &g = ctx->geo;
     zen_status_info *status = (zen_status_info *)(ws + L.status_off);
     uint32_t *counters = (uint32_t *)(ws + L.counters_off);
@@ -442,6 +494,16 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
             agg_clear_kernel<<<(uint32_t)blocks, 256, 0, s>>>(keys, n_keys, counters, n_servers * 16, status);
             ZEN_LAUNCH_CHECK();
         }
+    }
+    bool any_bitmap = false;
+    for (uint32_t w = 0; w < n_in; ++w) any_bitmap |= (src.indices[w] == nullptr);
+    if (any_bitmap) {
+        if (!ctx->d_domain || !L.decode_stride) return hipErrorInvalidValue;
+        ProfScope prof(ctx, K_BITMAP_DECODE, s);
+        bitmap_decode_kernel<<<dim3(n_in, n_servers), 1024, 0, s>>>(
+            src, src_bitmap, first_part_id, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off,
+            (uint32_t *)(ws + L.decode_off), L.decode_stride, status);
+        ZEN_LAUNCH_CHECK();
     }
     // rows per (part, server) are unknown on the host; size the x dimension for an even split of
     // max_in_rows over the parts, grid-stride loops cover any skew
@@ -523,7 +585,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
     {
         uint64_t units;   // work units per part: rows (wave per row), rows (D==1), or elements
         if (g.row_dim == 1) units = (per_part + AGG_THREADS - 1) / AGG_THREADS;
-        else if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) units = (per_part + 3) / 4;
+        else if (g.row_dim >= 64) units = (per_part + 3) / 4;
         else units = (per_part * g.row_dim + AGG_THREADS - 1) / AGG_THREADS;
         if (units < 1) units = 1;
         if (units > 8192) units = 8192;

@@ -99,8 +99,49 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
     ctx->fmt = fmt;
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return ZEN_ERR_DEVICE; }
     if (fmt == ZEN_INDEX_BITMAP) {
-        delete ctx;
-        return ZEN_ERR_INVALID;   // hash-bitmap tables: not built yet
+        // sorted hash domains, per-row ranks and per-tile rank bases, built once on the device
+        const Geometry &g = ctx->geo;
+        const uint32_t n = g.n_parts;
+        uint32_t *tmp_mask = nullptr;
+        zen_status_info *tmp_status = nullptr;
+        uint32_t *h_off = (uint32_t *)malloc((n + 1) * sizeof(uint32_t));
+        uint32_t *h_woff32 = (uint32_t *)malloc((n + 1) * sizeof(uint32_t));
+        ctx->h_bm_word_off = (uint64_t *)malloc((n + 1) * sizeof(uint64_t));
+        ctx->h_dom_sizes = (uint64_t *)malloc(n * sizeof(uint64_t));
+        bool ok = h_off && h_woff32 && ctx->h_bm_word_off && ctx->h_dom_sizes;
+        ok = ok && hipMalloc(&ctx->d_domain, n_rows * 4) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->d_rank, n_rows * 4) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->d_dom_offsets, (n + 1) * 4) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->d_bm_word_off, (n + 1) * 4) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->d_dom_tile_base, ((uint64_t)g.n_tiles + 1) * n * 4) == hipSuccess;
+        ok = ok && hipMalloc(&tmp_mask, (uint64_t)g.n_tiles * g.tile_words * 4) == hipSuccess;
+        ok = ok && hipMalloc(&tmp_status, 256) == hipSuccess;
+        zen_status st = ok ? ZEN_OK : ZEN_ERR_NOMEM;
+        if (ok) {
+            if (build_domain_tables(ctx, tmp_mask, tmp_status, nullptr) != hipSuccess ||
+                hipMemcpy(h_off, ctx->d_dom_offsets, (n + 1) * 4, hipMemcpyDeviceToHost) != hipSuccess)
+                st = ZEN_ERR_DEVICE;
+        }
+        if (st == ZEN_OK) {
+            uint64_t w = 0;
+            for (uint32_t p = 0; p < n; ++p) {
+                ctx->h_bm_word_off[p] = w;
+                h_woff32[p] = (uint32_t)w;
+                ctx->h_dom_sizes[p] = h_off[p + 1] - h_off[p];
+                w += (ctx->h_dom_sizes[p] + 31) / 32;
+            }
+            ctx->h_bm_word_off[n] = w;
+            h_woff32[n] = (uint32_t)w;
+            ctx->bm_total_words = w;
+            if (h_off[n] != n_rows) st = ZEN_ERR_DEVICE;
+            else if (hipMemcpy(ctx->d_bm_word_off, h_woff32, (n + 1) * 4, hipMemcpyHostToDevice) != hipSuccess)
+                st = ZEN_ERR_DEVICE;
+        }
+        if (tmp_mask) (void)hipFree(tmp_mask);
+        if (tmp_status) (void)hipFree(tmp_status);
+        free(h_off);
+        free(h_woff32);
+        if (st != ZEN_OK) { zen_ctx_destroy(ctx); return st; }
     }
     *out = ctx;
     return ZEN_OK;
@@ -111,6 +152,7 @@ zen_status zen_ctx_destroy(zen_ctx *ctx)
     if (!ctx) return ZEN_OK;
     prof_release(ctx);
     if (ctx->d_domain) (void)hipFree(ctx->d_domain);
+    if (ctx->d_rank) (void)hipFree(ctx->d_rank);
     if (ctx->d_dom_offsets) (void)hipFree(ctx->d_dom_offsets);
     if (ctx->d_dom_tile_base) (void)hipFree(ctx->d_dom_tile_base);
     if (ctx->d_bm_word_off) (void)hipFree(ctx->d_bm_word_off);
@@ -143,7 +185,7 @@ zen_status zen_aggregate_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uin
 {
     if (!ctx || !host_bytes || batch == 0 || max_in_rows > 0x7FFFFFFFull) return ZEN_ERR_INVALID;
     const uint32_t b = batch > ZEN_MAX_BATCH ? ZEN_MAX_BATCH : batch;
-    *host_bytes = aggregate_layout(ctx->geo, b, max_in_rows).total;
+    *host_bytes = aggregate_layout(ctx->geo, b, max_in_rows, ctx->fmt == ZEN_INDEX_BITMAP).total;
     return ZEN_OK;
 }
 
@@ -225,11 +267,13 @@ zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint6
     return ZEN_OK;
 }
 
-static zen_status run_aggregate(zen_ctx *ctx, const PartIdx &src, const Arr64<const float *> &src_values,
+static zen_status run_aggregate(zen_ctx *ctx, PartIdx src, const Arr64<const float *> &src_values,
                                 const Arr64<const uint32_t *> &src_bitmap, uint32_t n_in, uint32_t n_servers,
                                 uint32_t first_part, const AggOut &outs, const Arr64<float *> &out_values,
                                 uint64_t max_in_rows, char *ws, const AggLayout &L, hipStream_t s)
 {
+    src.dec_base = L.decode_stride ? (const uint32_t *)(ws + L.decode_off) : nullptr;
+    src.dec_stride = L.decode_stride;
     HIP_TRY(launch_aggregate(ctx, src, src_values, src_bitmap, n_in, n_servers, first_part, outs,
                              out_values, max_in_rows, ws, L, s));
     return ZEN_OK;
@@ -264,8 +308,8 @@ zen_status zen_aggregate(zen_ctx *ctx, const zen_part *host_parts, uint32_t n_in
         sv.v[w] = p.values;
         sb.v[w] = p.indices ? nullptr : p.bitmap;
     }
-    if (any_bitmap) return ZEN_ERR_INVALID;   // bitmap parts: not built yet
-    const AggLayout L = aggregate_layout(ctx->geo, 1, max_in_rows);
+    if (any_bitmap && ctx->fmt != ZEN_INDEX_BITMAP) return ZEN_ERR_INVALID;   // no domain tables
+    const AggLayout L = aggregate_layout(ctx->geo, 1, max_in_rows, ctx->fmt == ZEN_INDEX_BITMAP);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
     AggOut outs;
     Arr64<float *> ov;
@@ -287,7 +331,6 @@ zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint3
     if (n_workers > ZEN_MAX_BATCH || max_in_rows > 0x7FFFFFFFull || ((uintptr_t)workspace & 255u))
         return ZEN_ERR_INVALID;
     const Geometry &g = ctx->geo;
-    if (ctx->fmt == ZEN_INDEX_BITMAP) return ZEN_ERR_INVALID;   // bitmap parts: not built yet
     PartIdx src;
     Arr64<const float *> sv;
     Arr64<const uint32_t *> sb;
@@ -297,7 +340,7 @@ zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint3
     for (uint32_t w = 0; w < n_workers; ++w) {
         zen_status st = check_encoded(ctx, host_encs[w]);
         if (st != ZEN_OK) return st;
-        src.indices[w] = host_encs[w].indices;
+        src.indices[w] = ctx->fmt == ZEN_INDEX_BITMAP ? nullptr : host_encs[w].indices;   // BITMAP: decode
         src.bounds[w] = host_encs[w].offsets;
         sv.v[w] = host_encs[w].values;
         sb.v[w] = host_encs[w].bitmap;
@@ -308,7 +351,7 @@ zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint3
             return ZEN_ERR_INVALID;
     }
     const uint32_t group = g.n_parts < ZEN_MAX_BATCH ? g.n_parts : ZEN_MAX_BATCH;
-    const AggLayout L = aggregate_layout(g, group, max_in_rows);
+    const AggLayout L = aggregate_layout(g, group, max_in_rows, ctx->fmt == ZEN_INDEX_BITMAP);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
     if (g.n_parts > ZEN_MAX_BATCH) return ZEN_ERR_INVALID;   // one launch group per call for now
     AggOut outs;

@@ -5,6 +5,7 @@
 // rows.  The dense gradient is read exactly once, by the detect kernel, with 16-byte loads; all
 // later steps work from the 1-bit-per-row mask and touch the dense data only to copy non-zero rows.
 #include "zen_device.h"
+#include <string.h>
 #include "zen_internal.h"
 
 namespace zen {
@@ -273,109 +274,181 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
 }
 
 // ----------------------------------------------------------------------------------------------
-// E5 + E6 (+E7): one block per (tile, worker).  Walks the tile's mask in segments, expands the set
-// bits to an ascending row list in LDS, ranks every row stably inside its partition, writes the
-// index, and copies the row's values.
+// E5 + E6 (+E7): blocks walk (tile, worker) pairs.  For every non-empty tile: expand the mask in
+// segments to an ascending row list in LDS, rank every row stably inside its partition, write the
+// index, copy the row's values, and (hash-bitmap format) set the row's bit.
+//
+// Hash bitmap (Algorithm 2, hash_bitmap_encode): bit rank[row] of partition p, where rank[row] is
+// the row's position in the sorted domain II_p.  The bits of one (tile, partition) are contiguous
+// -- [tile_base[tile][p], tile_base[tile+1][p]) -- so they are assembled in LDS and flushed with
+// plain stores; only the first / last word of a range can be shared with a neighbouring tile and
+// goes out with atomicOr.  The bitmap must be zero before the kernel runs.
 // ----------------------------------------------------------------------------------------------
+struct BitmapTables {
+    const uint32_t *rank;       // [n_rows]
+    const uint32_t *tile_base;  // [n_tiles+1][n_parts]
+    const uint32_t *word_off;   // [n_parts+1]
+};
+
 __global__ void __launch_bounds__(SCATTER_THREADS)
 scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
-               uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words)
+               uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
+               BitmapTables bt)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t *s_run = smem;                          // [n_parts]
-    uint32_t *s_cnt = s_run + g.n_parts;             // [4][n_parts]
-    uint32_t *s_list = s_cnt + 4 * g.n_parts;        // [SEG_ROWS] tile-relative... absolute row ids
-    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS]
-    uint32_t *s_tmp = s_pos + SEG_ROWS;              // [32]
-    const uint32_t tile = blockIdx.x, worker = blockIdx.y;
     const uint32_t n = g.n_parts, D = g.row_dim;
+    uint32_t *s_run = smem;                          // [n]
+    uint32_t *s_cnt = s_run + n;                     // [4][n]
+    uint32_t *s_list = s_cnt + 4 * n;                // [SEG_ROWS] row ids of the segment, ascending
+    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row
+    uint32_t *s_tmp = s_pos + SEG_ROWS;              // [32]
+    uint32_t *s_b0 = s_tmp + 32;                     // bitmap only: [n] first bit of (tile, p)
+    uint32_t *s_b1 = s_b0 + n;                       //              [n] end bit of (tile, p)
+    uint32_t *s_boff = s_b1 + n;                     //              [n+1] LDS word offset of p's range
+    uint32_t *s_bm = s_boff + n + 1;                 //              [tile_words + 2n] assembled words
+    const uint32_t worker = blockIdx.y;
     const float *__restrict__ grad = grads.p[worker];
-    const uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
-    const uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * n;
     uint32_t *__restrict__ out_idx = outs.indices[worker];
     float *__restrict__ out_val = outs.values[worker];
+    uint32_t *__restrict__ out_bm = outs.bitmap[worker];
     const uint64_t cap = outs.cap_rows[worker];
-    const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+    const bool bitmap = g.bitmap && out_bm != nullptr;
 
-    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_run[i] = ghist[i];
     for (uint32_t i = threadIdx.x; i < 4 * n; i += blockDim.x) s_cnt[i] = 0;
 
-    for (uint32_t w0 = 0; w0 < g.tile_words; w0 += SEG_WORDS) {
-        // (a) expand up to 64 mask words into the ascending row list
-        uint32_t word = 0;
-        if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words) word = gmask[w0 + threadIdx.x];
-        uint32_t total;
-        const uint32_t pre = block_exclusive_scan(threadIdx.x < SEG_WORDS ? __popc(word) : 0u, s_tmp, &total);
-        if (total == 0) continue;   // uniform: total comes from LDS
-        if (threadIdx.x < SEG_WORDS) {
-            uint32_t k = pre;
-            const uint32_t rbase = (uint32_t)(row0 + (uint64_t)(w0 + threadIdx.x) * 32);
-            while (word) {
-                const uint32_t b = __ffs(word) - 1;
-                word &= word - 1;
-                s_list[k++] = rbase + b;
+    for (uint32_t tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
+        const uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
+        uint32_t any = 0;
+        for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= gmask[i];
+        if (!__syncthreads_or((int)(any != 0))) continue;     // empty tile (also the barrier between tiles)
+
+        const uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * n;
+        const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_run[i] = ghist[i];
+
+        uint32_t bm_words = 0;
+        if (bitmap) {
+            // per-partition bit ranges of this tile and their LDS placement
+            const uint32_t *tb0 = bt.tile_base + (uint64_t)tile * n, *tb1 = tb0 + n;
+            const uint32_t per = (n + blockDim.x - 1) / blockDim.x;   // consecutive partitions per thread
+            const uint32_t p0 = min(threadIdx.x * per, n), p1 = min(p0 + per, n);
+            uint32_t mine = 0;
+            for (uint32_t p = p0; p < p1; ++p) {
+                const uint32_t b0 = tb0[p], b1 = tb1[p];
+                s_b0[p] = b0;
+                s_b1[p] = b1;
+                mine += b1 > b0 ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0;
             }
+            uint32_t off = block_exclusive_scan(mine, s_tmp, &bm_words);
+            for (uint32_t p = p0; p < p1; ++p) {
+                const uint32_t b0 = s_b0[p], b1 = s_b1[p];
+                s_boff[p] = off;
+                off += b1 > b0 ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0;
+            }
+            if (threadIdx.x == 0) s_boff[n] = bm_words;
+            for (uint32_t i = threadIdx.x; i < bm_words; i += blockDim.x) s_bm[i] = 0;
         }
-        __syncthreads();
-        // (b) rank and write indices
-        for (uint32_t c = 0; c < total; c += blockDim.x) {
-            const uint32_t i = c + threadIdx.x;
-            const bool valid = i < total;
-            const uint32_t row = valid ? s_list[i] : 0u;
-            const uint32_t p = valid ? owner_of(row, g.seed, n, g.pow2_mask) : 0u;
-            const uint32_t pos = block_stable_rank(valid, p, g.part_bits, n, s_run, s_cnt);
-            if (valid) {
-                if (pos < cap) {
-                    if (out_idx) out_idx[pos] = row;
-                    if (D == 1) out_val[pos] = grad[row];
-                    s_pos[i] = pos;
-                } else {
-                    s_pos[i] = 0xFFFFFFFFu;
+
+        for (uint32_t w0 = 0; w0 < g.tile_words; w0 += SEG_WORDS) {
+            // (a) expand up to 64 mask words into the ascending row list
+            uint32_t word = 0;
+            if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words) word = gmask[w0 + threadIdx.x];
+            uint32_t total;
+            const uint32_t pre = block_exclusive_scan(threadIdx.x < SEG_WORDS ? __popc(word) : 0u, s_tmp, &total);
+            if (total == 0) continue;   // uniform: total comes from LDS
+            if (threadIdx.x < SEG_WORDS) {
+                uint32_t k = pre;
+                const uint32_t rbase = (uint32_t)(row0 + (uint64_t)(w0 + threadIdx.x) * 32);
+                while (word) {
+                    const uint32_t b = __ffs(word) - 1;
+                    word &= word - 1;
+                    s_list[k++] = rbase + b;
                 }
             }
-        }
-        // (c) copy rows (row_dim > 1)
-        if (D > 1) {
             __syncthreads();
-            if ((D & 3u) == 0 && D >= 256) {
-                // one wave per row, 16-byte vectors
-                const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
-                for (uint32_t i = threadIdx.x >> 6; i < total; i += nw) {
-                    const uint32_t pos = s_pos[i];
-                    if (pos == 0xFFFFFFFFu) continue;
-                    const u32x4 *src = (const u32x4 *)(grad + (uint64_t)s_list[i] * D);
-                    u32x4 *dst = (u32x4 *)(out_val + (uint64_t)pos * D);
-                    for (uint32_t v = lane; v < V; v += 64 * 4) {
-                        u32x4 x[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            if (v + 64 * u < V) x[u] = src[v + 64 * u];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            if (v + 64 * u < V) dst[v + 64 * u] = x[u];
+            // (b) rank, write indices, set bitmap bits
+            for (uint32_t c = 0; c < total; c += blockDim.x) {
+                const uint32_t i = c + threadIdx.x;
+                const bool valid = i < total;
+                const uint32_t row = valid ? s_list[i] : 0u;
+                const uint32_t p = valid ? owner_of(row, g.seed, n, g.pow2_mask) : 0u;
+                const uint32_t pos = block_stable_rank(valid, p, g.part_bits, n, s_run, s_cnt);
+                if (valid) {
+                    if (pos < cap) {
+                        if (out_idx) out_idx[pos] = row;
+                        if (D == 1 && out_val) out_val[pos] = grad[row];
+                        s_pos[i] = pos;
+                    } else {
+                        s_pos[i] = 0xFFFFFFFFu;
                     }
-                }
-            } else if ((D & 3u) == 0) {
-                const uint32_t V = D >> 2;
-                const uint32_t n_vec = total * V;           // total <= 2048, V < 64
-                for (uint32_t f = threadIdx.x; f < n_vec; f += blockDim.x) {
-                    const uint32_t i = f / V, v = f - i * V;
-                    const uint32_t pos = s_pos[i];
-                    if (pos != 0xFFFFFFFFu) {
-                        const u32x4 x = ((const u32x4 *)(grad + (uint64_t)s_list[i] * D))[v];
-                        ((u32x4 *)(out_val + (uint64_t)pos * D))[v] = x;
+                    if (bitmap) {
+                        const uint32_t bit = bt.rank[row];
+                        atomicOr(&s_bm[s_boff[p] + (bit >> 5) - (s_b0[p] >> 5)], 1u << (bit & 31));
                     }
-                }
-            } else {
-                const uint32_t n_el = total * D;            // total <= 2048, row_dim <= 2^20
-                for (uint32_t f = threadIdx.x; f < n_el; f += blockDim.x) {
-                    const uint32_t i = f / D, v = f - i * D;
-                    const uint32_t pos = s_pos[i];
-                    if (pos != 0xFFFFFFFFu) out_val[(uint64_t)pos * D + v] = grad[(uint64_t)s_list[i] * D + v];
                 }
             }
+            // (c) copy rows (row_dim > 1)
+            if (D > 1 && out_val) {
+                __syncthreads();
+                if ((D & 3u) == 0 && D >= 256) {
+                    // one wave per row, 16-byte vectors
+                    const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
+                    for (uint32_t i = threadIdx.x >> 6; i < total; i += nw) {
+                        const uint32_t pos = s_pos[i];
+                        if (pos == 0xFFFFFFFFu) continue;
+                        const u32x4 *src = (const u32x4 *)(grad + (uint64_t)s_list[i] * D);
+                        u32x4 *dst = (u32x4 *)(out_val + (uint64_t)pos * D);
+                        for (uint32_t v = lane; v < V; v += 64 * 4) {
+                            u32x4 x[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u)
+                                if (v + 64 * u < V) x[u] = src[v + 64 * u];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u)
+                                if (v + 64 * u < V) dst[v + 64 * u] = x[u];
+                        }
+                    }
+                } else if ((D & 3u) == 0) {
+                    const uint32_t V = D >> 2;
+                    const uint32_t n_vec = total * V;           // total <= 2048, V < 64
+                    for (uint32_t f = threadIdx.x; f < n_vec; f += blockDim.x) {
+                        const uint32_t i = f / V, v = f - i * V;
+                        const uint32_t pos = s_pos[i];
+                        if (pos != 0xFFFFFFFFu) {
+                            const u32x4 x = ((const u32x4 *)(grad + (uint64_t)s_list[i] * D))[v];
+                            ((u32x4 *)(out_val + (uint64_t)pos * D))[v] = x;
+                        }
+                    }
+                } else {
+                    const uint32_t n_el = total * D;            // total <= 2048, row_dim <= 2^20
+                    for (uint32_t f = threadIdx.x; f < n_el; f += blockDim.x) {
+                        const uint32_t i = f / D, v = f - i * D;
+                        const uint32_t pos = s_pos[i];
+                        if (pos != 0xFFFFFFFFu) out_val[(uint64_t)pos * D + v] = grad[(uint64_t)s_list[i] * D + v];
+                    }
+                }
+            }
+            __syncthreads();   // s_list / s_pos are rewritten by the next segment
         }
-        __syncthreads();   // s_list / s_pos are rewritten by the next segment
+
+        if (bitmap) {
+            __syncthreads();
+            for (uint32_t lw = threadIdx.x; lw < bm_words; lw += blockDim.x) {
+                const uint32_t v = s_bm[lw];
+                if (!v) continue;
+                // partition whose LDS range holds lw: last p with s_boff[p] <= lw
+                uint32_t lo = 0, hi = n;
+                while (hi - lo > 1) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (s_boff[mid] <= lw) lo = mid; else hi = mid;
+                }
+                const uint32_t p = lo, b0 = s_b0[p], b1 = s_b1[p];
+                const uint32_t k = lw - s_boff[p], last = ((b1 - 1) >> 5) - (b0 >> 5);
+                uint32_t *dst = out_bm + bt.word_off[p] + (b0 >> 5) + k;
+                const bool shared = (k == 0 && (b0 & 31u)) || (k == last && (b1 & 31u));
+                if (shared) atomicOr(dst, v); else *dst = v;
+            }
+        }
     }
 }
 
@@ -498,16 +571,122 @@ hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t
     return hipGetLastError();
 }
 
+static uint32_t scatter_grid_x(const Geometry &g, uint32_t batch)
+{
+    uint32_t gx = 4096 / (batch ? batch : 1);
+    if (gx < 64) gx = 64;
+    return gx < g.n_tiles ? gx : g.n_tiles;
+}
+
 hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
                           const EncodedPtrs &outs, uint32_t batch, char *ws, const EncodeLayout &L,
                           hipStream_t s)
 {
     const Geometry &g = ctx->geo;
+    BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off};
+    if (g.bitmap) {
+        // the bitmap is assembled with OR: clear it first (a fill kernel, not a memset node)
+        for (uint32_t w = 0; w < batch; ++w) {
+            if (!outs.bitmap[w]) continue;
+            hipError_t e = launch_fill_u32(outs.bitmap[w], ctx->bm_total_words, 0u, s);
+            if (e != hipSuccess) return e;
+        }
+    }
     ProfScope prof(ctx, K_SCATTER, s);
-    const size_t lds = (size_t)(5 * g.n_parts + 2 * SEG_ROWS + 32) * 4;
-    scatter_kernel<<<dim3(g.n_tiles, batch), SCATTER_THREADS, lds, s>>>(
+    size_t words = 5 * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
+    if (g.bitmap) words += 3 * (size_t)g.n_parts + 1 + g.tile_words + 2 * (size_t)g.n_parts;
+    scatter_kernel<<<dim3(scatter_grid_x(g, batch), batch), SCATTER_THREADS, words * 4, s>>>(
         g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
-        (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4);
+        (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// Hash-domain tables of a BITMAP context ("computed and sorted offline", section "Hash Bitmap"):
+// the domains are the partition of ALL rows by h0, i.e. the encode pipeline run on an all-ones mask.
+// ----------------------------------------------------------------------------------------------
+__global__ void ones_mask_kernel(uint32_t *mask, uint64_t n_words, uint64_t n_rows)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t r0 = i * 32;
+        uint32_t w = 0;
+        if (r0 + 32 <= n_rows) w = 0xFFFFFFFFu;
+        else if (r0 < n_rows) w = (1u << (uint32_t)(n_rows - r0)) - 1u;
+        mask[i] = w;
+    }
+}
+
+__global__ void __launch_bounds__(DETECT_THREADS)
+hist_from_mask_kernel(Geometry g, const uint32_t *mask, uint32_t *hist)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *s_hist = smem;
+    const uint32_t tile = blockIdx.x;
+    const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+    for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) s_hist[i] = 0;
+    __syncthreads();
+    const uint32_t *m = mask + (uint64_t)tile * g.tile_words;
+    for (uint32_t r = threadIdx.x; r < g.tile_rows; r += blockDim.x)
+        if ((m[r >> 5] >> (r & 31)) & 1u)
+            atomicAdd(&s_hist[owner_of((uint32_t)(row0 + r), g.seed, g.n_parts, g.pow2_mask)], 1u);
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) hist[(uint64_t)tile * g.n_parts + i] = s_hist[i];
+}
+
+// rank[domain[pos]] = pos - dom_offsets[owner]
+__global__ void domain_rank_kernel(Geometry g, const uint32_t *domain, const uint32_t *dom_offsets, uint32_t *rank)
+{
+    for (uint64_t pos = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; pos < g.n_rows;
+         pos += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t idx = domain[pos];
+        const uint32_t p = owner_of(idx, g.seed, g.n_parts, g.pow2_mask);
+        rank[idx] = (uint32_t)pos - dom_offsets[p];
+    }
+}
+
+// tile_base[t][p]: output position -> position inside the domain; row n_tiles = domain sizes
+__global__ void tile_base_fix_kernel(Geometry g, uint32_t *tile_base, const uint32_t *dom_offsets)
+{
+    const uint64_t total = ((uint64_t)g.n_tiles + 1) * g.n_parts;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t p = (uint32_t)(i % g.n_parts);
+        const uint64_t t = i / g.n_parts;
+        if (t == g.n_tiles) tile_base[i] = dom_offsets[p + 1] - dom_offsets[p];
+        else tile_base[i] -= dom_offsets[p];
+    }
+}
+
+hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info *tmp_status, hipStream_t s)
+{
+    Geometry g = ctx->geo;
+    g.row_dim = 1;      // indices only: the scatter copies no values
+    g.bitmap = 0;
+    const uint64_t n_words = (uint64_t)g.n_tiles * g.tile_words;
+    ones_mask_kernel<<<(uint32_t)((n_words + 255) / 256 > 65535 ? 65535 : (n_words + 255) / 256), 256, 0, s>>>(
+        tmp_mask, n_words, g.n_rows);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hist_from_mask_kernel<<<g.n_tiles, DETECT_THREADS, g.n_parts * 4, s>>>(g, tmp_mask, ctx->d_dom_tile_base);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    EncodedPtrs outs;
+    memset(&outs, 0, sizeof(outs));
+    outs.offsets[0] = ctx->d_dom_offsets;
+    outs.indices[0] = ctx->d_domain;
+    outs.cap_rows[0] = g.n_rows;
+    partition_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(g, outs, ctx->d_dom_tile_base, 0, tmp_status);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    GradPtrs grads;
+    memset(&grads, 0, sizeof(grads));
+    BitmapTables bt{nullptr, nullptr, nullptr};
+    const size_t words = 5 * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
+    scatter_kernel<<<dim3(scatter_grid_x(g, 1), 1), SCATTER_THREADS, words * 4, s>>>(
+        g, grads, outs, tmp_mask, 0, ctx->d_dom_tile_base, 0, bt);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    domain_rank_kernel<<<4096, 256, 0, s>>>(g, ctx->d_domain, ctx->d_dom_offsets, ctx->d_rank);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    tile_base_fix_kernel<<<1024, 256, 0, s>>>(g, ctx->d_dom_tile_base, ctx->d_dom_offsets);
     return hipGetLastError();
 }
 

@@ -56,6 +56,9 @@ struct PartIdx {
     const uint32_t *bounds[ZEN_MAX_BATCH];
     uint32_t single;
     uint32_t server0;   // batch form: first server (partition id) handled by this launch group
+    // parts given as hash bitmaps (indices[w] == NULL) are decoded into dec_base[server*dec_stride + ...]
+    const uint32_t *dec_base;
+    uint64_t dec_stride;
 };
 struct AggOut {
     uint32_t *indices[ZEN_MAX_BATCH];
@@ -101,7 +104,8 @@ struct zen_ctx {
     // hash-bitmap tables (BITMAP contexts only)
     uint32_t *d_domain;        // [n_rows] sorted domains, partition-major
     uint32_t *d_dom_offsets;   // [n_parts+1] start of each domain in d_domain
-    uint32_t *d_dom_tile_base; // [n_tiles][n_parts] rank of the first row of each tile in each domain
+    uint32_t *d_rank;          // [n_rows] position of every row inside its domain
+    uint32_t *d_dom_tile_base; // [n_tiles+1][n_parts] rank of the first row of each tile in each domain
     uint32_t *d_bm_word_off;   // [n_parts+1] first bitmap word of each partition
     uint64_t *h_bm_word_off;   // host copy
     uint64_t *h_dom_sizes;     // host copy
@@ -111,7 +115,7 @@ struct zen_ctx {
 namespace zen {
 
 EncodeLayout encode_layout(const Geometry &g, uint32_t batch);
-AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows);
+AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows, bool decode);
 
 // encode launchers (zen_encode.hip)
 // Kernel timing: ProfScope records an event pair around a launch when the context asks for it.
@@ -135,6 +139,7 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs
                           uint32_t batch, char *ws, const EncodeLayout &L, hipStream_t s);
 hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
                                char *ws, const EncodeLayout &L, hipStream_t s);
+hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info *tmp_status, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s);
 hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s);
 

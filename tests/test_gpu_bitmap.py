@@ -1,0 +1,133 @@
+"""GPU parity of the hash-bitmap index format (Algorithm 2) against the CPU oracle: layout, encode
+(bit-exact bitmap words), decode inside zen_aggregate, and the clustered-runs workload."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import MINI_WORKLOADS, Workload, worker_sparse, dense_from_sparse
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def zen():
+    import paper_2309_13254_amd as z
+
+    z.load_library()
+    return z
+
+
+def _ref_bitmap(oracle, wl, rows):
+    owner = oracle.owner_table(wl.n_rows, wl.n_parts, wl.hash_seed)
+    dom_count, word_off = oracle.bitmap_layout(owner, wl.n_parts)
+    nz = np.zeros(wl.n_rows, np.uint8)
+    nz[rows] = 1
+    return owner, dom_count, word_off, oracle.bitmap_encode(owner, wl.n_parts, nz, word_off)
+
+
+SHAPES = [(1, 1, 1), (33, 1, 3), (5000, 1, 4), (70001, 1, 64), (300000, 1, 100), (4099, 8, 16), (9001, 64, 16),
+          (333, 256, 8), (97, 1024, 8), (5000, 1, 1024), (40000, 4, 1000)]
+
+
+@pytest.mark.parametrize("R,D,n", SHAPES)
+def test_bitmap_layout_and_encode(oracle, zen, R, D, n):
+    import gpu_util as G
+
+    rng = np.random.default_rng(R + 13 * D + n)
+    wl = Workload("t", 0, R, D, n, int(rng.integers(0, 2**32)), "uniform")
+    ctx = zen.ZenContext(R, D, n, wl.hash_seed, zen.ZEN_INDEX_BITMAP)
+    total, woff, dsz = zen.zen_bitmap_layout(ctx)
+    owner = oracle.owner_table(R, n, wl.hash_seed)
+    dom_count, word_off = oracle.bitmap_layout(owner, n)
+    assert dsz == dom_count.tolist() and woff == word_off.tolist() and total == int(word_off[-1])
+    hosts, rowsets = [], []
+    for density in (0.0, 0.04, 0.6, 1.0):
+        rows = np.flatnonzero(rng.random(R) < density).astype(np.uint32)
+        vals = rng.standard_normal((rows.size, D)).astype(np.float32) + 4.0
+        hosts.append(dense_from_sparse(wl, rows, vals))
+        rowsets.append(rows)
+    grads = [torch.from_numpy(h).cuda() for h in hosts]
+    outs, (st, flags, _) = G.run_encode_batch(ctx, grads, [R] * len(grads))
+    assert st == 0 and flags == 0
+    for h, rows, enc in zip(hosts, rowsets, outs):
+        ref = oracle.encode(h, R, D, n, wl.hash_seed)
+        nz = np.zeros(R, np.uint8)
+        nz[rows] = 1
+        ref_bm = oracle.bitmap_encode(owner, n, nz, word_off)
+        assert np.array_equal(G.u32(enc.offsets), ref.offsets)
+        assert np.array_equal(G.u32(enc.bitmap[:total]), ref_bm)
+        assert np.array_equal(G.u32(enc.indices[:ref.nnz]), ref.indices)
+        assert np.array_equal(enc.values[:ref.nnz].cpu().numpy().view(np.uint32), ref.values.view(np.uint32))
+
+
+@pytest.mark.parametrize("cid", [5, 3])
+def test_bitmap_encode_then_aggregate(oracle, zen, cid):
+    import gpu_util as G
+    from dataclasses import replace
+
+    wl = replace(MINI_WORKLOADS[cid], bitmap=True)
+    n_workers = min(wl.n_workers, 16)
+    sparse = [worker_sparse(wl, w) for w in range(n_workers)]
+    grads = [G.dense_device(wl, r, v) for r, v in sparse]
+    ctx = zen.ZenContext(wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed, zen.ZEN_INDEX_BITMAP)
+    # BITMAP encode without an index array at all
+    encs = [zen.alloc_encoded(ctx, r.size, with_indices=False) for r, _ in sparse]
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, n_workers))
+    zen.zen_encode_batch(ctx, grads, encs, ws)
+    assert zen.zen_status_fetch(ctx, ws)[0] == 0
+    total, woff, _ = zen.zen_bitmap_layout(ctx)
+    refs = []
+    for (rows, vals), enc in zip(sparse, encs):
+        ref = oracle.encode(dense_from_sparse(wl, rows, vals), wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed)
+        _, _, word_off, ref_bm = _ref_bitmap(oracle, wl, rows)
+        assert np.array_equal(G.u32(enc.offsets), ref.offsets)
+        assert np.array_equal(G.u32(enc.bitmap[:total]), ref_bm)
+        assert np.array_equal(enc.values[:ref.nnz].cpu().numpy().view(np.uint32), ref.values.view(np.uint32))
+        refs.append(ref)
+    per_server = [sum(int(e.offsets[j + 1]) - int(e.offsets[j]) for e in refs) for j in range(wl.n_parts)]
+    max_in = max(per_server)
+    outs, (st, flags, _) = G.run_aggregate_batch(ctx, encs, [max(p, 1) for p in per_server], max_in)
+    assert st == 0 and flags == 0
+    for j in range(wl.n_parts):
+        parts = [(e.indices[e.offsets[j]:e.offsets[j + 1]], e.values[e.offsets[j]:e.offsets[j + 1]]) for e in refs]
+        ref = oracle.aggregate(parts, wl.n_rows, wl.row_dim)
+        U, idx, val = G.aggregated_to_host(outs[j])
+        assert U == ref.U and np.array_equal(idx, ref.indices)
+        G.check_sums(val, ref)
+
+
+def test_single_server_bitmap_parts(oracle, zen):
+    import gpu_util as G
+
+    R, D, n, seed = 20000, 4, 8, 99
+    ctx = zen.ZenContext(R, D, n, seed, zen.ZEN_INDEX_BITMAP)
+    owner = oracle.owner_table(R, n, seed)
+    dom_count, word_off = oracle.bitmap_layout(owner, n)
+    rng = np.random.default_rng(8)
+    part_id = 5
+    dom = np.flatnonzero(owner == part_id).astype(np.uint32)
+    parts_h, parts_d = [], []
+    for w in range(5):
+        rows = np.sort(rng.choice(dom, size=int(rng.integers(0, dom.size // 2)), replace=False)).astype(np.uint32)
+        vals = rng.standard_normal((rows.size, D)).astype(np.float32)
+        nz = np.zeros(R, np.uint8)
+        nz[rows] = 1
+        bm = oracle.bitmap_encode(owner, n, nz, word_off)[int(word_off[part_id]):int(word_off[part_id + 1])]
+        parts_h.append((rows, vals))
+        if w == 2:      # one part in COO form, mixed with bitmap parts
+            parts_d.append((G.to_dev(rows), None, torch.from_numpy(vals).cuda(),
+                            torch.tensor([rows.size], dtype=torch.int32, device="cuda")))
+        else:
+            parts_d.append((None, G.to_dev(bm) if bm.size else torch.zeros(1, dtype=torch.int32, device="cuda"),
+                            torch.from_numpy(vals).cuda() if rows.size else torch.empty((1, D), device="cuda"),
+                            torch.tensor([rows.size], dtype=torch.int32, device="cuda")))
+    total = sum(r.size for r, _ in parts_h)
+    ref = oracle.aggregate(parts_h, R, D)
+    out = zen.alloc_aggregated(ctx, total)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, total))
+    zen.zen_aggregate(ctx, parts_d, part_id, out, total, ws)
+    st, flags, _ = zen.zen_status_fetch(ctx, ws)
+    assert st == 0 and flags == 0
+    U, idx, val = G.aggregated_to_host(out)
+    assert U == ref.U and np.array_equal(idx, ref.indices)
+    G.check_sums(val, ref)
