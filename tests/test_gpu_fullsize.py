@@ -1,0 +1,112 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(zen_encode_batch over all workers, zen_aggregate_batch over all servers).
+
+The oracle cannot re-derive everything at these sizes in seconds, so: offsets / indices are
+checked against the oracle's partition of the planted non-zero rows (every worker, or a sample of
+workers for the largest workload), values against the planted rows, bitmaps by decoding sampled
+partitions with the oracle and by per-partition popcounts, and the aggregate on all (or sampled)
+servers against the oracle's aggregate of the oracle-partitioned inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import WORKLOADS, worker_sparse
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_partition(oracle, wl, rows):
+    own = (oracle.hash_many(rows, wl.hash_seed) % np.uint32(wl.n_parts)).astype(np.uint16)
+    return oracle.partition(rows, own, wl.n_parts)
+
+
+@pytest.mark.parametrize("cid", [2, 3, 4, 5])
+def test_full_size_workload(oracle, cid):
+    import gpu_util as G
+    import paper_2309_13254_amd as zen
+
+    wl = WORKLOADS[cid]
+    n, D = wl.n_parts, wl.row_dim
+    print("workload", wl.name, flush=True)
+    sparse = [worker_sparse(wl, w) for w in range(wl.n_workers)]
+    grads = [G.dense_device(wl, r, v) for r, v in sparse]
+    fmt = zen.ZEN_INDEX_BITMAP if wl.bitmap else zen.ZEN_INDEX_COO
+    ctx = zen.ZenContext(wl.n_rows, D, n, wl.hash_seed, fmt)
+    nnz = [r.size for r, _ in sparse]
+    encs = [zen.alloc_encoded(ctx, c, with_indices=True) for c in nnz]
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, wl.n_workers))
+    zen.zen_encode_batch(ctx, grads, encs, ws)
+    st, flags, _ = zen.zen_status_fetch(ctx, ws)
+    assert st == 0 and flags == 0
+    offs = np.stack([G.u32(e.offsets).astype(np.int64) for e in encs])
+    assert [int(o[-1]) for o in offs] == nnz                          # every planted row found, no other
+    assert np.all(np.diff(offs, axis=1) >= 0)
+
+    check_workers = list(range(wl.n_workers)) if cid != 5 else [0, 37]
+    refs = {}
+    for w in check_workers:
+        rows, vals = sparse[w]
+        r_off, r_idx = _oracle_partition(oracle, wl, rows)
+        refs[w] = (r_off, r_idx)
+        assert np.array_equal(offs[w], r_off.astype(np.int64))
+        assert np.array_equal(G.u32(encs[w].indices[:rows.size]), r_idx)
+        # values = planted rows in output order (sampled rows for the wide tables)
+        pos_of_row = np.searchsorted(rows, r_idx)
+        if vals.nbytes <= (64 << 20):
+            got = encs[w].values[:rows.size].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), vals[pos_of_row].view(np.uint32))
+        else:
+            sel = np.unique(np.random.default_rng(w).integers(0, rows.size, size=256))
+            got = encs[w].values[torch.from_numpy(sel).cuda()].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), vals[pos_of_row[sel]].view(np.uint32))
+    # Theorem 2 shape for Push on the large index sets
+    sizes = np.diff(offs, axis=1)
+    for w in range(wl.n_workers):
+        assert sizes[w].max() * n / nnz[w] <= 1 + 3 * np.sqrt(n * np.log(n) / nnz[w])
+
+    if wl.bitmap:
+        total, woff, dsz = zen.zen_bitmap_layout(ctx)
+        assert sum(dsz) == wl.n_rows and wl.n_rows // 32 <= total <= wl.n_rows // 32 + n
+        owner = oracle.owner_table(wl.n_rows, n, wl.hash_seed)
+        assert dsz == np.bincount(owner, minlength=n).tolist()
+        pop8 = np.array([bin(i).count("1") for i in range(256)], np.uint8)
+        for w in check_workers:
+            bm = G.u32(encs[w].bitmap[:total])
+            r_off, r_idx = refs[w]
+            for p in range(n):                                         # popcount = partition size
+                words = bm[woff[p]:woff[p + 1]]
+                assert int(pop8[words.view(np.uint8)].sum()) == int(r_off[p + 1]) - int(r_off[p])
+            for p in (3, n - 1):                                       # decode sampled partitions
+                dec = oracle.bitmap_decode(owner, p, bm[woff[p]:woff[p + 1]])
+                assert np.array_equal(dec, r_idx[int(r_off[p]):int(r_off[p + 1])])
+        del owner
+
+    per_server = np.diff(offs, axis=1).sum(axis=0)
+    max_in = int(per_server.max() * 1.05) + 16
+    aggs = [zen.alloc_aggregated(ctx, max_in) for _ in range(n)]
+    ws2 = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, n, max_in))
+    zen.zen_aggregate_batch(ctx, encs, aggs, max_in, ws2)
+    st, flags, _ = zen.zen_status_fetch(ctx, ws2)
+    assert st == 0 and flags == 0
+    counts = [int(a.count.item()) for a in aggs]
+    union = np.unique(np.concatenate([r for r, _ in sparse]))
+    assert sum(counts) == union.size                                   # sum_j U_j = |union|
+    assert max(counts) * n / union.size <= 1 + 3 * np.sqrt(n * np.log(n) / union.size)   # Theorem 2, Pull
+
+    check_servers = list(range(n)) if cid in (2, 3) else ([0, 17] if cid == 4 else [5, 63])
+    # oracle partition of every worker is needed for the sampled servers
+    for w in range(wl.n_workers):
+        if w not in refs:
+            refs[w] = _oracle_partition(oracle, wl, sparse[w][0])
+    for j in check_servers:
+        parts = []
+        for w in range(wl.n_workers):
+            rows, vals = sparse[w]
+            r_off, r_idx = refs[w]
+            seg = r_idx[int(r_off[j]):int(r_off[j + 1])]
+            parts.append((seg, vals[np.searchsorted(rows, seg)]))
+        ref = oracle.aggregate(parts, wl.n_rows, D)
+        U, idx, val = G.aggregated_to_host(aggs[j])
+        assert U == ref.U and np.array_equal(idx, ref.indices)
+        G.check_sums(val, ref)
