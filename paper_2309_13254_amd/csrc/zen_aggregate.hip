@@ -11,12 +11,14 @@
 namespace zen {
 
 static constexpr int AGG_THREADS = 256;
-static constexpr int SORT_SMALL_THREADS = 1024;
-static constexpr uint32_t SMALL_MAX_KEYS = 8192;   // unique keys one block sorts in LDS (32 KB)
+static constexpr int SMALL_THREADS = 1024;
+static constexpr uint32_t SMALL_MAX_IN = 6500;     // rows into one server that the one-block LDS path takes:
+                                                   // table of 8192 slots (load <= 0.8) x 2 arrays + 8192 sorted
+                                                   // keys = 96 KB of the 160 KB LDS
 static constexpr int RS_ITEMS = 8;                 // radix sort: keys per thread per block
 static constexpr int RS_BLOCK_KEYS = AGG_THREADS * RS_ITEMS;
 
-enum : uint32_t { CNT_UNIQUE = 0, CNT_TOTAL_IN = 1, CNT_SKIP = 2 };
+enum : uint32_t { CNT_UNIQUE = 0, CNT_TOTAL_IN = 1, CNT_SKIP = 2, CNT_FLAGS = 3, CNT_NEEDED = 4 };
 
 // rows [begin, begin+count) of idx are the part's indices; its values start at row vbegin
 struct PartRange { const uint32_t *idx; uint32_t begin, count, vbegin; };
@@ -50,11 +52,14 @@ __device__ __forceinline__ PartRange part_range(const PartIdx &src, uint32_t w, 
 __global__ void __launch_bounds__(1024)
 bitmap_decode_kernel(PartIdx src, Arr64<const uint32_t *> src_bitmap, uint32_t first_part,
                      const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *word_off,
-                     uint32_t *dec_base, uint64_t dec_stride, zen_status_info *status)
+                     uint32_t *dec_base, uint64_t dec_stride, zen_status_info *status, uint32_t *dec_flags)
 {
     __shared__ uint32_t s_tmp[32];
     const uint32_t w = blockIdx.x, server = blockIdx.y;
-    if (src.indices[w] || !src_bitmap.v[w]) return;
+    if (src.indices[w] || !src_bitmap.v[w]) {
+        if (dec_flags && threadIdx.x == 0) dec_flags[server * ZEN_MAX_BATCH + w] = 0;
+        return;
+    }
     const uint32_t p = first_part + server;
     const PartRange r = part_range(src, w, server);
     const uint32_t *bm = src_bitmap.v[w] + (src.single ? 0u : word_off[p]);
@@ -77,7 +82,10 @@ bitmap_decode_kernel(PartIdx src, Arr64<const uint32_t *> src_bitmap, uint32_t f
         }
         run += total;
     }
-    if (threadIdx.x == 0 && run != r.count) atomicOr(&status->flags, 4u);   // bitmap and row count disagree
+    if (threadIdx.x == 0) {   // bitmap and row count must agree
+        if (dec_flags) dec_flags[server * ZEN_MAX_BATCH + w] = run != r.count ? 4u : 0u;
+        else if (run != r.count) atomicOr(&status->flags, 4u);
+    }
 }
 
 __device__ __forceinline__ uint32_t probe_find(const uint32_t *__restrict__ keys, uint32_t cap_mask,
@@ -142,64 +150,254 @@ agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base
     }
 }
 
-// A3, small tables: one block per server.  Compacts the occupied slots into LDS, sorts them with a
-// bitonic network, writes out_indices / *count, and stores every key's rank into its slot.
-__global__ void __launch_bounds__(SORT_SMALL_THREADS)
-agg_sort_small_kernel(uint32_t seed, const uint32_t *keys_base, uint32_t *rank_base, uint64_t table_cap,
-                      uint32_t *counters_base, AggOut outs, zen_status_info *status)
+// ----------------------------------------------------------------------------------------------
+// Small tables (max_in_rows <= SMALL_MAX_IN): the whole merge of one server runs in one block with
+// the open-addressing table in LDS.
+//   insert every incoming index (LDS atomicCAS, linear probing) and count its occurrences
+//   -> compact + bitonic-sort the unique keys -> out_indices, *count
+//   -> exclusive scan of the occurrence counts in key order = row_start[] (CSR over output rows)
+//   -> every incoming row appends its id (part << 32 | row in the part's values) to its key's list
+// agg_gather_kernel then sums each output row from its contributor list in ascending (part, row)
+// order with plain loads and one store: no value atomics, no zero fill, reproducible bit for bit.
+// ----------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lds_probe(const uint32_t *tkeys, uint32_t cap_mask, uint32_t key, uint32_t seed)
 {
-    __shared__ uint32_t s_keys[SMALL_MAX_KEYS];
+    uint32_t slot = table_hash(key, seed) & cap_mask;
+    while (tkeys[slot] != key) slot = (slot + 1) & cap_mask;   // the key is present: terminates
+    return slot;
+}
+
+__global__ void __launch_bounds__(SMALL_THREADS)
+agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32_t max_in_rows,
+                 uint32_t *counters_base, AggOut outs, uint32_t *rowstart_base, uint32_t *contrib_base,
+                 uint64_t ws_stride, const uint32_t *dec_flags)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *tkeys = smem;                 // [cap]
+    uint32_t *tval = tkeys + cap;           // [cap] occurrences, later the fill cursor
+    uint32_t *sorted = tval + cap;          // [power of two >= max_in_rows]
+    __shared__ uint32_t s_tmp[32];
+    __shared__ uint32_t s_pre[ZEN_MAX_BATCH + 1];
+    __shared__ uint32_t s_begin[ZEN_MAX_BATCH];
+    __shared__ uint32_t s_vbegin[ZEN_MAX_BATCH];
+    __shared__ const uint32_t *s_idx[ZEN_MAX_BATCH];
     __shared__ uint32_t s_n;
     const uint32_t server = blockIdx.x;
-    const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
-    uint32_t *rank = rank_base + (uint64_t)server * table_cap;
     uint32_t *counters = counters_base + server * 16;
-    const uint32_t cap_mask = (uint32_t)(table_cap - 1);
+    uint32_t *rowstart = rowstart_base + (uint64_t)server * ws_stride;
+    uint64_t *contrib = (uint64_t *)(contrib_base + (uint64_t)server * ws_stride);   // ws_stride >= 2*max_in_rows
+    const uint32_t cap_mask = cap - 1;
+
+    uint32_t mine = 0, flags = 0;
+    if (threadIdx.x < n_in) {
+        const PartRange r = part_range(src, threadIdx.x, server);
+        mine = r.count;
+        s_idx[threadIdx.x] = r.idx;
+        s_begin[threadIdx.x] = r.begin;
+        s_vbegin[threadIdx.x] = r.vbegin;
+        if (dec_flags) flags = dec_flags[server * ZEN_MAX_BATCH + threadIdx.x];
+    }
     if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
-    if (counters[CNT_SKIP]) {
-        if (threadIdx.x == 0) *outs.count[server] = 0;
+    uint32_t total_in;
+    const uint32_t pre = block_exclusive_scan(mine, s_tmp, &total_in);
+    if (threadIdx.x < n_in) s_pre[threadIdx.x] = pre;
+    if (threadIdx.x == 0) s_pre[n_in] = total_in;
+    flags = __syncthreads_or((int)flags) ? 4u : 0u;
+    if (total_in > max_in_rows) {
+        if (threadIdx.x == 0) {
+            *outs.count[server] = 0;
+            counters[CNT_UNIQUE] = 0;
+            counters[CNT_SKIP] = 1;
+            counters[CNT_FLAGS] = flags | 2u;
+            counters[CNT_NEEDED] = total_in;
+        }
         return;
     }
-    for (uint32_t i = threadIdx.x; i < table_cap; i += blockDim.x) {
-        const uint32_t k = keys[i];
-        if (k != ZEN_EMPTY_KEY) {
-            const uint32_t at = atomicAdd(&s_n, 1u);
-            if (at < SMALL_MAX_KEYS) s_keys[at] = k;   // cannot overflow: cap <= 2*SMALL_MAX_KEYS at load <= 1/2
+    for (uint32_t i = threadIdx.x; i < cap; i += blockDim.x) { tkeys[i] = ZEN_EMPTY_KEY; tval[i] = 0; }
+    __syncthreads();
+
+    // insert + count
+    for (uint32_t e = threadIdx.x; e < total_in; e += blockDim.x) {
+        uint32_t lo = 0, hi = n_in;
+        while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (s_pre[mid] <= e) lo = mid; else hi = mid; }
+        const uint32_t key = s_idx[lo][s_begin[lo] + (e - s_pre[lo])];
+        if (key == ZEN_EMPTY_KEY) { flags |= 4u; continue; }
+        uint32_t slot = table_hash(key, seed) & cap_mask;
+        for (;;) {
+            const uint32_t prev = atomicCAS(&tkeys[slot], ZEN_EMPTY_KEY, key);
+            if (prev == ZEN_EMPTY_KEY || prev == key) break;
+            slot = (slot + 1) & cap_mask;   // load <= 0.8: an empty slot exists
         }
+        atomicAdd(&tval[slot], 1u);
     }
     __syncthreads();
-    const uint32_t U = min(s_n, SMALL_MAX_KEYS);
+
+    // compact + sort the unique keys
+    for (uint32_t i = threadIdx.x; i < cap; i += blockDim.x) {
+        const uint32_t k = tkeys[i];
+        if (k != ZEN_EMPTY_KEY) sorted[atomicAdd(&s_n, 1u)] = k;
+    }
+    __syncthreads();
+    const uint32_t U = s_n;
     uint32_t P = 1;
     while (P < U) P <<= 1;
-    for (uint32_t i = U + threadIdx.x; i < P; i += blockDim.x) s_keys[i] = ZEN_EMPTY_KEY;   // pad high
+    for (uint32_t i = U + threadIdx.x; i < P; i += blockDim.x) sorted[i] = ZEN_EMPTY_KEY;   // pad high
     __syncthreads();
     for (uint32_t k = 2; k <= P; k <<= 1) {
         for (uint32_t j = k >> 1; j > 0; j >>= 1) {
             for (uint32_t t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
-                const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));   // index with bit j clear
+                const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
                 const uint32_t hi = lo | j;
                 const bool up = (lo & k) == 0;
-                const uint32_t a = s_keys[lo], b = s_keys[hi];
-                if ((a > b) == up) { s_keys[lo] = b; s_keys[hi] = a; }
+                const uint32_t a = sorted[lo], b = sorted[hi];
+                if ((a > b) == up) { sorted[lo] = b; sorted[hi] = a; }
             }
             __syncthreads();
         }
     }
+
+    // row_start = exclusive scan of the occurrence counts in key order; slots get their fill cursor
     const uint64_t cap_rows = outs.cap_rows[server];
     uint32_t *out_idx = outs.indices[server];
-    for (uint32_t u = threadIdx.x; u < U; u += blockDim.x) {
-        const uint32_t key = s_keys[u];
+    const uint32_t per = (U + blockDim.x - 1) / blockDim.x;
+    const uint32_t u0 = min(threadIdx.x * per, U), u1 = min(u0 + per, U);
+    uint32_t sum = 0;
+    for (uint32_t u = u0; u < u1; ++u) sum += tval[lds_probe(tkeys, cap_mask, sorted[u], seed)];
+    uint32_t n_listed;   // incoming rows with a valid key
+    uint32_t run = block_exclusive_scan(sum, s_tmp, &n_listed);
+    for (uint32_t u = u0; u < u1; ++u) {
+        const uint32_t key = sorted[u];
+        const uint32_t slot = lds_probe(tkeys, cap_mask, key, seed);
+        const uint32_t c = tval[slot];
+        tval[slot] = run;
+        rowstart[u] = run;
         if (u < cap_rows) out_idx[u] = key;
-        const uint32_t slot = probe_find(keys, cap_mask, key, seed);
-        if (slot != 0xFFFFFFFFu) rank[slot] = u;
+        run += c;
     }
+    if (threadIdx.x == 0) rowstart[U] = n_listed;
+    __syncthreads();
+
+    // fill the contributor lists
+    for (uint32_t e = threadIdx.x; e < total_in; e += blockDim.x) {
+        uint32_t lo = 0, hi = n_in;
+        while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (s_pre[mid] <= e) lo = mid; else hi = mid; }
+        const uint32_t i = e - s_pre[lo];
+        const uint32_t key = s_idx[lo][s_begin[lo] + i];
+        if (key == ZEN_EMPTY_KEY) continue;
+        const uint32_t at = atomicAdd(&tval[lds_probe(tkeys, cap_mask, key, seed)], 1u);
+        contrib[at] = ((uint64_t)lo << 32) | (uint64_t)(s_vbegin[lo] + i);
+    }
+    flags = __syncthreads_or((int)flags) ? 4u : 0u;
     if (threadIdx.x == 0) {
         *outs.count[server] = U;
         counters[CNT_UNIQUE] = U;
-        if ((uint64_t)U > cap_rows) {
-            atomicOr(&status->flags, 1u);
-            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)U);
+        counters[CNT_SKIP] = 0;
+        counters[CNT_FLAGS] = flags | ((uint64_t)U > cap_rows ? 1u : 0u);
+        counters[CNT_NEEDED] = (uint64_t)U > cap_rows ? U : 0u;
+    }
+}
+
+// Smallest contributor id strictly greater than `prev` (ids are distinct); ~0 if none.
+__device__ __forceinline__ uint64_t next_contrib(const uint64_t *list, uint32_t len, uint64_t prev, bool first)
+{
+    uint64_t best = ~0ull;
+    for (uint32_t k = 0; k < len; ++k) {
+        const uint64_t e = list[k];
+        if ((first || e > prev) && e < best) best = e;
+    }
+    return best;
+}
+
+// A2 (values), small tables: out_values[u] = sum of the rows listed for u, in ascending (part, row)
+// order.  Wide rows: one wave per output row; narrow rows: one thread per output element.
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_servers,
+                  uint32_t *counters_base, const uint32_t *rowstart_base, const uint32_t *contrib_base,
+                  uint64_t ws_stride, Arr64<float *> out_values, AggOut outs, zen_status_info *status)
+{
+    const uint32_t server = blockIdx.y;
+    const uint32_t D = row_dim;
+    if (blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
+        // status of the whole call = OR / max over the servers' own results
+        uint32_t fl = 0, need = 0;
+        for (uint32_t j = 0; j < n_servers; ++j) {
+            fl |= counters_base[j * 16 + CNT_FLAGS];
+            need = max(need, counters_base[j * 16 + CNT_NEEDED]);
+        }
+        status->flags = fl;
+        status->reserved = 0;
+        status->needed_rows = need;
+    }
+    const uint32_t *counters = counters_base + server * 16;
+    if (counters[CNT_SKIP]) return;
+    const uint32_t U = counters[CNT_UNIQUE];
+    const uint64_t cap_rows = outs.cap_rows[server];
+    const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
+    const uint32_t *rowstart = rowstart_base + (uint64_t)server * ws_stride;
+    const uint64_t *contrib = (const uint64_t *)(contrib_base + (uint64_t)server * ws_stride);
+    float *__restrict__ out = out_values.v[server];
+
+    if ((D & 3u) == 0 && D >= 256) {
+        const uint32_t lane = lane_id(), nw = blockDim.x >> 6, V = D >> 2;
+        for (uint32_t u = blockIdx.x * nw + (threadIdx.x >> 6); u < rows; u += gridDim.x * nw) {
+            const uint32_t r0 = rowstart[u], len = rowstart[u + 1] - r0;
+            // the row's contributor list, sorted across the lanes (lists longer than a wave: see below)
+            const bool in_wave = len <= ZEN_WAVE;
+            uint64_t mine = ~0ull;
+            uint32_t my_rank = 0xFFFFFFFFu;
+            if (in_wave) {
+                if (lane < len) mine = contrib[r0 + lane];
+                uint32_t below = 0;
+                for (uint32_t j = 0; j < len; ++j) {
+                    const uint64_t cj = ((uint64_t)__shfl((uint32_t)(mine >> 32), j, ZEN_WAVE) << 32) |
+                                        __shfl((uint32_t)mine, j, ZEN_WAVE);
+                    below += cj < mine ? 1u : 0u;
+                }
+                if (lane < len) my_rank = below;
+            }
+            f32x4 *o4 = (f32x4 *)(out + (uint64_t)u * D);
+            for (uint32_t v0 = 0; v0 < V; v0 += 64 * 4) {
+                f32x4 acc[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                uint64_t prev = 0;
+                for (uint32_t k = 0; k < len; ++k) {
+                    uint64_t e;
+                    if (in_wave) {
+                        const uint32_t srcl = (uint32_t)__ffsll((unsigned long long)ballot(my_rank == k)) - 1u;
+                        e = ((uint64_t)__shfl((uint32_t)(mine >> 32), srcl, ZEN_WAVE) << 32) |
+                            __shfl((uint32_t)mine, srcl, ZEN_WAVE);
+                    } else {
+                        e = next_contrib(contrib + r0, len, prev, k == 0);   // wave-uniform
+                    }
+                    prev = e;
+                    const f32x4 *s4 = (const f32x4 *)(src_values.v[(uint32_t)(e >> 32)] + (e & 0xFFFFFFFFull) * D);
+                    f32x4 x[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        x[q] = (v0 + 64 * q + lane < V) ? s4[v0 + 64 * q + lane] : (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[q] += x[q];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (v0 + 64 * q + lane < V) o4[v0 + 64 * q + lane] = acc[q];
+            }
+        }
+    } else {
+        const uint64_t n_el = (uint64_t)rows * D;
+        for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_el;
+             f += (uint64_t)gridDim.x * blockDim.x) {
+            const uint32_t u = (uint32_t)(f / D), c = (uint32_t)(f - (uint64_t)u * D);
+            const uint32_t r0 = rowstart[u], len = rowstart[u + 1] - r0;
+            float acc = 0.f;
+            uint64_t prev = 0;
+            for (uint32_t k = 0; k < len; ++k) {
+                const uint64_t e = next_contrib(contrib + r0, len, prev, k == 0);
+                prev = e;
+                acc += src_values.v[(uint32_t)(e >> 32)][(e & 0xFFFFFFFFull) * D + c];
+            }
+            out[f] = acc;
         }
     }
 }
@@ -443,7 +641,7 @@ AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_ro
     uint64_t cap = 1024;
     while (cap < 2 * max_in_rows) cap <<= 1;
     L.table_cap = cap;
-    L.small_path = cap <= 2 * (uint64_t)SMALL_MAX_KEYS ? 1u : 0u;
+    L.small_path = max_in_rows <= SMALL_MAX_IN ? 1u : 0u;
     uint64_t off = 0;
     L.status_off = off; off += 256;
     L.counters_off = off; off += align_up((uint64_t)batch * 16 * 4, 256);
@@ -460,6 +658,7 @@ AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_ro
     if (decode) {
         L.decode_stride = L.uniq_cap;
         off += align_up((uint64_t)batch * L.decode_stride * 4, 256);
+        L.decflags_off = off; off += align_up((uint64_t)batch * ZEN_MAX_BATCH * 4, 256);
     }
     (void)g;
     L.total = off;
@@ -486,6 +685,50 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
     const uint64_t cap = L.table_cap;
     const uint64_t n_keys = (uint64_t)n_servers * cap;
 
+    bool any_bitmap = false;
+    for (uint32_t w = 0; w < n_in; ++w) any_bitmap |= (src.indices[w] == nullptr);
+    if (any_bitmap && (!ctx->d_domain || !L.decode_stride)) return hipErrorInvalidValue;
+
+    if (L.small_path) {
+        uint32_t *dec_flags = any_bitmap ? (uint32_t *)(ws + L.decflags_off) : nullptr;
+        if (any_bitmap) {
+            ProfScope prof(ctx, K_BITMAP_DECODE, s);
+            bitmap_decode_kernel<<<dim3(n_in, n_servers), 1024, 0, s>>>(
+                src, src_bitmap, first_part_id, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off,
+                (uint32_t *)(ws + L.decode_off), L.decode_stride, status, dec_flags);
+            ZEN_LAUNCH_CHECK();
+        }
+        uint32_t lcap = 1024, sortp = 1;
+        while ((uint64_t)lcap * 4 < max_in_rows * 5) lcap <<= 1;   // load <= 0.8
+        while (sortp < max_in_rows) sortp <<= 1;
+        const size_t lds = ((size_t)2 * lcap + sortp) * 4;
+        static bool lds_attr_set = false;
+        if (!lds_attr_set) {
+            (void)hipFuncSetAttribute((const void *)agg_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (2 * 8192 + 8192) * 4);
+            (void)hipGetLastError();
+            lds_attr_set = true;
+        }
+        {
+            ProfScope prof(ctx, K_AGG_SORT_SMALL, s);
+            agg_small_kernel<<<n_servers, SMALL_THREADS, lds, s>>>(src, n_in, g.seed, lcap, (uint32_t)max_in_rows,
+                                                                   counters, outs, keys, rank, cap, dec_flags);
+            ZEN_LAUNCH_CHECK();
+        }
+        {
+            uint64_t gx;
+            if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) gx = (max_in_rows + 3) / 4;
+            else gx = (max_in_rows * g.row_dim + AGG_THREADS - 1) / AGG_THREADS;
+            if (gx < 1) gx = 1;
+            if (gx > 8192) gx = 8192;
+            ProfScope prof(ctx, K_AGG_GATHER, s);
+            agg_gather_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
+                src_values, g.row_dim, n_servers, counters, keys, rank, cap, out_values, outs, status);
+            ZEN_LAUNCH_CHECK();
+        }
+        return hipSuccess;
+    }
+
     {
         uint64_t blocks = (n_keys + 1023) / 1024;
         if (blocks > 16384) blocks = 16384;
@@ -495,14 +738,11 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
             ZEN_LAUNCH_CHECK();
         }
     }
-    bool any_bitmap = false;
-    for (uint32_t w = 0; w < n_in; ++w) any_bitmap |= (src.indices[w] == nullptr);
     if (any_bitmap) {
-        if (!ctx->d_domain || !L.decode_stride) return hipErrorInvalidValue;
         ProfScope prof(ctx, K_BITMAP_DECODE, s);
         bitmap_decode_kernel<<<dim3(n_in, n_servers), 1024, 0, s>>>(
             src, src_bitmap, first_part_id, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off,
-            (uint32_t *)(ws + L.decode_off), L.decode_stride, status);
+            (uint32_t *)(ws + L.decode_off), L.decode_stride, status, nullptr);
         ZEN_LAUNCH_CHECK();
     }
     // rows per (part, server) are unknown on the host; size the x dimension for an even split of
@@ -518,14 +758,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         ZEN_LAUNCH_CHECK();
     }
 
-    if (L.small_path) {
-        {
-            ProfScope prof(ctx, K_AGG_SORT_SMALL, s);
-            agg_sort_small_kernel<<<n_servers, SORT_SMALL_THREADS, 0, s>>>(g.seed, keys, rank, cap, counters, outs,
-                                                                           status);
-            ZEN_LAUNCH_CHECK();
-        }
-    } else {
+    {
         uint32_t *uniq = (uint32_t *)(ws + L.uniq_off);
         uint32_t *hist = (uint32_t *)(ws + L.sorthist_off);
         const uint64_t ustride = 2 * L.uniq_cap, hstride = L.sort_blocks * 256;

@@ -24,10 +24,15 @@ static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32
     g.part_bits = 0;
     while ((1u << g.part_bits) < n_parts) ++g.part_bits;
     g.bitmap = bitmap ? 1u : 0u;
-    const uint64_t target_bytes = 128 * 1024;
+    uint64_t target_bytes = 128 * 1024;
+    if (const char *e = getenv("ZEN_TILE_BYTES")) {   // tuning knob: dense bytes per tile
+        const long long v = atoll(e);
+        if (v >= 4096 && v <= (8 << 20)) target_bytes = (uint64_t)v;
+    }
     if (row_dim == 1) {
         g.mode = MODE_ELEM;
-        uint64_t t = 32768;                      // 128 KB
+        uint64_t t = 2048;
+        while (t * 2 * 4 <= target_bytes && t < 65536) t <<= 1;   // 32768 rows = 128 KB
         while (t > 2048 && n_rows / t < 1024) t >>= 1;   // small tensors: keep >= ~1024 tiles
         g.tile_rows = (uint32_t)t;
     } else if ((row_dim & 3u) == 0 && row_dim <= 128 && is_pow2(row_dim / 4)) {
@@ -383,8 +388,9 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
 
 static const char *const kKernelNames[K_COUNT] = {
     "detect_kernel", "partition_scan_kernel", "scatter_kernel", "agg_clear_kernel", "agg_insert_kernel",
-    "agg_sort_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
-    "agg_finalize_kernel", "agg_zero_kernel", "agg_accum_kernel", "nonzero_list_kernels", "bitmap_decode_kernel"};
+    "agg_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
+    "agg_finalize_kernel", "agg_zero_kernel", "agg_accum_kernel", "nonzero_list_kernels", "bitmap_decode_kernel",
+    "agg_gather_kernel"};
 
 static void prof_release(zen_ctx *ctx)
 {

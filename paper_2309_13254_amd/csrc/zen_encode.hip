@@ -224,8 +224,9 @@ __global__ void __launch_bounds__(SCAN_THREADS)
 partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_t hist_stride_words,
                       zen_status_info *status)
 {
-    __shared__ uint32_t s_part[SCAN_THREADS];   // [grp][p] partial sums, later group prefixes
+    __shared__ uint32_t s_part[SCAN_THREADS];   // [grp][p] partial sums
     __shared__ uint32_t s_off[ZEN_MAX_PARTS + 1];
+    __shared__ uint32_t s_tmp[32];
     const uint32_t worker = blockIdx.x;
     uint32_t *hist = hist_base + worker * hist_stride_words;
     const uint32_t n = g.n_parts;
@@ -240,30 +241,35 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
     for (uint32_t t = t0; t < t1; ++t) sum += hist[(uint64_t)t * n + p];
     if (active) s_part[grp * n + p] = sum;
     __syncthreads();
-    // exclusive scan over groups for each p; total per p
-    if (threadIdx.x < n) {
-        uint32_t run = 0;
-        for (uint32_t gI = 0; gI < n_groups; ++gI) {
-            const uint32_t t = s_part[gI * n + threadIdx.x];
-            s_part[gI * n + threadIdx.x] = run;
-            run += t;
-        }
-        s_off[threadIdx.x + 1] = run;   // totals, shifted by one
+    // exclusive scan over groups for each p (Hillis-Steele along the group axis, all p at once)
+    __shared__ uint32_t s_alt[SCAN_THREADS];
+    uint32_t *cur = s_part, *nxt = s_alt;
+    for (uint32_t d = 1; d < n_groups; d <<= 1) {
+        uint32_t v = 0;
+        if (active) v = cur[grp * n + p] + (grp >= d ? cur[(grp - d) * n + p] : 0u);
+        if (active) nxt[grp * n + p] = v;
+        __syncthreads();
+        uint32_t *t = cur; cur = nxt; nxt = t;
     }
-    __syncthreads();
+    // cur = inclusive prefix over groups; totals per p = last group's value
+    uint32_t tot_p = 0;
+    if (threadIdx.x < n) tot_p = cur[(n_groups - 1) * n + threadIdx.x];
+    uint32_t n_total;
+    const uint32_t off_p = block_exclusive_scan(tot_p, s_tmp, &n_total);
+    if (threadIdx.x < n) s_off[threadIdx.x] = off_p;
+    uint32_t my_prefix = 0;   // rows of partition p in the groups before mine
+    if (active) my_prefix = cur[grp * n + p] - sum;
     if (threadIdx.x == 0) {
-        s_off[0] = 0;
-        uint32_t run = 0;
-        for (uint32_t q = 0; q < n; ++q) { run += s_off[q + 1]; s_off[q + 1] = run; }
-        if ((uint64_t)run > outs.cap_rows[worker]) {
+        s_off[n] = n_total;
+        if ((uint64_t)n_total > outs.cap_rows[worker]) {
             atomicOr(&status->flags, 1u);
-            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)run);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)n_total);
         }
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) outs.offsets[worker][i] = s_off[i];
     if (active) {
-        uint32_t run = s_off[p] + s_part[grp * n + p];
+        uint32_t run = s_off[p] + my_prefix;
         for (uint32_t t = t0; t < t1; ++t) {
             const uint64_t a = (uint64_t)t * n + p;
             const uint32_t h = hist[a];
@@ -391,21 +397,30 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             if (D > 1 && out_val) {
                 __syncthreads();
                 if ((D & 3u) == 0 && D >= 256) {
-                    // one wave per row, 16-byte vectors
-                    const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
-                    for (uint32_t i = threadIdx.x >> 6; i < total; i += nw) {
-                        const uint32_t pos = s_pos[i];
-                        if (pos == 0xFFFFFFFFu) continue;
-                        const u32x4 *src = (const u32x4 *)(grad + (uint64_t)s_list[i] * D);
-                        u32x4 *dst = (u32x4 *)(out_val + (uint64_t)pos * D);
+                    // one wave copies four rows at a time, 16 x 16-byte loads in flight per lane
+                    const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6, wv = threadIdx.x >> 6;
+                    for (uint32_t i0 = wv * 4; i0 < total; i0 += nw * 4) {
+                        const u32x4 *src[4];
+                        u32x4 *dst[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t i = i0 + q;
+                            const uint32_t pos = i < total ? s_pos[i] : 0xFFFFFFFFu;
+                            src[q] = pos != 0xFFFFFFFFu ? (const u32x4 *)(grad + (uint64_t)s_list[i] * D) : nullptr;
+                            dst[q] = pos != 0xFFFFFFFFu ? (u32x4 *)(out_val + (uint64_t)pos * D) : nullptr;
+                        }
                         for (uint32_t v = lane; v < V; v += 64 * 4) {
-                            u32x4 x[4];
+                            u32x4 x[4][4];
 #pragma unroll
-                            for (int u = 0; u < 4; ++u)
-                                if (v + 64 * u < V) x[u] = src[v + 64 * u];
+                            for (int q = 0; q < 4; ++q)
 #pragma unroll
-                            for (int u = 0; u < 4; ++u)
-                                if (v + 64 * u < V) dst[v + 64 * u] = x[u];
+                                for (int u = 0; u < 4; ++u)
+                                    if (src[q] && v + 64 * u < V) x[q][u] = src[q][v + 64 * u];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                                for (int u = 0; u < 4; ++u)
+                                    if (dst[q] && v + 64 * u < V) dst[q][v + 64 * u] = x[q][u];
                         }
                     }
                 } else if ((D & 3u) == 0) {

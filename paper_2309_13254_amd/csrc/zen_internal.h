@@ -77,6 +77,7 @@ struct AggLayout {
     uint64_t sort_blocks;    // radix-sort blocks per server
     uint64_t decode_off;     // bitmap parts: per (server, part) decoded indices
     uint64_t decode_stride;
+    uint64_t decflags_off;   // small path: per (server, part) decode consistency flag
     uint64_t table_cap;      // slots per server (power of two)
     uint32_t small_path;     // 1: one block per server sorts in LDS
     uint64_t total;
@@ -88,6 +89,7 @@ namespace zen {
 enum KernelId : uint32_t {
     K_DETECT = 0, K_PARTITION_SCAN, K_SCATTER, K_AGG_CLEAR, K_AGG_INSERT, K_AGG_SORT_SMALL, K_AGG_COMPACT,
     K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_ZERO, K_AGG_ACCUM, K_NONZERO_LIST, K_BITMAP_DECODE,
+    K_AGG_GATHER,
     K_COUNT
 };
 struct ProfRecord { hipEvent_t start, stop; uint32_t kernel; };
