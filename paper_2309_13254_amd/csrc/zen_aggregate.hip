@@ -243,8 +243,11 @@ agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32
     while (P < U) P <<= 1;
     for (uint32_t i = U + threadIdx.x; i < P; i += blockDim.x) sorted[i] = ZEN_EMPTY_KEY;   // pad high
     __syncthreads();
+    // Bitonic network.  Pair t of a stage with stride j touches elements inside [128*(t/64), +128)
+    // whenever j <= 64, i.e. only data of its own wave: those stages need no block barrier.
     for (uint32_t k = 2; k <= P; k <<= 1) {
         for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            if (j >= 128) __syncthreads();
             for (uint32_t t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
                 const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
                 const uint32_t hi = lo | j;
@@ -252,9 +255,11 @@ agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32
                 const uint32_t a = sorted[lo], b = sorted[hi];
                 if ((a > b) == up) { sorted[lo] = b; sorted[hi] = a; }
             }
-            __syncthreads();
+            if (j == 128) __syncthreads();
+            else __builtin_amdgcn_wave_barrier();
         }
     }
+    __syncthreads();
 
     // row_start = exclusive scan of the occurrence counts in key order; slots get their fill cursor
     const uint64_t cap_rows = outs.cap_rows[server];

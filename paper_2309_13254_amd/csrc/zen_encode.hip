@@ -161,6 +161,10 @@ __device__ __forceinline__ void detect_row(const float *__restrict__ g, uint64_t
 
 // E1 + E3: one block per (tile, worker).  Writes the tile's mask words and its owner histogram
 // hist[tile][0..n_parts).
+// PATH: 0 = row_dim 1; 1..6 = 4*2^(PATH-1) floats per row with 2^(PATH-1) lanes per row;
+//       7 = wave per row, 16-byte loads; 8 = wave per row, 4-byte loads.  One kernel per path so
+//       that each keeps its own register budget (the widest path would set everyone's occupancy).
+template <int PATH>
 __global__ void __launch_bounds__(DETECT_THREADS)
 detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
               uint32_t *hist_base, uint64_t hist_stride_words, zen_status_info *reset_status)
@@ -176,28 +180,15 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
         reset_status->flags = 0; reset_status->reserved = 0; reset_status->needed_rows = 0;
     }
     for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) s_hist[i] = 0;
-    if (g.mode == MODE_ROW) {
+    if (PATH >= 7) {
         for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) s_mask[i] = 0;
         __syncthreads();
     }
 
-    switch (g.mode) {
-    case MODE_ELEM: detect_elem<8>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-    case MODE_SUB:
-        switch (g.row_dim) {
-        case 4: detect_sub<1>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-        case 8: detect_sub<2>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-        case 16: detect_sub<4>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-        case 32: detect_sub<8>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-        case 64: detect_sub<16>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-        default: detect_sub<32>(grad, g.n_rows, row0, g.tile_rows, s_mask); break;
-        }
-        break;
-    default:
-        if ((g.row_dim & 3u) == 0) detect_row<4>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
-        else detect_row<1>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
-        break;
-    }
+    if (PATH == 0) detect_elem<8>(grad, g.n_rows, row0, g.tile_rows, s_mask);
+    else if (PATH <= 6) detect_sub<(PATH >= 1 && PATH <= 6) ? (1 << (PATH - 1)) : 1>(grad, g.n_rows, row0, g.tile_rows, s_mask);
+    else if (PATH == 7) detect_row<4>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
+    else detect_row<1>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
     __syncthreads();
 
     uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
@@ -304,8 +295,9 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     extern __shared__ uint32_t smem[];
     const uint32_t n = g.n_parts, D = g.row_dim;
     uint32_t *s_run = smem;                          // [n]
-    uint32_t *s_cnt = s_run + n;                     // [4][n]
-    uint32_t *s_list = s_cnt + 4 * n;                // [SEG_ROWS] row ids of the segment, ascending
+    const uint32_t n_waves = blockDim.x >> 6;
+    uint32_t *s_cnt = s_run + n;                     // [n_waves][n]
+    uint32_t *s_list = s_cnt + n_waves * n;                // [SEG_ROWS] row ids of the segment, ascending
     uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row
     uint32_t *s_tmp = s_pos + SEG_ROWS;              // [32]
     uint32_t *s_b0 = s_tmp + 32;                     // bitmap only: [n] first bit of (tile, p)
@@ -320,7 +312,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     const uint64_t cap = outs.cap_rows[worker];
     const bool bitmap = g.bitmap && out_bm != nullptr;
 
-    for (uint32_t i = threadIdx.x; i < 4 * n; i += blockDim.x) s_cnt[i] = 0;
+    for (uint32_t i = threadIdx.x; i < n_waves * n; i += blockDim.x) s_cnt[i] = 0;
 
     for (uint32_t tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
         const uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
@@ -397,27 +389,27 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             if (D > 1 && out_val) {
                 __syncthreads();
                 if ((D & 3u) == 0 && D >= 256) {
-                    // one wave copies four rows at a time, 16 x 16-byte loads in flight per lane
+                    // one wave copies two rows at a time, 8 x 16-byte loads in flight per lane
                     const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6, wv = threadIdx.x >> 6;
-                    for (uint32_t i0 = wv * 4; i0 < total; i0 += nw * 4) {
-                        const u32x4 *src[4];
-                        u32x4 *dst[4];
+                    for (uint32_t i0 = wv * 2; i0 < total; i0 += nw * 2) {
+                        const u32x4 *src[2];
+                        u32x4 *dst[2];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
+                        for (int q = 0; q < 2; ++q) {
                             const uint32_t i = i0 + q;
                             const uint32_t pos = i < total ? s_pos[i] : 0xFFFFFFFFu;
                             src[q] = pos != 0xFFFFFFFFu ? (const u32x4 *)(grad + (uint64_t)s_list[i] * D) : nullptr;
                             dst[q] = pos != 0xFFFFFFFFu ? (u32x4 *)(out_val + (uint64_t)pos * D) : nullptr;
                         }
                         for (uint32_t v = lane; v < V; v += 64 * 4) {
-                            u32x4 x[4][4];
+                            u32x4 x[2][4];
 #pragma unroll
-                            for (int q = 0; q < 4; ++q)
+                            for (int q = 0; q < 2; ++q)
 #pragma unroll
                                 for (int u = 0; u < 4; ++u)
                                     if (src[q] && v + 64 * u < V) x[q][u] = src[q][v + 64 * u];
 #pragma unroll
-                            for (int q = 0; q < 4; ++q)
+                            for (int q = 0; q < 2; ++q)
 #pragma unroll
                                 for (int u = 0; u < 4; ++u)
                                     if (dst[q] && v + 64 * u < V) dst[q][v + 64 * u] = x[q][u];
@@ -569,9 +561,23 @@ hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, ch
     const Geometry &g = ctx->geo;
     const size_t lds = (size_t)(g.tile_words + g.n_parts) * 4;
     ProfScope prof(ctx, K_DETECT, s);
-    detect_kernel<<<dim3(g.n_tiles, batch), DETECT_THREADS, lds, s>>>(
-        g, grads, (uint32_t *)(ws + L.mask_off), L.mask_stride / 4, (uint32_t *)(ws + L.hist_off),
-        L.hist_stride / 4, reset_status ? (zen_status_info *)(ws + L.status_off) : nullptr);
+    uint32_t *mask = (uint32_t *)(ws + L.mask_off), *hist = (uint32_t *)(ws + L.hist_off);
+    zen_status_info *rs = reset_status ? (zen_status_info *)(ws + L.status_off) : nullptr;
+    const dim3 grid(g.n_tiles, batch);
+    int path;
+    if (g.mode == MODE_ELEM) path = 0;
+    else if (g.mode == MODE_SUB) { path = 1; while ((4u << (path - 1)) < g.row_dim) ++path; }
+    else path = (g.row_dim & 3u) == 0 ? 7 : 8;
+#define ZEN_DETECT_CASE(P)                                                                                 \
+    case P:                                                                                                \
+        detect_kernel<P><<<grid, DETECT_THREADS, lds, s>>>(g, grads, mask, L.mask_stride / 4, hist,        \
+                                                          L.hist_stride / 4, rs);                          \
+        break;
+    switch (path) {
+        ZEN_DETECT_CASE(0) ZEN_DETECT_CASE(1) ZEN_DETECT_CASE(2) ZEN_DETECT_CASE(3) ZEN_DETECT_CASE(4)
+        ZEN_DETECT_CASE(5) ZEN_DETECT_CASE(6) ZEN_DETECT_CASE(7) ZEN_DETECT_CASE(8)
+    }
+#undef ZEN_DETECT_CASE
     return hipGetLastError();
 }
 
@@ -586,12 +592,17 @@ hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t
     return hipGetLastError();
 }
 
+// Blocks per worker: about 4096 blocks per launch; a block that would get only two or three tiles
+// gets one instead (short launches are latency-bound, not block-overhead-bound).
 static uint32_t scatter_grid_x(const Geometry &g, uint32_t batch)
 {
     uint32_t gx = 4096 / (batch ? batch : 1);
     if (gx < 64) gx = 64;
+    if (g.n_tiles <= 3 * gx) gx = g.n_tiles;
     return gx < g.n_tiles ? gx : g.n_tiles;
 }
+
+static uint32_t scatter_threads(const Geometry &) { return (uint32_t)SCATTER_THREADS; }
 
 hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
                           const EncodedPtrs &outs, uint32_t batch, char *ws, const EncodeLayout &L,
@@ -608,9 +619,10 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
         }
     }
     ProfScope prof(ctx, K_SCATTER, s);
-    size_t words = 5 * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
+    const uint32_t threads = scatter_threads(g);
+    size_t words = (1 + threads / 64) * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
     if (g.bitmap) words += 3 * (size_t)g.n_parts + 1 + g.tile_words + 2 * (size_t)g.n_parts;
-    scatter_kernel<<<dim3(scatter_grid_x(g, batch), batch), SCATTER_THREADS, words * 4, s>>>(
+    scatter_kernel<<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
         g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
         (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
     return hipGetLastError();
