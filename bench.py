@@ -89,6 +89,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-times", action="store_true", help="extra untimed pass timing every kernel")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain 1 GiB copy kernel three times (reference for hardware "
+                         "byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (the n workers are n buffers on that GPU); --gpus %d is not "
@@ -161,6 +164,14 @@ def main():
         torch.cuda.synchronize()
         kernel_ms = {k: round(v[0] / 5, 4) for k, v in zen.zen_profile_collect(ctx).items()}
         zen.zen_profile_enable(ctx, 0, 0)
+
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            zen.zen_calibration_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -167,6 +167,11 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
 zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out,
                          void *hip_stream);
 
+/* Plain device-to-device streaming copy of `bytes` (multiple of 16, both pointers 16-byte aligned):
+ * reads `bytes`, writes `bytes`.  Not part of the method: it is the kernel of known traffic against
+ * which hardware HBM byte counters are scaled when the library is profiled. */
+zen_status zen_calibration_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream);
+
 /*
  * Optional kernel timing with HIP events recorded on the launch stream (for benchmarks; not part of
  * the method).  mode 0 = off, 1 = time the dense-scan (detect) kernel only, 2 = time every kernel.

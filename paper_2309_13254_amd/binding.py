@@ -16,7 +16,7 @@ __all__ = [
     "zen_ctx_create", "zen_ctx_destroy", "zen_bitmap_layout", "zen_encode_workspace_bytes",
     "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
     "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
-    "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
+    "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "alloc_encoded", "alloc_aggregated", "alloc_workspace",
 ]
 
@@ -78,6 +78,7 @@ def load_library():
         "zen_aggregate_batch": [vp, C.POINTER(_Encoded), u32, C.POINTER(_Aggregated), u64, vp, u64, vp],
         "zen_status_fetch": [vp, vp, vp, C.POINTER(_StatusInfo)],
         "zen_hash_many": [vp, u64, u32, vp, vp],
+        "zen_calibration_copy": [vp, vp, u64, vp],
         "zen_profile_enable": [vp, u32, u32],
         "zen_profile_collect": [vp, u32, C.POINTER(C.c_double), C.POINTER(u32), C.POINTER(u32)],
     }
@@ -286,3 +287,10 @@ def zen_profile_collect(ctx):
     n = C.c_uint32()
     _check(load_library().zen_profile_collect(ctx.handle, 16, ms, cnt, C.byref(n)), "zen_profile_collect")
     return {zen_profile_kernel_name(k): (float(ms[k]), int(cnt[k])) for k in range(int(n.value)) if cnt[k]}
+
+
+def zen_calibration_copy(src, dst, stream=None):
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    return _check(load_library().zen_calibration_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)),
+                  "zen_calibration_copy")

@@ -446,6 +446,13 @@ const char *zen_profile_kernel_name(uint32_t kernel)
     return kernel < K_COUNT ? kKernelNames[kernel] : "";
 }
 
+zen_status zen_calibration_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream)
+{
+    if (!src || !dst || (bytes & 15u) || ((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u)) return ZEN_ERR_INVALID;
+    HIP_TRY(launch_copy(src, dst, bytes, (hipStream_t)hip_stream));
+    return ZEN_OK;
+}
+
 zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, void *hip_stream)
 {
     if (count && (!idx || !out)) return ZEN_ERR_INVALID;

@@ -529,6 +529,21 @@ __global__ void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v)
         p[i] = v;
 }
 
+// Plain streaming copy: the reference kernel against which hardware HBM byte counters are scaled.
+__global__ void __launch_bounds__(256) copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, uint64_t n_vec)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (uint64_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+hipError_t launch_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s)
+{
+    const uint64_t n_vec = bytes / 16;
+    if (n_vec == 0) return hipSuccess;
+    copy_kernel<<<16384, 256, 0, s>>>((const u32x4 *)src, (u32x4 *)dst, n_vec);
+    return hipGetLastError();
+}
+
 __global__ void hash_many_kernel(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out)
 {
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;

@@ -142,6 +142,7 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs
 hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
                                char *ws, const EncodeLayout &L, hipStream_t s);
 hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info *tmp_status, hipStream_t s);
+hipError_t launch_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s);
 hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s);
 
