@@ -177,7 +177,7 @@ zen_status zen_calibration_copy(const void *src, void *dst, uint64_t bytes, void
  * the method).  mode 0 = off, 1 = time the dense-scan (detect) kernel only, 2 = time every kernel.
  * max_records event pairs are created up front; launches beyond that are not timed.
  * zen_profile_collect waits for the recorded events, adds up milliseconds and launch counts per
- * kernel into host arrays of at least 16 entries (index = kernel id, name from
+ * kernel into host arrays of at least 32 entries (index = kernel id, name from
  * zen_profile_kernel_name), and empties the record pool.
  */
 zen_status zen_profile_enable(zen_ctx *ctx, uint32_t mode, uint32_t max_records);

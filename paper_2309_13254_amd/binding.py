@@ -282,10 +282,10 @@ def zen_profile_kernel_name(kernel):
 
 def zen_profile_collect(ctx):
     """-> {kernel name: (total ms, launches)} for the kernels timed since the last collect."""
-    ms = (C.c_double * 16)()
-    cnt = (C.c_uint32 * 16)()
+    ms = (C.c_double * 32)()
+    cnt = (C.c_uint32 * 32)()
     n = C.c_uint32()
-    _check(load_library().zen_profile_collect(ctx.handle, 16, ms, cnt, C.byref(n)), "zen_profile_collect")
+    _check(load_library().zen_profile_collect(ctx.handle, 32, ms, cnt, C.byref(n)), "zen_profile_collect")
     return {zen_profile_kernel_name(k): (float(ms[k]), int(cnt[k])) for k in range(int(n.value)) if cnt[k]}
 
 

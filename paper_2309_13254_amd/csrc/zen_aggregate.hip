@@ -640,8 +640,9 @@ agg_accum_kernel(PartIdx src, Arr64<const float *> src_values, uint32_t seed, ui
 // ----------------------------------------------------------------------------------------------
 static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
-AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows, bool decode)
+AggLayout aggregate_layout(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_rows)
 {
+    const bool decode = ctx->fmt == ZEN_INDEX_BITMAP;
     AggLayout L{};
     uint64_t cap = 1024;
     while (cap < 2 * max_in_rows) cap <<= 1;
@@ -664,8 +665,9 @@ AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_ro
         L.decode_stride = L.uniq_cap;
         off += align_up((uint64_t)batch * L.decode_stride * 4, 256);
         L.decflags_off = off; off += align_up((uint64_t)batch * ZEN_MAX_BATCH * 4, 256);
+        L.bm_chunks = bitmap_merge_chunks(ctx->max_dom_words);
+        L.bmcnt_off = off; off += align_up((uint64_t)batch * (ZEN_MAX_BATCH + 1) * L.bm_chunks * 4, 256);
     }
-    (void)g;
     L.total = off;
     return L;
 }
@@ -693,6 +695,15 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
     bool any_bitmap = false;
     for (uint32_t w = 0; w < n_in; ++w) any_bitmap |= (src.indices[w] == nullptr);
     if (any_bitmap && (!ctx->d_domain || !L.decode_stride)) return hipErrorInvalidValue;
+    bool all_bitmap = n_in > 0;
+    for (uint32_t w = 0; w < n_in; ++w) all_bitmap &= (src.indices[w] == nullptr && src_bitmap.v[w] != nullptr);
+    if (all_bitmap) {
+        // every part is a hash bitmap: merge in the bitmaps' own domain (OR + popcount ranks)
+        Arr64<const uint32_t *> bounds;
+        for (uint32_t w = 0; w < ZEN_MAX_BATCH; ++w) bounds.v[w] = src.bounds[w];
+        return launch_bitmap_merge(ctx, src_bitmap, bounds, src_values, n_in, src.single != 0, n_servers,
+                                   first_part_id, outs, out_values, ws, L, s);
+    }
 
     if (L.small_path) {
         uint32_t *dec_flags = any_bitmap ? (uint32_t *)(ws + L.decflags_off) : nullptr;

@@ -134,6 +134,7 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
                 h_woff32[p] = (uint32_t)w;
                 ctx->h_dom_sizes[p] = h_off[p + 1] - h_off[p];
                 w += (ctx->h_dom_sizes[p] + 31) / 32;
+                if ((ctx->h_dom_sizes[p] + 31) / 32 > ctx->max_dom_words) ctx->max_dom_words = (ctx->h_dom_sizes[p] + 31) / 32;
             }
             ctx->h_bm_word_off[n] = w;
             h_woff32[n] = (uint32_t)w;
@@ -190,7 +191,7 @@ zen_status zen_aggregate_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uin
 {
     if (!ctx || !host_bytes || batch == 0 || max_in_rows > 0x7FFFFFFFull) return ZEN_ERR_INVALID;
     const uint32_t b = batch > ZEN_MAX_BATCH ? ZEN_MAX_BATCH : batch;
-    *host_bytes = aggregate_layout(ctx->geo, b, max_in_rows, ctx->fmt == ZEN_INDEX_BITMAP).total;
+    *host_bytes = aggregate_layout(ctx, b, max_in_rows).total;
     return ZEN_OK;
 }
 
@@ -314,7 +315,7 @@ zen_status zen_aggregate(zen_ctx *ctx, const zen_part *host_parts, uint32_t n_in
         sb.v[w] = p.indices ? nullptr : p.bitmap;
     }
     if (any_bitmap && ctx->fmt != ZEN_INDEX_BITMAP) return ZEN_ERR_INVALID;   // no domain tables
-    const AggLayout L = aggregate_layout(ctx->geo, 1, max_in_rows, ctx->fmt == ZEN_INDEX_BITMAP);
+    const AggLayout L = aggregate_layout(ctx, 1, max_in_rows);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
     AggOut outs;
     Arr64<float *> ov;
@@ -356,7 +357,7 @@ zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint3
             return ZEN_ERR_INVALID;
     }
     const uint32_t group = g.n_parts < ZEN_MAX_BATCH ? g.n_parts : ZEN_MAX_BATCH;
-    const AggLayout L = aggregate_layout(g, group, max_in_rows, ctx->fmt == ZEN_INDEX_BITMAP);
+    const AggLayout L = aggregate_layout(ctx, group, max_in_rows);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
     if (g.n_parts > ZEN_MAX_BATCH) return ZEN_ERR_INVALID;   // one launch group per call for now
     AggOut outs;
@@ -390,7 +391,7 @@ static const char *const kKernelNames[K_COUNT] = {
     "detect_kernel", "partition_scan_kernel", "scatter_kernel", "agg_clear_kernel", "agg_insert_kernel",
     "agg_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
     "agg_finalize_kernel", "agg_zero_kernel", "agg_accum_kernel", "nonzero_list_kernels", "bitmap_decode_kernel",
-    "agg_gather_kernel"};
+    "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel"};
 
 static void prof_release(zen_ctx *ctx)
 {

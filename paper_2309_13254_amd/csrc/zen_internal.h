@@ -78,6 +78,8 @@ struct AggLayout {
     uint64_t decode_off;     // bitmap parts: per (server, part) decoded indices
     uint64_t decode_stride;
     uint64_t decflags_off;   // small path: per (server, part) decode consistency flag
+    uint64_t bmcnt_off;      // bitmap merge: per server (ZEN_MAX_BATCH+1) x bm_chunks u32
+    uint64_t bm_chunks;
     uint64_t table_cap;      // slots per server (power of two)
     uint32_t small_path;     // 1: one block per server sorts in LDS
     uint64_t total;
@@ -89,7 +91,7 @@ namespace zen {
 enum KernelId : uint32_t {
     K_DETECT = 0, K_PARTITION_SCAN, K_SCATTER, K_AGG_CLEAR, K_AGG_INSERT, K_AGG_SORT_SMALL, K_AGG_COMPACT,
     K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_ZERO, K_AGG_ACCUM, K_NONZERO_LIST, K_BITMAP_DECODE,
-    K_AGG_GATHER,
+    K_AGG_GATHER, K_BM_COUNT, K_BM_SCAN, K_BM_MERGE,
     K_COUNT
 };
 struct ProfRecord { hipEvent_t start, stop; uint32_t kernel; };
@@ -112,12 +114,19 @@ struct zen_ctx {
     uint64_t *h_bm_word_off;   // host copy
     uint64_t *h_dom_sizes;     // host copy
     uint64_t bm_total_words;
+    uint64_t max_dom_words;    // largest per-partition bitmap, in words
 };
 
 namespace zen {
 
 EncodeLayout encode_layout(const Geometry &g, uint32_t batch);
-AggLayout aggregate_layout(const Geometry &g, uint32_t batch, uint64_t max_in_rows, bool decode);
+AggLayout aggregate_layout(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_rows);
+uint64_t bitmap_merge_chunks(uint64_t max_dom_words);
+hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitmaps,
+                               const Arr64<const uint32_t *> &bounds, const Arr64<const float *> &src_values,
+                               uint32_t n_in, bool single, uint32_t n_servers, uint32_t first_part,
+                               const AggOut &outs, const Arr64<float *> &out_values, char *ws, const AggLayout &L,
+                               hipStream_t s);
 
 // encode launchers (zen_encode.hip)
 // Kernel timing: ProfScope records an event pair around a launch when the context asks for it.

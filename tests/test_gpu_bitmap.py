@@ -96,10 +96,13 @@ def test_bitmap_encode_then_aggregate(oracle, zen, cid):
         G.check_sums(val, ref)
 
 
-def test_single_server_bitmap_parts(oracle, zen):
+@pytest.mark.parametrize("mixed", [True, False])
+@pytest.mark.parametrize("D", [1, 4, 100])
+def test_single_server_bitmap_parts(oracle, zen, mixed, D):
     import gpu_util as G
 
-    R, D, n, seed = 20000, 4, 8, 99
+    # mixed: one COO part among the bitmaps -> decode + table path; else the bitmap-domain merge
+    R, n, seed = 20000, 8, 99
     ctx = zen.ZenContext(R, D, n, seed, zen.ZEN_INDEX_BITMAP)
     owner = oracle.owner_table(R, n, seed)
     dom_count, word_off = oracle.bitmap_layout(owner, n)
@@ -114,7 +117,7 @@ def test_single_server_bitmap_parts(oracle, zen):
         nz[rows] = 1
         bm = oracle.bitmap_encode(owner, n, nz, word_off)[int(word_off[part_id]):int(word_off[part_id + 1])]
         parts_h.append((rows, vals))
-        if w == 2:      # one part in COO form, mixed with bitmap parts
+        if w == 2 and mixed:      # one part in COO form, mixed with bitmap parts
             parts_d.append((G.to_dev(rows), None, torch.from_numpy(vals).cuda(),
                             torch.tensor([rows.size], dtype=torch.int32, device="cuda")))
         else:
