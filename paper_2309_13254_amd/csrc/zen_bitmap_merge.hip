@@ -44,11 +44,19 @@ bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off,
     if (threadIdx.x <= a.n_in) s_c[threadIdx.x] = 0;
     __syncthreads();
     uint32_t uni = 0;
-    for (uint32_t w = 0; w < a.n_in; ++w) {
-        const uint32_t word = k < n_words ? part_words(a, w, p, word_off)[k] : 0u;
-        uni |= word;
-        const uint32_t s = wave_sum(__popc(word));
-        if (lane_id() == 0 && s) atomicAdd(&s_c[w], s);
+    for (uint32_t w0 = 0; w0 < a.n_in; w0 += 8) {
+        uint32_t wd[8];
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q)
+            wd[q] = (w0 + q < a.n_in && k < n_words) ? part_words(a, w0 + q, p, word_off)[k] : 0u;
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) {
+            if (w0 + q >= a.n_in) break;
+            uni |= wd[q];
+            if (ballot(wd[q] != 0) == 0) continue;
+            const uint32_t s = wave_sum(__popc(wd[q]));
+            if (lane_id() == 0) atomicAdd(&s_c[w0 + q], s);
+        }
     }
     const uint32_t su = wave_sum(__popc(uni));
     if (lane_id() == 0 && su) atomicAdd(&s_c[a.n_in], su);
@@ -141,11 +149,18 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
         uint32_t *s_uex = s_uni + ZEN_WAVE;      // exclusive count of union bits before each word
         // pass A: union word and per-wave totals for every part
         uint32_t uni = 0;
-        for (uint32_t w = 0; w < n_in; ++w) {
-            const uint32_t word = k < n_words ? part_words(a, w, p, word_off)[k] : 0u;
-            uni |= word;
-            const uint32_t s = wave_sum(__popc(word));
-            if (lane == 0) s_wtot[w * 4 + wave] = s;
+        for (uint32_t w0 = 0; w0 < n_in; w0 += 8) {
+            uint32_t wd[8];
+#pragma unroll
+            for (uint32_t q = 0; q < 8; ++q)
+                wd[q] = (w0 + q < n_in && k < n_words) ? part_words(a, w0 + q, p, word_off)[k] : 0u;
+#pragma unroll
+            for (uint32_t q = 0; q < 8; ++q) {
+                if (w0 + q >= n_in) break;
+                uni |= wd[q];
+                const uint32_t s = wave_sum(__popc(wd[q]));
+                if (lane == 0) s_wtot[(w0 + q) * 4 + wave] = s;
+            }
         }
         const uint32_t uc = __popc(uni);
         const uint32_t uinc = wave_inclusive_scan(uc);
@@ -160,12 +175,20 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
         for (uint32_t i = lane; i < u_wave; i += ZEN_WAVE) acc[i] = 0.f;
         // pass B: every part adds its values, in part order; the wave walks the part's values (a
         // contiguous run) and finds each value's (word, bit) by searching the prefix tables
-        for (uint32_t w = 0; w < n_in; ++w) {
-            const uint32_t word = k < n_words ? part_words(a, w, p, word_off)[k] : 0u;
+        for (uint32_t w0 = 0; w0 < n_in; w0 += 8) {
+          uint32_t wd[8];
+#pragma unroll
+          for (uint32_t q = 0; q < 8; ++q)
+              wd[q] = (w0 + q < n_in && k < n_words) ? part_words(a, w0 + q, p, word_off)[k] : 0u;
+#pragma unroll
+          for (uint32_t q = 0; q < 8; ++q) {
+            const uint32_t w = w0 + q;
+            if (w >= n_in) break;
+            const uint32_t word = wd[q];
+            if (ballot(word != 0) == 0) continue;     // wave-uniform: the part has no row in these 64 words
             const uint32_t c = __popc(word);
             const uint32_t inc = wave_inclusive_scan(c);
             const uint32_t t_wave = __shfl(inc, ZEN_WAVE - 1, ZEN_WAVE);
-            if (t_wave == 0) continue;                // wave-uniform
             s_word[lane] = word;
             s_ex[lane] = inc - c;
             uint32_t vbase = pre[(uint64_t)w * n_chunks + chunk] + (a.single ? 0u : a.bounds[w][p]);
@@ -188,6 +211,7 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
                 acc[s_uex[lo] + __popc(s_uni[lo] & ((1u << pos) - 1u))] += vals[i];
             }
             __builtin_amdgcn_wave_barrier();
+          }
         }
         // write out the wave's output range: indices from the sorted domain, values from LDS
         const uint32_t k0 = chunk * BM_CHUNK_WORDS + wave * ZEN_WAVE;

@@ -51,7 +51,7 @@ __device__ __forceinline__ void detect_elem(const float *__restrict__ g, uint64_
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t c = c0 + u;
-            if (c < n_chunks) {
+            if (c < n_chunks && ballot(nonzero_mag(v[u]) != 0) != 0) {   // s_mask starts zeroed
                 uint32_t nib = ((v[u].x & 0x7fffffffu) ? 1u : 0u) | ((v[u].y & 0x7fffffffu) ? 2u : 0u) |
                                ((v[u].z & 0x7fffffffu) ? 4u : 0u) | ((v[u].w & 0x7fffffffu) ? 8u : 0u);
                 uint32_t word = nib << (4 * (lane & 7));
@@ -180,7 +180,7 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
         reset_status->flags = 0; reset_status->reserved = 0; reset_status->needed_rows = 0;
     }
     for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) s_hist[i] = 0;
-    if (PATH >= 7) {
+    if (PATH >= 7 || PATH == 0) {
         for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) s_mask[i] = 0;
         __syncthreads();
     }
@@ -194,11 +194,22 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
     uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
     for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) gmask[i] = s_mask[i];
 
-    // owner histogram of the tile's non-zero rows
-    for (uint32_t r = threadIdx.x; r < g.tile_rows; r += blockDim.x) {
-        if ((s_mask[r >> 5] >> (r & 31)) & 1u) {
-            const uint32_t p = owner_of((uint32_t)(row0 + r), g.seed, g.n_parts, g.pow2_mask);
-            atomicAdd(&s_hist[p], 1u);
+    // owner histogram of the tile's non-zero rows: walk the mask words, most of them are zero
+    if (g.tile_words >= blockDim.x) {
+        for (uint32_t wi = threadIdx.x; wi < g.tile_words; wi += blockDim.x) {
+            uint32_t word = s_mask[wi];
+            while (word) {
+                const uint32_t b = __ffs(word) - 1;
+                word &= word - 1;
+                atomicAdd(&s_hist[owner_of((uint32_t)(row0 + wi * 32 + b), g.seed, g.n_parts, g.pow2_mask)], 1u);
+            }
+        }
+    } else {
+        for (uint32_t r = threadIdx.x; r < g.tile_rows; r += blockDim.x) {
+            if ((s_mask[r >> 5] >> (r & 31)) & 1u) {
+                const uint32_t p = owner_of((uint32_t)(row0 + r), g.seed, g.n_parts, g.pow2_mask);
+                atomicAdd(&s_hist[p], 1u);
+            }
         }
     }
     __syncthreads();
@@ -287,6 +298,9 @@ struct BitmapTables {
     const uint32_t *word_off;   // [n_parts+1]
 };
 
+// ELEM = (row_dim == 1): values are single floats fetched ahead of the ranking loop; otherwise rows
+// are copied after it.  Two instantiations so that each keeps its own register budget.
+template <bool ELEM>
 __global__ void __launch_bounds__(SCATTER_THREADS)
 scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
@@ -364,8 +378,30 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 }
             }
             __syncthreads();
-            // (b) rank, write indices, set bitmap bits
-            for (uint32_t c = 0; c < total; c += blockDim.x) {
+            // (b) rank, write indices, set bitmap bits.  row_dim == 1: the value and the bitmap rank of
+            // up to PF chunks are fetched first so the barrier-paced ranking loop does not wait on them.
+            constexpr uint32_t PF = SEG_ROWS / SCATTER_THREADS;   // 8
+            const bool prefetch = ELEM;
+            float pf_val[PF];
+            uint32_t pf_bit[PF];
+            if (ELEM) {
+#pragma unroll
+                for (uint32_t q = 0; q < PF; ++q) {
+                    const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                    pf_val[q] = 0.f;
+                    pf_bit[q] = 0;
+                    if (i < total) {
+                        const uint32_t row = s_list[i];
+                        if (out_val) pf_val[q] = grad[row];
+                        if (bitmap) pf_bit[q] = bt.rank[row];
+                    }
+                }
+            }
+            // total <= SEG_ROWS: at most PF chunks when the block has SCATTER_THREADS threads
+#pragma unroll
+            for (uint32_t q = 0; q < PF; ++q) {
+                const uint32_t c = q * blockDim.x;
+                if (c >= total) break;                      // uniform
                 const uint32_t i = c + threadIdx.x;
                 const bool valid = i < total;
                 const uint32_t row = valid ? s_list[i] : 0u;
@@ -374,19 +410,19 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 if (valid) {
                     if (pos < cap) {
                         if (out_idx) out_idx[pos] = row;
-                        if (D == 1 && out_val) out_val[pos] = grad[row];
+                        if (ELEM && out_val) out_val[pos] = pf_val[q];
                         s_pos[i] = pos;
                     } else {
                         s_pos[i] = 0xFFFFFFFFu;
                     }
                     if (bitmap) {
-                        const uint32_t bit = bt.rank[row];
+                        const uint32_t bit = prefetch ? pf_bit[q] : bt.rank[row];
                         atomicOr(&s_bm[s_boff[p] + (bit >> 5) - (s_b0[p] >> 5)], 1u << (bit & 31));
                     }
                 }
             }
             // (c) copy rows (row_dim > 1)
-            if (D > 1 && out_val) {
+            if (!ELEM && out_val) {
                 __syncthreads();
                 if ((D & 3u) == 0 && D >= 256) {
                     // one wave copies two rows at a time, 8 x 16-byte loads in flight per lane
@@ -637,9 +673,14 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
     const uint32_t threads = scatter_threads(g);
     size_t words = (1 + threads / 64) * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
     if (g.bitmap) words += 3 * (size_t)g.n_parts + 1 + g.tile_words + 2 * (size_t)g.n_parts;
-    scatter_kernel<<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
-        g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
-        (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
+    if (g.row_dim == 1)
+        scatter_kernel<true><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
+            g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
+    else
+        scatter_kernel<false><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
+            g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
     return hipGetLastError();
 }
 
@@ -723,7 +764,7 @@ hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info
     memset(&grads, 0, sizeof(grads));
     BitmapTables bt{nullptr, nullptr, nullptr};
     const size_t words = 5 * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
-    scatter_kernel<<<dim3(scatter_grid_x(g, 1), 1), SCATTER_THREADS, words * 4, s>>>(
+    scatter_kernel<true><<<dim3(scatter_grid_x(g, 1), 1), SCATTER_THREADS, words * 4, s>>>(
         g, grads, outs, tmp_mask, 0, ctx->d_dom_tile_base, 0, bt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     domain_rank_kernel<<<4096, 256, 0, s>>>(g, ctx->d_domain, ctx->d_dom_offsets, ctx->d_rank);
