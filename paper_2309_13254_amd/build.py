@@ -19,7 +19,8 @@ FLAGS = [
 
 def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("ZEN_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -DZEN_DETECT_THREADS=512 for tuning runs
+    cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)

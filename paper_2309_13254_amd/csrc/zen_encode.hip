@@ -10,13 +10,29 @@
 
 namespace zen {
 
-static constexpr int DETECT_THREADS = 256;
+#ifndef ZEN_DETECT_THREADS
+#define ZEN_DETECT_THREADS 256
+#endif
+#ifndef ZEN_DETECT_NT
+#define ZEN_DETECT_NT 1
+#endif
+#ifndef ZEN_ROW_UNROLL
+#define ZEN_ROW_UNROLL 4
+#endif
+static constexpr int DETECT_THREADS = ZEN_DETECT_THREADS;
 static constexpr int SCATTER_THREADS = 256;
 static constexpr int SCAN_THREADS = 1024;
 static constexpr int SEG_WORDS = 64;              // mask words expanded per scatter segment
 static constexpr int SEG_ROWS = SEG_WORDS * 32;   // 2048
 
-__device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ u32x4 load_stream(const u32x4 *p)
+{
+#if ZEN_DETECT_NT
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
 
 // ----------------------------------------------------------------------------------------------
 // E1: detection.  Each variant fills s_mask[tile_words] (bit r%32 of word r/32, tile-relative).
@@ -112,7 +128,7 @@ __device__ __forceinline__ void detect_sub(const float *__restrict__ g, uint64_t
 template <int VEC>
 __device__ __forceinline__ uint32_t row_or(const float *__restrict__ row, uint32_t nvec, uint32_t lane)
 {
-    constexpr int U = 4;
+    constexpr int U = ZEN_ROW_UNROLL;
     uint32_t acc = 0;
     for (uint32_t k = lane; k < nvec; k += 64 * U) {
         if (VEC == 4) {
