@@ -102,6 +102,8 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
     memset(ctx, 0, sizeof(*ctx));
     make_geometry(ctx->geo, n_rows, row_dim, n_parts, hash_seed, fmt == ZEN_INDEX_BITMAP);
     ctx->fmt = fmt;
+    ctx->small_encode = 1;   // ZEN_ENCODE_SMALL=0 forces the tiled partition path (testing / tuning)
+    if (const char *e = getenv("ZEN_ENCODE_SMALL")) ctx->small_encode = atoi(e) != 0;
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return ZEN_ERR_DEVICE; }
     if (fmt == ZEN_INDEX_BITMAP) {
         // sorted hash domains, per-row ranks and per-tile rank bases, built once on the device
@@ -238,9 +240,14 @@ zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32
             outs.bitmap[i] = host_outs[w0 + i].bitmap;
             outs.cap_rows[i] = host_outs[w0 + i].cap_rows;
         }
-        HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, s));
-        HIP_TRY(launch_partition_scan(ctx, outs, nb, ws, L, s));
-        HIP_TRY(launch_scatter(ctx, grads, outs, nb, ws, L, s));
+        if (encode_small_applies(ctx, outs, nb)) {
+            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, false, s));
+            HIP_TRY(launch_encode_small(ctx, grads, outs, nb, ws, L, s));
+        } else {
+            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, true, s));
+            HIP_TRY(launch_partition_scan(ctx, outs, nb, ws, L, s));
+            HIP_TRY(launch_scatter(ctx, grads, outs, nb, ws, L, s));
+        }
     }
     return ZEN_OK;
 }
@@ -268,7 +275,7 @@ zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint6
     GradPtrs grads;
     memset(&grads, 0, sizeof(grads));
     grads.p[0] = grad;
-    HIP_TRY(launch_detect(ctx, grads, 1, ws, L, true, s));
+    HIP_TRY(launch_detect(ctx, grads, 1, ws, L, true, true, s));
     HIP_TRY(launch_nonzero_list(ctx, indices, cap_rows, count, ws, L, s));
     return ZEN_OK;
 }
@@ -391,7 +398,7 @@ static const char *const kKernelNames[K_COUNT] = {
     "detect_kernel", "partition_scan_kernel", "scatter_kernel", "agg_clear_kernel", "agg_insert_kernel",
     "agg_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
     "agg_finalize_kernel", "agg_zero_kernel", "agg_accum_kernel", "nonzero_list_kernels", "bitmap_decode_kernel",
-    "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel"};
+    "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel", "encode_small_kernel", "gather_rows_kernel"};
 
 static void prof_release(zen_ctx *ctx)
 {

@@ -210,6 +210,7 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
     uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
     for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) gmask[i] = s_mask[i];
 
+    if (!hist_base) return;   // the one-block-per-worker partition path hashes the rows itself
     // owner histogram of the tile's non-zero rows: walk the mask words, most of them are zero
     if (g.tile_words >= blockDim.x) {
         for (uint32_t wi = threadIdx.x; wi < g.tile_words; wi += blockDim.x) {
@@ -623,12 +624,12 @@ hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, 
 }
 
 hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
-                         const EncodeLayout &L, bool reset_status, hipStream_t s)
+                         const EncodeLayout &L, bool reset_status, bool want_hist, hipStream_t s)
 {
     const Geometry &g = ctx->geo;
     const size_t lds = (size_t)(g.tile_words + g.n_parts) * 4;
     ProfScope prof(ctx, K_DETECT, s);
-    uint32_t *mask = (uint32_t *)(ws + L.mask_off), *hist = (uint32_t *)(ws + L.hist_off);
+    uint32_t *mask = (uint32_t *)(ws + L.mask_off), *hist = want_hist ? (uint32_t *)(ws + L.hist_off) : nullptr;
     zen_status_info *rs = reset_status ? (zen_status_info *)(ws + L.status_off) : nullptr;
     const dim3 grid(g.n_tiles, batch);
     int path;
@@ -698,6 +699,211 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
             g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
             (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
     return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// Few non-zero rows (output capacity <= ESMALL_MAX_ROWS and a mask one block can walk): the whole
+// E2-E5 of a worker runs in ONE block -- compact the mask to an ascending row list in LDS, histogram
+// the owners, scan, rank stably, write offsets and indices -- and the rows are then copied by a
+// separate launch with one wave per output row, so that a run of dense tiles cannot become one
+// block's long pole.  Results are identical to the tiled path.
+// ----------------------------------------------------------------------------------------------
+static constexpr int ESMALL_THREADS = 1024;
+static constexpr uint32_t ESMALL_MAX_ROWS = 16384;
+static constexpr uint32_t ESMALL_MAX_WORDS = 16384;   // mask words (x32 rows) one block walks in <= 16 rounds
+
+__global__ void __launch_bounds__(ESMALL_THREADS)
+encode_small_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
+                    uint64_t mask_stride_words, uint32_t list_cap, BitmapTables bt, zen_status_info *status)
+{
+    extern __shared__ uint32_t smem[];
+    const uint32_t n = g.n_parts, n_waves = blockDim.x >> 6;
+    uint32_t *s_hist = smem;                     // [n]
+    uint32_t *s_run = s_hist + n;                // [n]
+    uint32_t *s_cnt = s_run + n;                 // [n_waves][n]
+    uint32_t *s_list = s_cnt + n_waves * n;      // [list_cap]
+    uint32_t *s_tmp = s_list + list_cap;         // [32]
+    const uint32_t worker = blockIdx.x;
+    const uint32_t *gmask = mask_base + worker * mask_stride_words;
+    const uint32_t n_words = g.n_tiles * g.tile_words;
+    const float *__restrict__ grad = grads.p[worker];
+    uint32_t *__restrict__ out_idx = outs.indices[worker];
+    float *__restrict__ out_val = outs.values[worker];
+    uint32_t *__restrict__ out_bm = g.bitmap ? outs.bitmap[worker] : nullptr;
+    const uint64_t cap = outs.cap_rows[worker];
+
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_hist[i] = 0;
+    for (uint32_t i = threadIdx.x; i < n_waves * n; i += blockDim.x) s_cnt[i] = 0;
+    __syncthreads();
+    // E2 + E3: ascending row list and owner histogram
+    uint32_t total = 0;
+    for (uint32_t w0 = 0; w0 < n_words; w0 += blockDim.x) {
+        const uint32_t wi = w0 + threadIdx.x;
+        uint32_t word = wi < n_words ? gmask[wi] : 0u;
+        uint32_t chunk_total;
+        const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &chunk_total);
+        uint32_t k = total + pre;
+        while (word) {
+            const uint32_t b = __ffs(word) - 1;
+            word &= word - 1;
+            const uint32_t row = wi * 32 + b;
+            atomicAdd(&s_hist[owner_of(row, g.seed, n, g.pow2_mask)], 1u);
+            if (k < list_cap) s_list[k] = row;
+            ++k;
+        }
+        total += chunk_total;
+    }
+    __syncthreads();
+    // E4: offsets
+    uint32_t unused;
+    const uint32_t off = block_exclusive_scan(threadIdx.x < n ? s_hist[threadIdx.x] : 0u, s_tmp, &unused);
+    if (threadIdx.x < n) {
+        s_run[threadIdx.x] = off;
+        outs.offsets[worker][threadIdx.x] = off;
+    }
+    if (threadIdx.x == 0) {
+        outs.offsets[worker][n] = total;
+        if ((uint64_t)total > cap) {
+            atomicOr(&status->flags, 1u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)total);
+        }
+    }
+    __syncthreads();
+    // E5 (+E7): stable rank inside each partition, indices, element values, bitmap bits.  The list
+    // holds every row unless the gradient has more non-zero rows than the list (then the output
+    // capacity is exceeded too): in that case the mask is walked again in 64-word segments.
+    const bool fits = total <= list_cap;
+    const uint32_t n_rounds = fits ? 1u : (n_words + SEG_WORDS - 1) / SEG_WORDS;
+    for (uint32_t round = 0; round < n_rounds; ++round) {
+        uint32_t listed = total;
+        if (!fits) {
+            const uint32_t wi = round * SEG_WORDS + threadIdx.x;
+            uint32_t word = (threadIdx.x < SEG_WORDS && wi < n_words) ? gmask[wi] : 0u;
+            const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &listed);
+            uint32_t k = pre;
+            while (word) {
+                const uint32_t b = __ffs(word) - 1;
+                word &= word - 1;
+                s_list[k++] = wi * 32 + b;      // list_cap >= SEG_ROWS
+            }
+            __syncthreads();
+        }
+        for (uint32_t c = 0; c < listed; c += blockDim.x) {
+            const uint32_t i = c + threadIdx.x;
+            const bool valid = i < listed;
+            const uint32_t row = valid ? s_list[i] : 0u;
+            const uint32_t p = valid ? owner_of(row, g.seed, n, g.pow2_mask) : 0u;
+            const uint32_t pos = block_stable_rank(valid, p, g.part_bits, n, s_run, s_cnt);
+            if (valid) {
+                if (pos < cap) {
+                    out_idx[pos] = row;
+                    if (g.row_dim == 1 && out_val) out_val[pos] = grad[row];
+                }
+                if (out_bm) {
+                    const uint32_t bit = bt.rank[row];
+                    atomicOr(out_bm + bt.word_off[p] + (bit >> 5), 1u << (bit & 31));
+                }
+            }
+        }
+        __syncthreads();   // the list is rewritten by the next round
+    }
+}
+
+// E6 on its own: values[pos] = grad[indices[pos]] for pos < min(nnz, capacity); one wave per row
+// (wide rows) or one thread per 16 bytes / per element (narrow rows).
+__global__ void __launch_bounds__(256)
+gather_rows_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs)
+{
+    const uint32_t worker = blockIdx.y, D = g.row_dim;
+    const float *__restrict__ grad = grads.p[worker];
+    const uint32_t *__restrict__ idx = outs.indices[worker];
+    float *__restrict__ out_val = outs.values[worker];
+    const uint32_t nnz = outs.offsets[worker][g.n_parts];
+    const uint32_t rows = (uint64_t)nnz < outs.cap_rows[worker] ? nnz : (uint32_t)outs.cap_rows[worker];
+    if ((D & 3u) == 0 && D >= 256) {
+        const uint32_t V = D >> 2, lane = lane_id(), nw = blockDim.x >> 6;
+        for (uint32_t pos = blockIdx.x * nw + (threadIdx.x >> 6); pos < rows; pos += gridDim.x * nw) {
+            const u32x4 *src = (const u32x4 *)(grad + (uint64_t)idx[pos] * D);
+            u32x4 *dst = (u32x4 *)(out_val + (uint64_t)pos * D);
+            for (uint32_t v = lane; v < V; v += 64 * 4) {
+                u32x4 x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (v + 64 * u < V) x[u] = src[v + 64 * u];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (v + 64 * u < V) dst[v + 64 * u] = x[u];
+            }
+        }
+    } else if ((D & 3u) == 0) {
+        const uint32_t V = D >> 2;
+        const uint64_t n_vec = (uint64_t)rows * V;
+        for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_vec;
+             f += (uint64_t)gridDim.x * blockDim.x) {
+            const uint32_t pos = (uint32_t)(f / V), v = (uint32_t)(f - (uint64_t)pos * V);
+            ((u32x4 *)(out_val + (uint64_t)pos * D))[v] = ((const u32x4 *)(grad + (uint64_t)idx[pos] * D))[v];
+        }
+    } else {
+        const uint64_t n_el = (uint64_t)rows * D;
+        for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_el;
+             f += (uint64_t)gridDim.x * blockDim.x) {
+            const uint32_t pos = (uint32_t)(f / D), v = (uint32_t)(f - (uint64_t)pos * D);
+            out_val[(uint64_t)pos * D + v] = grad[(uint64_t)idx[pos] * D + v];
+        }
+    }
+}
+
+bool encode_small_applies(const zen_ctx *ctx, const EncodedPtrs &outs, uint32_t batch)
+{
+    const Geometry &g = ctx->geo;
+    if (!ctx->small_encode || (uint64_t)g.n_tiles * g.tile_words > ESMALL_MAX_WORDS) return false;
+    for (uint32_t w = 0; w < batch; ++w)
+        if (!outs.indices[w] || outs.cap_rows[w] > ESMALL_MAX_ROWS) return false;
+    return true;
+}
+
+hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs, uint32_t batch,
+                               char *ws, const EncodeLayout &L, hipStream_t s)
+{
+    const Geometry &g = ctx->geo;
+    BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off};
+    uint64_t max_cap = 1;
+    for (uint32_t w = 0; w < batch; ++w) {
+        if (outs.cap_rows[w] > max_cap) max_cap = outs.cap_rows[w];
+        if (g.bitmap && outs.bitmap[w]) {
+            hipError_t e = launch_fill_u32(outs.bitmap[w], ctx->bm_total_words, 0u, s);
+            if (e != hipSuccess) return e;
+        }
+    }
+    uint32_t list_cap = SEG_ROWS;
+    while (list_cap < max_cap) list_cap <<= 1;
+    const size_t lds = ((size_t)(2 + ESMALL_THREADS / 64) * g.n_parts + list_cap + 32) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)encode_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)(((size_t)18 * ZEN_MAX_PARTS + ESMALL_MAX_ROWS + 32) * 4));
+        (void)hipGetLastError();
+        attr_set = true;
+    }
+    {
+        ProfScope prof(ctx, K_ENCODE_SMALL, s);
+        encode_small_kernel<<<batch, ESMALL_THREADS, lds, s>>>(g, grads, outs, (const uint32_t *)(ws + L.mask_off),
+                                                              L.mask_stride / 4, list_cap, bt,
+                                                              (zen_status_info *)(ws + L.status_off));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (g.row_dim > 1) {
+        uint64_t gx;
+        if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) gx = (max_cap + 3) / 4;
+        else gx = (max_cap * g.row_dim / 4 + 255) / 256;
+        if (gx < 1) gx = 1;
+        if (gx > 8192) gx = 8192;
+        ProfScope prof(ctx, K_GATHER_ROWS, s);
+        gather_rows_kernel<<<dim3((uint32_t)gx, batch), 256, 0, s>>>(g, grads, outs);
+        return hipGetLastError();
+    }
+    return hipSuccess;
 }
 
 // ----------------------------------------------------------------------------------------------

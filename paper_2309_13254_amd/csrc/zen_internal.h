@@ -91,7 +91,7 @@ namespace zen {
 enum KernelId : uint32_t {
     K_DETECT = 0, K_PARTITION_SCAN, K_SCATTER, K_AGG_CLEAR, K_AGG_INSERT, K_AGG_SORT_SMALL, K_AGG_COMPACT,
     K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_ZERO, K_AGG_ACCUM, K_NONZERO_LIST, K_BITMAP_DECODE,
-    K_AGG_GATHER, K_BM_COUNT, K_BM_SCAN, K_BM_MERGE,
+    K_AGG_GATHER, K_BM_COUNT, K_BM_SCAN, K_BM_MERGE, K_ENCODE_SMALL, K_GATHER_ROWS,
     K_COUNT
 };
 struct ProfRecord { hipEvent_t start, stop; uint32_t kernel; };
@@ -115,6 +115,7 @@ struct zen_ctx {
     uint64_t *h_dom_sizes;     // host copy
     uint64_t bm_total_words;
     uint64_t max_dom_words;    // largest per-partition bitmap, in words
+    uint32_t small_encode;     // 1: few-row encodes take the one-block-per-worker partition path
 };
 
 namespace zen {
@@ -143,7 +144,10 @@ struct ProfScope {
 };
 
 hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
-                         const EncodeLayout &L, bool reset_status, hipStream_t s);
+                         const EncodeLayout &L, bool reset_status, bool want_hist, hipStream_t s);
+bool encode_small_applies(const zen_ctx *ctx, const EncodedPtrs &outs, uint32_t batch);
+hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs, uint32_t batch,
+                               char *ws, const EncodeLayout &L, hipStream_t s);
 hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t batch, char *ws,
                                  const EncodeLayout &L, hipStream_t s);
 hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs,

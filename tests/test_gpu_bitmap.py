@@ -1,5 +1,7 @@
 """GPU parity of the hash-bitmap index format (Algorithm 2) against the CPU oracle: layout, encode
 (bit-exact bitmap words), decode inside zen_aggregate, and the clustered-runs workload."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -7,6 +9,14 @@ import torch
 from workloads import MINI_WORKLOADS, Workload, worker_sparse, dense_from_sparse
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True, params=["small", "tiled"])
+def partition_path(request, monkeypatch):
+    """Run every test through both partition paths: the one-block-per-worker path that few-row
+    encodes take by default, and the tiled histogram / scan / scatter path."""
+    monkeypatch.setenv("ZEN_ENCODE_SMALL", "1" if request.param == "small" else "0")
+    return request.param
 
 
 @pytest.fixture(scope="module")

@@ -2,6 +2,8 @@
 
 Bit-exact on offsets, indices and values (the values are copies).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -9,6 +11,14 @@ import torch
 from workloads import MINI_WORKLOADS, Workload, worker_sparse, dense_from_sparse
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True, params=["small", "tiled"])
+def partition_path(request, monkeypatch):
+    """Run every test through both partition paths: the one-block-per-worker path that few-row
+    encodes take by default, and the tiled histogram / scan / scatter path."""
+    monkeypatch.setenv("ZEN_ENCODE_SMALL", "1" if request.param == "small" else "0")
+    return request.param
 
 
 @pytest.fixture(scope="module")
