@@ -47,6 +47,7 @@ static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32
         if (g.tile_rows > 2048) g.tile_rows = 2048;
     }
     g.tile_words = g.tile_rows / 32;
+    g.sparse_mask = g.mode == MODE_ELEM ? 1u : 0u;
     g.n_tiles = (uint32_t)((n_rows + g.tile_rows - 1) / g.tile_rows);
 }
 
@@ -59,6 +60,8 @@ EncodeLayout encode_layout(const Geometry &g, uint32_t batch)
     L.mask_off = off; off += L.mask_stride * batch;
     L.hist_stride = align_up((uint64_t)g.n_tiles * g.n_parts * 4, 256);
     L.hist_off = off; off += L.hist_stride * batch;
+    L.flag_stride = align_up((uint64_t)g.n_tiles * 4, 256);
+    L.flag_off = off; off += L.flag_stride * batch;
     L.total = off;
     return L;
 }
@@ -121,7 +124,7 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
         ok = ok && hipMalloc(&ctx->d_dom_offsets, (n + 1) * 4) == hipSuccess;
         ok = ok && hipMalloc(&ctx->d_bm_word_off, (n + 1) * 4) == hipSuccess;
         ok = ok && hipMalloc(&ctx->d_dom_tile_base, ((uint64_t)g.n_tiles + 1) * n * 4) == hipSuccess;
-        ok = ok && hipMalloc(&tmp_mask, (uint64_t)g.n_tiles * g.tile_words * 4) == hipSuccess;
+        ok = ok && hipMalloc(&tmp_mask, ((uint64_t)g.n_tiles * g.tile_words + g.n_tiles) * 4) == hipSuccess;   // mask + tile flags
         ok = ok && hipMalloc(&tmp_status, 256) == hipSuccess;
         zen_status st = ok ? ZEN_OK : ZEN_ERR_NOMEM;
         if (ok) {

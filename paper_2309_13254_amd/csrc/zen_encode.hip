@@ -183,7 +183,8 @@ __device__ __forceinline__ void detect_row(const float *__restrict__ g, uint64_t
 template <int PATH>
 __global__ void __launch_bounds__(DETECT_THREADS)
 detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
-              uint32_t *hist_base, uint64_t hist_stride_words, zen_status_info *reset_status)
+              uint32_t *hist_base, uint64_t hist_stride_words, uint32_t *tflag_base, uint64_t tflag_stride,
+              zen_status_info *reset_status)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *s_mask = smem;                  // [tile_words]
@@ -207,9 +208,20 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
     else detect_row<1>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
     __syncthreads();
 
+    // Tile flag: 1 iff the tile holds a non-zero row.  Mask words and histogram rows of empty tiles
+    // are NOT written (every consumer looks at the flag first): for sparse inputs that removes most
+    // of the write traffic, which costs the streaming read far more than its byte share.
+    // Used where a tile has many mask words (element-level inputs); elsewhere the mask itself is
+    // as small as a flag array would be and everything is always written.
+    if (g.sparse_mask) {
+        uint32_t any = 0;
+        for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= s_mask[i];
+        const int flag = __syncthreads_or((int)(any != 0));
+        if (threadIdx.x == 0) tflag_base[worker * tflag_stride + tile] = flag ? 1u : 0u;
+        if (!flag) return;
+    }
     uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
     for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) gmask[i] = s_mask[i];
-
     if (!hist_base) return;   // the one-block-per-worker partition path hashes the rows itself
     // owner histogram of the tile's non-zero rows: walk the mask words, most of them are zero
     if (g.tile_words >= blockDim.x) {
@@ -241,13 +253,14 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(SCAN_THREADS)
 partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_t hist_stride_words,
-                      zen_status_info *status)
+                      const uint32_t *tflag_base, uint64_t tflag_stride, zen_status_info *status)
 {
     __shared__ uint32_t s_part[SCAN_THREADS];   // [grp][p] partial sums
     __shared__ uint32_t s_off[ZEN_MAX_PARTS + 1];
     __shared__ uint32_t s_tmp[32];
     const uint32_t worker = blockIdx.x;
     uint32_t *hist = hist_base + worker * hist_stride_words;
+    const uint32_t *tflag = tflag_base + worker * tflag_stride;   // rows of empty tiles are undefined
     const uint32_t n = g.n_parts;
     const uint32_t n_groups = SCAN_THREADS / n;   // >= 1 since n <= 1024
     const uint32_t p = threadIdx.x % n, grp = threadIdx.x / n;
@@ -257,7 +270,8 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
     const uint32_t t1 = active ? min(t0 + per, g.n_tiles) : 0;
 
     uint32_t sum = 0;
-    for (uint32_t t = t0; t < t1; ++t) sum += hist[(uint64_t)t * n + p];
+    for (uint32_t t = t0; t < t1; ++t)
+        if (!g.sparse_mask || tflag[t]) sum += hist[(uint64_t)t * n + p];
     if (active) s_part[grp * n + p] = sum;
     __syncthreads();
     // exclusive scan over groups for each p (Hillis-Steele along the group axis, all p at once)
@@ -290,6 +304,7 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
     if (active) {
         uint32_t run = s_off[p] + my_prefix;
         for (uint32_t t = t0; t < t1; ++t) {
+            if (g.sparse_mask && !tflag[t]) continue;
             const uint64_t a = (uint64_t)t * n + p;
             const uint32_t h = hist[a];
             hist[a] = run;
@@ -321,7 +336,7 @@ template <bool ELEM>
 __global__ void __launch_bounds__(SCATTER_THREADS)
 scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
-               BitmapTables bt)
+               const uint32_t *tflag_base, uint64_t tflag_stride, BitmapTables bt)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t n = g.n_parts, D = g.row_dim;
@@ -347,9 +362,15 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 
     for (uint32_t tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
         const uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
-        uint32_t any = 0;
-        for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= gmask[i];
-        if (!__syncthreads_or((int)(any != 0))) continue;     // empty tile (also the barrier between tiles)
+        if (ELEM) {   // element-level inputs carry per-tile flags (sparse_mask)
+            const uint32_t flag = tflag_base[worker * tflag_stride + tile];
+            __syncthreads();                                   // the barrier between tiles
+            if (!flag) continue;                               // empty tile: its mask words were never written
+        } else {
+            uint32_t any = 0;
+            for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= gmask[i];
+            if (!__syncthreads_or((int)(any != 0))) continue;  // empty tile (also the barrier between tiles)
+        }
 
         const uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * n;
         const uint64_t row0 = (uint64_t)tile * g.tile_rows;
@@ -515,11 +536,12 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 // E2 on its own: ascending list of non-zero rows from the mask (zen_nonzero).  The scan kernel has
 // turned hist into bases, so with n_parts = 1 geometry hist[tile][0] is the tile's output position.
 __global__ void __launch_bounds__(SCATTER_THREADS)
-nonzero_list_kernel(Geometry g, const uint32_t *gmask_base, const uint32_t *tile_base, uint32_t *indices,
-                    uint64_t cap_rows)
+nonzero_list_kernel(Geometry g, const uint32_t *gmask_base, const uint32_t *tflag, const uint32_t *tile_base,
+                    uint32_t *indices, uint64_t cap_rows)
 {
     __shared__ uint32_t s_tmp[32];
     const uint32_t tile = blockIdx.x;
+    if (g.sparse_mask && !tflag[tile]) return;
     const uint32_t *gmask = gmask_base + (uint64_t)tile * g.tile_words;
     uint32_t run = tile_base[tile];
     const uint64_t row0 = (uint64_t)tile * g.tile_rows;
@@ -564,13 +586,14 @@ tile_scan_kernel(uint32_t *tile_cnt, uint32_t n_tiles, uint32_t *count, uint64_t
 
 // Per-tile popcount of the mask (n_parts-independent), used by zen_nonzero.
 __global__ void __launch_bounds__(256)
-tile_popcount_kernel(Geometry g, const uint32_t *gmask_base, uint32_t *tile_cnt)
+tile_popcount_kernel(Geometry g, const uint32_t *gmask_base, const uint32_t *tflag, uint32_t *tile_cnt)
 {
     __shared__ uint32_t s_tmp[32];
     const uint32_t tile = blockIdx.x;
     const uint32_t *gmask = gmask_base + (uint64_t)tile * g.tile_words;
     uint32_t c = 0;
-    for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) c += __popc(gmask[i]);
+    if (!g.sparse_mask || tflag[tile])
+        for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) c += __popc(gmask[i]);
     uint32_t total;
     block_exclusive_scan(c, s_tmp, &total);
     if (threadIdx.x == 0) tile_cnt[tile] = total;
@@ -631,6 +654,7 @@ hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, ch
     ProfScope prof(ctx, K_DETECT, s);
     uint32_t *mask = (uint32_t *)(ws + L.mask_off), *hist = want_hist ? (uint32_t *)(ws + L.hist_off) : nullptr;
     zen_status_info *rs = reset_status ? (zen_status_info *)(ws + L.status_off) : nullptr;
+    uint32_t *tflag = (uint32_t *)(ws + L.flag_off);
     const dim3 grid(g.n_tiles, batch);
     int path;
     if (g.mode == MODE_ELEM) path = 0;
@@ -639,7 +663,7 @@ hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, ch
 #define ZEN_DETECT_CASE(P)                                                                                 \
     case P:                                                                                                \
         detect_kernel<P><<<grid, DETECT_THREADS, lds, s>>>(g, grads, mask, L.mask_stride / 4, hist,        \
-                                                          L.hist_stride / 4, rs);                          \
+                                                          L.hist_stride / 4, tflag, L.flag_stride / 4, rs); \
         break;
     switch (path) {
         ZEN_DETECT_CASE(0) ZEN_DETECT_CASE(1) ZEN_DETECT_CASE(2) ZEN_DETECT_CASE(3) ZEN_DETECT_CASE(4)
@@ -655,8 +679,8 @@ hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t
     const Geometry &g = ctx->geo;
     ProfScope prof(ctx, K_PARTITION_SCAN, s);
     partition_scan_kernel<<<batch, SCAN_THREADS, 0, s>>>(g, outs, (uint32_t *)(ws + L.hist_off),
-                                                         L.hist_stride / 4,
-                                                         (zen_status_info *)(ws + L.status_off));
+                                                         L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
+                                                         L.flag_stride / 4, (zen_status_info *)(ws + L.status_off));
     return hipGetLastError();
 }
 
@@ -693,11 +717,13 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
     if (g.row_dim == 1)
         scatter_kernel<true><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
             g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
-            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
+            L.flag_stride / 4, bt);
     else
         scatter_kernel<false><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
             g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
-            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, bt);
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
+            L.flag_stride / 4, bt);
     return hipGetLastError();
 }
 
@@ -714,7 +740,8 @@ static constexpr uint32_t ESMALL_MAX_WORDS = 16384;   // mask words (x32 rows) o
 
 __global__ void __launch_bounds__(ESMALL_THREADS)
 encode_small_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
-                    uint64_t mask_stride_words, uint32_t list_cap, BitmapTables bt, zen_status_info *status)
+                    uint64_t mask_stride_words, const uint32_t *tflag_base, uint64_t tflag_stride,
+                    uint32_t list_cap, BitmapTables bt, zen_status_info *status)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t n = g.n_parts, n_waves = blockDim.x >> 6;
@@ -725,6 +752,7 @@ encode_small_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t
     uint32_t *s_tmp = s_list + list_cap;         // [32]
     const uint32_t worker = blockIdx.x;
     const uint32_t *gmask = mask_base + worker * mask_stride_words;
+    const uint32_t *tflag = tflag_base + worker * tflag_stride;   // mask words of empty tiles are undefined
     const uint32_t n_words = g.n_tiles * g.tile_words;
     const float *__restrict__ grad = grads.p[worker];
     uint32_t *__restrict__ out_idx = outs.indices[worker];
@@ -739,7 +767,7 @@ encode_small_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t
     uint32_t total = 0;
     for (uint32_t w0 = 0; w0 < n_words; w0 += blockDim.x) {
         const uint32_t wi = w0 + threadIdx.x;
-        uint32_t word = wi < n_words ? gmask[wi] : 0u;
+        uint32_t word = (wi < n_words && (!g.sparse_mask || tflag[wi / g.tile_words])) ? gmask[wi] : 0u;
         uint32_t chunk_total;
         const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &chunk_total);
         uint32_t k = total + pre;
@@ -778,7 +806,7 @@ encode_small_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t
         uint32_t listed = total;
         if (!fits) {
             const uint32_t wi = round * SEG_WORDS + threadIdx.x;
-            uint32_t word = (threadIdx.x < SEG_WORDS && wi < n_words) ? gmask[wi] : 0u;
+            uint32_t word = (threadIdx.x < SEG_WORDS && wi < n_words && (!g.sparse_mask || tflag[wi / g.tile_words])) ? gmask[wi] : 0u;
             const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &listed);
             uint32_t k = pre;
             while (word) {
@@ -888,7 +916,8 @@ hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const Encode
     {
         ProfScope prof(ctx, K_ENCODE_SMALL, s);
         encode_small_kernel<<<batch, ESMALL_THREADS, lds, s>>>(g, grads, outs, (const uint32_t *)(ws + L.mask_off),
-                                                              L.mask_stride / 4, list_cap, bt,
+                                                              L.mask_stride / 4, (const uint32_t *)(ws + L.flag_off),
+                                                              L.flag_stride / 4, list_cap, bt,
                                                               (zen_status_info *)(ws + L.status_off));
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -923,7 +952,7 @@ __global__ void ones_mask_kernel(uint32_t *mask, uint64_t n_words, uint64_t n_ro
 }
 
 __global__ void __launch_bounds__(DETECT_THREADS)
-hist_from_mask_kernel(Geometry g, const uint32_t *mask, uint32_t *hist)
+hist_from_mask_kernel(Geometry g, const uint32_t *mask, uint32_t *hist, uint32_t *tflag)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *s_hist = smem;
@@ -937,6 +966,7 @@ hist_from_mask_kernel(Geometry g, const uint32_t *mask, uint32_t *hist)
             atomicAdd(&s_hist[owner_of((uint32_t)(row0 + r), g.seed, g.n_parts, g.pow2_mask)], 1u);
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) hist[(uint64_t)tile * g.n_parts + i] = s_hist[i];
+    if (threadIdx.x == 0) tflag[tile] = 1u;   // every tile of the all-rows mask holds rows
 }
 
 // rank[domain[pos]] = pos - dom_offsets[owner]
@@ -973,21 +1003,22 @@ hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info
         tmp_mask, n_words, g.n_rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hist_from_mask_kernel<<<g.n_tiles, DETECT_THREADS, g.n_parts * 4, s>>>(g, tmp_mask, ctx->d_dom_tile_base);
+    uint32_t *tflag = tmp_mask + n_words;   // the caller allocates n_tiles flag words behind the mask
+    hist_from_mask_kernel<<<g.n_tiles, DETECT_THREADS, g.n_parts * 4, s>>>(g, tmp_mask, ctx->d_dom_tile_base, tflag);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     EncodedPtrs outs;
     memset(&outs, 0, sizeof(outs));
     outs.offsets[0] = ctx->d_dom_offsets;
     outs.indices[0] = ctx->d_domain;
     outs.cap_rows[0] = g.n_rows;
-    partition_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(g, outs, ctx->d_dom_tile_base, 0, tmp_status);
+    partition_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(g, outs, ctx->d_dom_tile_base, 0, tflag, 0, tmp_status);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     GradPtrs grads;
     memset(&grads, 0, sizeof(grads));
     BitmapTables bt{nullptr, nullptr, nullptr};
     const size_t words = 5 * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
     scatter_kernel<true><<<dim3(scatter_grid_x(g, 1), 1), SCATTER_THREADS, words * 4, s>>>(
-        g, grads, outs, tmp_mask, 0, ctx->d_dom_tile_base, 0, bt);
+        g, grads, outs, tmp_mask, 0, ctx->d_dom_tile_base, 0, tflag, 0, bt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     domain_rank_kernel<<<4096, 256, 0, s>>>(g, ctx->d_domain, ctx->d_dom_offsets, ctx->d_rank);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1002,14 +1033,15 @@ hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_row
     ProfScope prof(ctx, K_NONZERO_LIST, s);
     uint32_t *mask = (uint32_t *)(ws + L.mask_off);
     uint32_t *tile_cnt = (uint32_t *)(ws + L.hist_off);   // reused: n_tiles words fit (n_parts >= 1)
-    tile_popcount_kernel<<<g.n_tiles, 256, 0, s>>>(g, mask, tile_cnt);
+    const uint32_t *tflag = (const uint32_t *)(ws + L.flag_off);
+    tile_popcount_kernel<<<g.n_tiles, 256, 0, s>>>(g, mask, tflag, tile_cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     tile_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(tile_cnt, g.n_tiles, count, cap_rows,
                                                 (zen_status_info *)(ws + L.status_off));
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    nonzero_list_kernel<<<g.n_tiles, SCATTER_THREADS, 0, s>>>(g, mask, tile_cnt, indices, cap_rows);
+    nonzero_list_kernel<<<g.n_tiles, SCATTER_THREADS, 0, s>>>(g, mask, tflag, tile_cnt, indices, cap_rows);
     return hipGetLastError();
 }
 

@@ -26,6 +26,7 @@ struct Geometry {
     uint32_t tile_words;     // tile_rows / 32
     uint32_t n_tiles;        // ceil(n_rows / tile_rows)
     uint32_t bitmap;         // 1 = hash-bitmap index format
+    uint32_t sparse_mask;    // 1 = per-tile flags gate the mask words / histogram rows (element-level inputs)
 };
 
 // Per-call encode workspace layout (bytes from the workspace base).
@@ -35,6 +36,8 @@ struct EncodeLayout {
     uint64_t mask_stride;
     uint64_t hist_off;       // per worker: n_tiles*n_parts u32 (tile-major)
     uint64_t hist_stride;
+    uint64_t flag_off;       // per worker: n_tiles u32, 1 = the tile has a non-zero row (its mask words and
+    uint64_t flag_stride;    //             histogram row exist), 0 = empty tile (nothing else was written)
     uint64_t total;
 };
 
