@@ -7,6 +7,7 @@ smoke check and the benchmark's cpu_baseline leg may use it.
 from .zen_ref import (  # noqa: F401
     build,
     lib,
+    use_library,
     hash32,
     hash_many,
     owner_table,

@@ -36,11 +36,23 @@ def build(force=False):
     return _SO
 
 
+def use_library(path):
+    """Point the wrapper at another build of the oracle (the mutation test loads deliberately broken
+    copies to prove that the pins notice); use_library(None) returns to the real one."""
+    global _lib, _SO_OVERRIDE
+    _SO_OVERRIDE = path
+    _lib = None
+
+
+_SO_OVERRIDE = None
+
+
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_SO)
+        if _SO_OVERRIDE is None:
+            build()
+        L = C.CDLL(_SO_OVERRIDE or _SO)
         L.zen_ref_hash.restype = C.c_uint32
         L.zen_ref_hash.argtypes = [C.c_uint32, C.c_uint32]
         L.zen_ref_hash_many.restype = None

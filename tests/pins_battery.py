@@ -1,0 +1,94 @@
+"""Compact battery of oracle pins, runnable on any build of oracle/zen_ref.c:
+
+    python tests/pins_battery.py /path/to/libzen_ref_variant.so      (exit status 0 = every pin holds)
+
+Used by test_oracle_mutations.py in a child process, because a broken oracle may corrupt memory.
+"""
+import os
+import sys
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, HERE)
+sys.path.insert(0, os.path.dirname(HERE))
+
+import brute  # noqa: E402
+
+
+def battery(oracle):
+    """Compact pins; raises AssertionError (or any exception) when the oracle is wrong."""
+    from sklearn.utils import murmurhash3_32
+
+    # hash: published vectors + library
+    assert oracle.hash32(0x87654321, 0) == 0xF55B516B and oracle.hash32(0x87654321, 0x5082EDEE) == 0x2362F9DE
+    assert oracle.hash32(0xFFFFFFFF, 0) == 0x76293B50 and oracle.hash32(0, 0) == 0x2362F9DE
+    idx = np.arange(0, 5000, 7, dtype=np.uint32)
+    assert np.array_equal(oracle.hash_many(idx, 99), murmurhash3_32(idx.view(np.int32), seed=99, positive=True).astype(np.uint32))
+    own = oracle.owner_table(4096, 8, 1)
+    assert np.array_equal(own, (murmurhash3_32(np.arange(4096, dtype=np.int32), seed=1, positive=True) % 8).astype(np.uint16))
+    # encode vs brute force, special values
+    rng = np.random.default_rng(0)
+    R, D, n = 97, 3, 5
+    g = np.zeros((R, D), np.float32)
+    rows = rng.choice(R, 30, replace=False)
+    g[rows, rng.integers(0, D, 30)] = rng.standard_normal(30).astype(np.float32)
+    g[3] = [0.0, -0.0, 0.0]
+    g[4] = [0.0, 0.0, 2.0]
+    owner = oracle.owner_table(R, n, 77)
+    b_off, b_idx, b_val = brute.encode(g, owner, n)
+    enc = oracle.encode(g, R, D, n, 77)
+    assert enc.rc == 0 and enc.offsets.tolist() == b_off and enc.indices.tolist() == b_idx
+    assert np.array_equal(enc.values.view(np.uint32), np.stack(b_val).view(np.uint32))
+    # hash bitmap: the paper's worked example (|G| = 15, 3 servers, non-zeros {5, 7} 1-based are the
+    # second and third members of server 0's set) + brute force + round trip
+    ex_owner = np.array([0 if (r + 1) in (2, 5, 7, 11, 14) else 1 + (r % 2) for r in range(15)], np.uint16)
+    nz = np.zeros(15, np.uint8)
+    nz[[4, 6]] = 1
+    dom_count, word_off = oracle.bitmap_layout(ex_owner, 3)
+    bm = oracle.bitmap_encode(ex_owner, 3, nz, word_off)
+    assert int(bm[int(word_off[0])]) == 0b110 and int(dom_count.sum()) == 15
+    assert oracle.bitmap_decode(ex_owner, 0, bm[int(word_off[0]):int(word_off[1])]).tolist() == [4, 6]
+    # domains whose size is an exact multiple of 32 (and an empty one) need no padding word
+    dc3, wo3 = oracle.bitmap_layout(np.array([0] * 64 + [2] * 32, np.uint16), 3)
+    assert dc3.tolist() == [64, 0, 32] and wo3.tolist() == [0, 2, 2, 3]
+    R2, n2 = 1000, 7
+    owner2 = oracle.owner_table(R2, n2, 3)
+    nz2 = (rng.random(R2) < 0.3).astype(np.uint8)
+    dc2, wo2 = oracle.bitmap_layout(owner2, n2)
+    assert np.array_equal(np.diff(wo2), (dc2 + np.uint64(31)) // np.uint64(32))
+    bm2 = oracle.bitmap_encode(owner2, n2, nz2, wo2)
+    ref2 = brute.bitmap(owner2, n2, np.flatnonzero(nz2))
+    for p in range(n2):
+        words = bm2[int(wo2[p]):int(wo2[p + 1])]
+        assert sum(int(w) << (32 * k) for k, w in enumerate(words)) == ref2[p][0]
+        dec = oracle.bitmap_decode(owner2, p, words)
+        assert dec.tolist() == [r for r in np.flatnonzero(nz2).tolist() if owner2[r] == p]
+    # aggregate vs dense sum (duplicates, cancellation)
+    parts = []
+    for w in range(4):
+        i = rng.integers(0, 60, size=25).astype(np.uint32)
+        parts.append((i, rng.standard_normal((25, 2)).astype(np.float32)))
+    parts.append((np.array([7], np.uint32), -parts[0][1][:1] * 0 + np.float32(1.5)))
+    parts.append((np.array([7, 58], np.uint32), np.array([[-1.5, -1.5], [0.25, 0.5]], np.float32)))
+    acc, touched = brute.aggregate_dense(parts, 60, 2)
+    out = oracle.aggregate(parts, 60, 2)
+    assert out.U == len(touched) and out.indices.tolist() == touched
+    assert np.array_equal(out.sum64, acc[touched]) and np.array_equal(out.values, acc[touched].astype(np.float32))
+    single = oracle.aggregate([(np.array([9, 2], np.uint32), np.array([[1.0, 2.0], [3.0, 4.0]], np.float32))], 60, 2)
+    assert single.indices.tolist() == [2, 9] and single.values.tolist() == [[3.0, 4.0], [1.0, 2.0]]
+    cancel = oracle.aggregate([(np.array([5], np.uint32), np.ones((1, 2), np.float32)),
+                               (np.array([5], np.uint32), -np.ones((1, 2), np.float32))], 60, 2)
+    assert cancel.U == 1 and cancel.indices.tolist() == [5]
+    # imbalance-ratio example of section "Balance dimension"
+    assert abs(oracle.imbalance([1, 4, 1]) - 2.0) < 1e-12
+
+
+
+
+if __name__ == "__main__":
+    import oracle
+
+    oracle.use_library(sys.argv[1])
+    battery(oracle)
+    print("battery ok")

@@ -75,6 +75,12 @@ def test_bitmap_size_closed_forms():
     assert round(16 * tensor_mb / 32) == 428
 
 
+def test_layout_word_boundaries(oracle):
+    # |II_p| an exact multiple of 32 needs no padding word; an empty domain takes no word at all
+    dom_count, word_off = oracle.bitmap_layout(np.array([0] * 64 + [2] * 32 + [3] * 33, np.uint16), 4)
+    assert dom_count.tolist() == [64, 0, 32, 33] and word_off.tolist() == [0, 2, 2, 3, 5]
+
+
 def test_hash_bitmap_total_is_constant_in_n(oracle):
     R = 1 << 16
     for n in (1, 2, 16, 64, 128):

@@ -1,0 +1,76 @@
+"""The pins must notice a broken oracle.
+
+Each case plants one plausible mistake in a copy of oracle/zen_ref.c (on the CPU, never in the GPU
+path), builds it, and runs a compact battery of the same pins the other oracle tests use: published
+hash vectors, the library hash, brute force on tiny inputs, the paper's worked hash-bitmap example,
+the dense-sum aggregate.  Every mutant has to fail the battery; the unmodified source has to pass.
+"""
+import os
+import subprocess
+import sys
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = open(os.path.join(ROOT, "oracle", "zen_ref.c")).read()
+
+MUTANTS = [
+    ("hash: wrong first constant", "k *= 0xcc9e2d51u;", "k *= 0xcc9e2d53u;"),
+    ("hash: rotation 15 -> 16", "k = rotl32(k, 15);", "k = rotl32(k, 16);"),
+    ("hash: key length not mixed in", "h ^= 4u; /* key length in bytes */", ""),
+    ("hash: h*5 -> h*3", "h = h * 5u + 0xe6546b64u;", "h = h * 3u + 0xe6546b64u;"),
+    ("hash: finaliser shift dropped", "h ^= h >> 13;\n    h *= 0xc2b2ae35u;", "h *= 0xc2b2ae35u;"),
+    ("owner: seed ignored", "return zen_ref_hash(idx, seed) % n;", "return zen_ref_hash(idx, 0) % n;"),
+    ("nonzero: sign bit counted (-0 becomes non-zero)", "if ((bits & 0x7fffffffu) != 0) { nz = 1; break; }",
+     "if (bits != 0) { nz = 1; break; }"),
+    ("nonzero: only the first column looked at", "for (uint32_t c = 0; c < row_dim; ++c) {\n            uint32_t bits;",
+     "for (uint32_t c = 0; c < 1; ++c) {\n            uint32_t bits;"),
+    ("partition: offsets shifted by one", "offsets[p + 1] = (uint32_t)pos;", "offsets[p + 1] = (uint32_t)pos + (p + 1 < n);"),
+    ("partition: wrong partition order", "for (uint32_t p = 0; p < n; ++p) {\n        for (uint64_t k = 0; k < nnz; ++k)\n            if (owner_of_I[k] == p)",
+     "for (uint32_t p = 0; p < n; ++p) {\n        for (uint64_t k = 0; k < nnz; ++k)\n            if (owner_of_I[k] == n - 1 - p)"),
+    ("gather: row k instead of row indices[k]", "grad + (uint64_t)indices[k] * row_dim,", "grad + (uint64_t)k * row_dim,"),
+    ("bitmap layout: no padding to a word", "word_off[p + 1] = word_off[p] + (dom_count[p] + 31) / 32;",
+     "word_off[p + 1] = word_off[p] + dom_count[p] / 32 + 1;"),
+    ("bitmap encode: MSB-first", "bitmap[word_off[p] + (j >> 5)] |= 1u << (j & 31);",
+     "bitmap[word_off[p] + (j >> 5)] |= 0x80000000u >> (j & 31);"),
+    ("bitmap encode: position counted over all rows", "if (nz[r]) bitmap[word_off[p] + (j >> 5)] |= 1u << (j & 31);\n            ++j;",
+     "if (nz[r]) bitmap[word_off[p] + (r >> 5)] |= 1u << (r & 31);\n            ++j;"),
+    ("bitmap decode: wrong bit", "if ((bitmap_p[j >> 5] >> (j & 31)) & 1u) indices[count++] = (uint32_t)r;",
+     "if ((bitmap_p[j >> 5] >> ((j + 1) & 31)) & 1u) indices[count++] = (uint32_t)r;"),
+    ("aggregate: last occurrence wins", "sum[o + c] += (double)row[c];", "sum[o + c] = (double)row[c];"),
+    ("aggregate: sign lost", "sum[o + c] += (double)row[c];", "sum[o + c] += fabs((double)row[c]);"),
+    ("aggregate: transposed value index", "const float *row = val[w] + k * (uint64_t)row_dim;",
+     "const float *row = val[w] + (counts[w] - 1 - k) * (uint64_t)row_dim;"),
+    ("aggregate: zero sums dropped from the count", "for (uint64_t r = 0; r < n_rows; ++r) if (occ[r]) ++U;",
+     "for (uint64_t r = 0; r < n_rows; ++r) if (occ[r] > 1) ++U;"),
+    ("imbalance: factor n missing", "return (double)n * (double)mx / (double)total;", "return (double)mx / (double)total;"),
+]
+
+
+def _build(source, tmpdir, name):
+    c = os.path.join(tmpdir, name + ".c")
+    so = os.path.join(tmpdir, name + ".so")
+    open(c, "w").write(source)
+    subprocess.check_call(["gcc", "-O1", "-std=c99", "-shared", "-fPIC", "-o", so, c, "-lm"])
+    return so
+
+
+def run_battery(so_path):
+    """Runs tests/pins_battery.py on a build of the oracle in a child process (a broken oracle may
+    corrupt memory); returns True iff every pin held."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "tests", "pins_battery.py"), so_path],
+                       capture_output=True, text=True, timeout=120)
+    return r.returncode == 0 and "battery ok" in r.stdout
+
+
+def test_unmodified_oracle_passes_the_battery():
+    with tempfile.TemporaryDirectory() as d:
+        assert run_battery(_build(SRC, d, "clean"))
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_every_mutant_fails_a_pin(name, old, new):
+    assert SRC.count(old) >= 1, "mutation site not found: " + name
+    with tempfile.TemporaryDirectory() as d:
+        assert not run_battery(_build(SRC.replace(old, new, 1), d, "mutant")), "mutant survived every pin: " + name
