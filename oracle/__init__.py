@@ -19,5 +19,8 @@ from .zen_ref import (  # noqa: F401
     bitmap_encode,
     bitmap_decode,
     aggregate,
+    member_mask,
+    densify,
+    pull_apply,
     imbalance,
 )

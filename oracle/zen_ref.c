@@ -27,7 +27,10 @@
  *     the partition's domain is non-zero; bits are packed LSB-first into
  *     32-bit words and every partition starts on a word boundary;
  *   - aggregation sums every occurrence of an index in fp64, in input order,
- *     and keeps an index even when its sum is exactly zero.
+ *     and keeps an index even when its sum is exactly zero;
+ *   - the hash bitmap a server builds for Pull marks membership in its
+ *     aggregated index set (not "value != 0"), so values and set bits stay
+ *     paired one to one.
  *
  * Parity status: every function below is pinned by tests/test_oracle_*.py
  * (published MurmurHash3 vectors and an independent library implementation,
@@ -289,6 +292,72 @@ int64_t zen_ref_aggregate(uint32_t n_in, const uint32_t *const *idx, const float
     }
     free(occ); free(pos); free(sum); free(abs_);
     return U;
+}
+
+/*
+ * Pull, server side (section "Hash Bitmap": hash_bitmap_encode is invoked at
+ * each server on what it aggregated).  The server's tensor is the aggregated
+ * sparse partition; reading taken: a row is "present" iff it belongs to the
+ * aggregated index set, so a row whose sum cancelled to zero keeps its bit and
+ * the k-th value stays the value of the k-th set bit.  member[r] = 1 iff r is in
+ * idx[0..count); the bitmap itself is then zen_ref_bitmap_encode(member).
+ */
+int zen_ref_member_mask(const uint32_t *idx, uint64_t count, uint64_t n_rows, uint8_t *member)
+{
+    memset(member, 0, (size_t)n_rows);
+    for (uint64_t k = 0; k < count; ++k) {
+        if (idx[k] >= n_rows) return ZEN_REF_ERR_INVALID;
+        member[idx[k]] = 1;
+    }
+    return ZEN_REF_OK;
+}
+
+/*
+ * A sparse tensor given as parts (indices, rows) written out densely: G[idx] =
+ * row, zero elsewhere (section "Elemental Dimensions for Synchronization": the
+ * outcome of synchronization is the aggregated tensor, identical on all GPUs).
+ * An index out of range, or one that occurs twice, is an error: parts of one
+ * synchronized tensor are disjoint (Algorithm 1 sends an index to one server).
+ */
+int zen_ref_densify(uint32_t n_in, const uint32_t *const *idx, const float *const *val,
+                    const uint64_t *counts, uint64_t n_rows, uint32_t row_dim, float *dense)
+{
+    uint8_t *seen = (uint8_t *)calloc((size_t)n_rows + 1, 1);
+    if (!seen) return ZEN_REF_ERR_INVALID;
+    memset(dense, 0, (size_t)n_rows * row_dim * 4);
+    for (uint32_t w = 0; w < n_in; ++w)
+        for (uint64_t k = 0; k < counts[w]; ++k) {
+            uint32_t r = idx[w][k];
+            if (r >= n_rows || seen[r]) { free(seen); return ZEN_REF_ERR_INVALID; }
+            seen[r] = 1;
+            memcpy(dense + (uint64_t)r * row_dim, val[w] + k * (uint64_t)row_dim, (size_t)row_dim * 4);
+        }
+    free(seen);
+    return ZEN_REF_OK;
+}
+
+/*
+ * Pull, worker side (section "Hash Bitmap": after a worker has received the
+ * hash bitmaps of all servers it calls hash_bitmap_decode with the matching
+ * II_p): partition p's bitmap starts at word_off[p]; its k-th set bit names row
+ * II_p[bit position], whose values are val[p][k].  The decoded partitions are
+ * written out densely.  The number of set bits must equal counts[p].
+ */
+int zen_ref_pull_apply(const uint16_t *owner, uint64_t n_rows, uint32_t n, uint32_t row_dim,
+                       const uint64_t *word_off, const uint32_t *bitmap, const float *const *val,
+                       const uint64_t *counts, float *dense)
+{
+    uint32_t *idx = (uint32_t *)malloc(((size_t)n_rows + 1) * 4);
+    if (!idx) return ZEN_REF_ERR_INVALID;
+    memset(dense, 0, (size_t)n_rows * row_dim * 4);
+    for (uint32_t p = 0; p < n; ++p) {
+        int64_t k = zen_ref_bitmap_decode(owner, n_rows, p, bitmap + word_off[p], idx);
+        if ((uint64_t)k != counts[p]) { free(idx); return ZEN_REF_ERR_INVALID; }
+        for (int64_t i = 0; i < k; ++i)
+            memcpy(dense + (uint64_t)idx[i] * row_dim, val[p] + (uint64_t)i * row_dim, (size_t)row_dim * 4);
+    }
+    free(idx);
+    return ZEN_REF_OK;
 }
 
 /*

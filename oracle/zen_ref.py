@@ -79,6 +79,14 @@ def lib():
         L.zen_ref_aggregate.restype = C.c_int64
         L.zen_ref_aggregate.argtypes = [C.c_uint32, C.POINTER(_u32p), C.POINTER(_f32p), _u64p, C.c_uint64,
                                         C.c_uint32, _u32p, _f32p, _f64p, _f64p, _u32p, C.c_uint64]
+        L.zen_ref_member_mask.restype = C.c_int
+        L.zen_ref_member_mask.argtypes = [_u32p, C.c_uint64, C.c_uint64, _u8p]
+        L.zen_ref_densify.restype = C.c_int
+        L.zen_ref_densify.argtypes = [C.c_uint32, C.POINTER(_u32p), C.POINTER(_f32p), _u64p, C.c_uint64,
+                                      C.c_uint32, _f32p]
+        L.zen_ref_pull_apply.restype = C.c_int
+        L.zen_ref_pull_apply.argtypes = [_u16p, C.c_uint64, C.c_uint32, C.c_uint32, _u64p, _u32p,
+                                         C.POINTER(_f32p), _u64p, _f32p]
         L.zen_ref_imbalance.restype = C.c_double
         L.zen_ref_imbalance.argtypes = [_u64p, C.c_uint32]
         _lib = L
@@ -224,6 +232,50 @@ def aggregate(parts, n_rows, row_dim, cap_rows=None, want_f64=True):
     return SimpleNamespace(U=U, indices=out_idx[:U], values=out_val[:U],
                            sum64=out_sum[:U] if want_f64 else None,
                            abs64=out_abs[:U] if want_f64 else None, ncontrib=out_nc[:U])
+
+
+def member_mask(indices, n_rows):
+    indices = _c(indices, np.uint32).reshape(-1)
+    member = np.empty(int(n_rows), np.uint8)
+    rc = lib().zen_ref_member_mask(_p(indices, _u32p), indices.size, int(n_rows), _p(member, _u8p))
+    if rc != 0:
+        raise ValueError("zen_ref_member_mask: rc=%d" % rc)
+    return member
+
+
+def densify(parts, n_rows, row_dim):
+    """parts: list of (indices u32[count], values f32[count, D]), pairwise disjoint -> dense f32[R, D]."""
+    n_in = len(parts)
+    idx = [_c(p[0], np.uint32).reshape(-1) for p in parts]
+    val = [_c(p[1], np.float32).reshape(-1) for p in parts]
+    for i, v in zip(idx, val):
+        assert v.size == i.size * int(row_dim)
+    counts = np.array([i.size for i in idx], np.uint64)
+    idx_arr = (_u32p * max(n_in, 1))(*[_p(i, _u32p) for i in idx])
+    val_arr = (_f32p * max(n_in, 1))(*[_p(v, _f32p) for v in val])
+    dense = np.empty((int(n_rows), int(row_dim)), np.float32)
+    rc = lib().zen_ref_densify(n_in, idx_arr, val_arr, _p(counts, _u64p), int(n_rows), int(row_dim),
+                               _p(dense, _f32p))
+    if rc != 0:
+        raise ValueError("zen_ref_densify: rc=%d" % rc)
+    return dense
+
+
+def pull_apply(owner, n, row_dim, word_off, bitmap, values):
+    """values: list over the n partitions of f32[count_p, D] in bit order -> dense f32[R, D]."""
+    owner = _c(owner, np.uint16)
+    word_off = _c(word_off, np.uint64)
+    bitmap = _c(bitmap, np.uint32)
+    assert len(values) == int(n) and word_off.size == int(n) + 1 and bitmap.size >= int(word_off[-1])
+    val = [_c(v, np.float32).reshape(-1) for v in values]
+    counts = np.array([v.size // int(row_dim) for v in val], np.uint64)
+    val_arr = (_f32p * int(n))(*[_p(v, _f32p) for v in val])
+    dense = np.empty((owner.size, int(row_dim)), np.float32)
+    rc = lib().zen_ref_pull_apply(_p(owner, _u16p), owner.size, int(n), int(row_dim), _p(word_off, _u64p),
+                                  _p(bitmap, _u32p), val_arr, _p(counts, _u64p), _p(dense, _f32p))
+    if rc != 0:
+        raise ValueError("zen_ref_pull_apply: rc=%d" % rc)
+    return dense
 
 
 def imbalance(sizes):

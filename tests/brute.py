@@ -59,3 +59,12 @@ def aggregate_dense(parts, n_rows, row_dim):
             acc[int(r)] += np.asarray(val[k], np.float64)
             touched.add(int(r))
     return acc, sorted(touched)
+
+
+def densify(parts, n_rows, row_dim):
+    """Dense fp32 tensor holding every part's rows at their indices, zero elsewhere."""
+    out = np.zeros((n_rows, row_dim), np.float32)
+    for idx, val in parts:
+        for k, r in enumerate(idx):
+            out[int(r)] = np.asarray(val[k], np.float32)
+    return out

@@ -80,6 +80,26 @@ def battery(oracle):
     cancel = oracle.aggregate([(np.array([5], np.uint32), np.ones((1, 2), np.float32)),
                                (np.array([5], np.uint32), -np.ones((1, 2), np.float32))], 60, 2)
     assert cancel.U == 1 and cancel.indices.tolist() == [5]
+    # Pull side: worked example continued (values of the second and third member land at rows 5 and 7,
+    # 1-based), brute-force placement, partition p reads its own words
+    mem = oracle.member_mask([4, 6], 15)
+    assert mem.tolist() == [0, 0, 0, 0, 1, 0, 1] + [0] * 8
+    d15 = oracle.pull_apply(ex_owner, 3, 1, word_off, oracle.bitmap_encode(ex_owner, 3, mem, word_off),
+                            [np.array([[10.0], [20.0]], np.float32), np.zeros((0, 1), np.float32),
+                             np.zeros((0, 1), np.float32)])
+    assert d15[:, 0].tolist() == [0, 0, 0, 0, 10.0, 0, 20.0] + [0] * 8
+    present = np.flatnonzero(nz2).astype(np.uint32)
+    pv = rng.standard_normal((present.size, 2)).astype(np.float32)
+    pparts = [(present[owner2[present] == p], pv[owner2[present] == p]) for p in range(n2)]
+    want = brute.densify(pparts, R2, 2)
+    assert np.array_equal(oracle.densify(pparts, R2, 2), want)
+    assert np.array_equal(oracle.pull_apply(owner2, n2, 2, wo2, bm2, [v for _, v in pparts]), want)
+    try:                                                   # two set bits, three value rows: refused
+        oracle.pull_apply(ex_owner, 3, 1, word_off, oracle.bitmap_encode(ex_owner, 3, mem, word_off),
+                          [np.ones((3, 1), np.float32), np.zeros((0, 1), np.float32), np.zeros((0, 1), np.float32)])
+        raise AssertionError("count mismatch accepted")
+    except ValueError:
+        pass
     # imbalance-ratio example of section "Balance dimension"
     assert abs(oracle.imbalance([1, 4, 1]) - 2.0) < 1e-12
 

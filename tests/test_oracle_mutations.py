@@ -44,6 +44,16 @@ MUTANTS = [
      "const float *row = val[w] + (counts[w] - 1 - k) * (uint64_t)row_dim;"),
     ("aggregate: zero sums dropped from the count", "for (uint64_t r = 0; r < n_rows; ++r) if (occ[r]) ++U;",
      "for (uint64_t r = 0; r < n_rows; ++r) if (occ[r] > 1) ++U;"),
+    ("member mask: index shifted by one", "member[idx[k]] = 1;", "member[idx[k] ? idx[k] - 1 : 0] = 1;"),
+    ("densify: row k placed at row k", "memcpy(dense + (uint64_t)r * row_dim, val[w] + k * (uint64_t)row_dim,",
+     "memcpy(dense + (uint64_t)k * row_dim, val[w] + k * (uint64_t)row_dim,"),
+    ("densify: value row taken from the index", "memcpy(dense + (uint64_t)r * row_dim, val[w] + k * (uint64_t)row_dim,",
+     "memcpy(dense + (uint64_t)r * row_dim, val[w] + (counts[w] - 1 - k) * (uint64_t)row_dim,"),
+    ("pull apply: every partition reads partition 0's words", "zen_ref_bitmap_decode(owner, n_rows, p, bitmap + word_off[p], idx);",
+     "zen_ref_bitmap_decode(owner, n_rows, p, bitmap + word_off[0], idx);"),
+    ("pull apply: value of the next set bit", "val[p] + (uint64_t)i * row_dim, (size_t)row_dim * 4);",
+     "val[p] + (uint64_t)(i + 1 < k ? i + 1 : i) * row_dim, (size_t)row_dim * 4);"),
+    ("pull apply: count not checked", "if ((uint64_t)k != counts[p]) { free(idx); return ZEN_REF_ERR_INVALID; }", ""),
     ("imbalance: factor n missing", "return (double)n * (double)mx / (double)total;", "return (double)mx / (double)total;"),
 ]
 
