@@ -10,6 +10,8 @@
  *                  indices are aggregated; Definition "imbalance ratio": index set II_i at server i]
  *   hash bitmap    optional index encoding of a partition over its hash domain
  *                  [section "Hash Bitmap", Algorithm 2 hash_bitmap_encode / hash_bitmap_decode]
+ *   zen_pull_*     the way back: a server's aggregated partition as a hash bitmap, and the worker's
+ *                  decode of all servers' bitmaps into the synchronized dense tensor
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name starts with host_ or the comment says "host".
@@ -86,7 +88,8 @@ typedef struct {
 
 /* Status block fetched from a workspace. */
 typedef struct {
-    uint32_t flags;        /* bit 0: output capacity overflow, bit 1: table/bound overflow */
+    uint32_t flags;        /* bit 0: output capacity overflow, bit 1: table/bound overflow,
+                              bit 2: inconsistent input (bitmap vs row count, foreign or unsorted index) */
     uint32_t reserved;
     uint64_t needed_rows;  /* largest number of rows any overflowing output / table needed */
 } zen_status_info;
@@ -156,6 +159,57 @@ zen_status zen_aggregate(zen_ctx *ctx, const zen_part *host_parts, uint32_t n_in
 zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint32_t n_workers,
                                const zen_aggregated *host_outs, uint64_t max_in_rows, void *workspace,
                                uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * ---- Pull: what a server sends back and what a worker does with it (section "Hash Bitmap") -----
+ *
+ * All Pull calls need a ZEN_INDEX_BITMAP context for their bitmap forms (the sorted domains II_p
+ * live in the context) and a workspace of zen_pull_workspace_bytes; they keep a status block at the
+ * start of the workspace like the other calls (flag bit 2 = inconsistent input, reported by
+ * zen_status_fetch as ZEN_ERR_INVALID).
+ */
+zen_status zen_pull_workspace_bytes(const zen_ctx *ctx, uint64_t *host_bytes);
+
+/*
+ * hash_bitmap_encode at server part_id (Algorithm 2; "invoked at each server" on its aggregated
+ * partition).  indices: the server's aggregated row ids, ASCENDING and distinct, all owned by
+ * part_id (exactly what zen_aggregate writes); count: device scalar, clamped to cap_rows.
+ * bitmap_words: the partition's own ceil(|II_p|/32) words; every one of them is written (bit j = 1
+ * iff the j-th smallest row of II_p is in `indices`; padding 0).  A row counts as present when it is
+ * in the index list, whatever its value, so the k-th value row keeps belonging to the k-th set bit
+ * and the values are sent as they are.  Input that is not such a list raises flag bit 2; nothing is
+ * read or written out of bounds.
+ */
+zen_status zen_pull_encode(zen_ctx *ctx, const uint32_t *indices, const uint32_t *count, uint64_t cap_rows,
+                           uint32_t part_id, uint32_t *bitmap_words, void *workspace, uint64_t workspace_bytes,
+                           void *hip_stream);
+
+/* The same for all n_parts servers: host_aggs[j] = server j's zen_aggregate output, bitmap = the
+ * whole layout of zen_bitmap_layout (partition j at word offset j). */
+zen_status zen_pull_encode_batch(zen_ctx *ctx, const zen_aggregated *host_aggs, uint32_t *bitmap, void *workspace,
+                                 uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * hash_bitmap_decode (Algorithm 2): out_indices = II_p[positions of the 1 bits], ascending;
+ * *out_count = number of set bits.  More set bits than out_cap_rows: the first out_cap_rows indices
+ * are written and the capacity flag is raised with needed_rows = the number of set bits.  Padding
+ * bits of the last word are ignored.
+ */
+zen_status zen_pull_decode(zen_ctx *ctx, const uint32_t *bitmap_words, uint32_t part_id, uint32_t *out_indices,
+                           uint64_t out_cap_rows, uint32_t *out_count, void *workspace, uint64_t workspace_bytes,
+                           void *hip_stream);
+
+/*
+ * Worker side of Pull: the n_parts aggregated partitions (host_parts[p] = what server p sent: a hash
+ * bitmap or an index list, values, count) written out as the synchronized dense tensor
+ * dense[n_rows][row_dim] (16-byte aligned): dense[row] = the row's values where some partition holds
+ * the row, 0 elsewhere [section "Elemental Dimensions for Synchronization": every GPU ends with the
+ * same aggregated result].  Partitions are disjoint by construction; if an index occurs twice one of
+ * its rows wins.  A bitmap whose set bits do not number *count, or an index >= n_rows, raises flag
+ * bit 2; rows beyond *count are never read.  Index-list parts work with a COO context too.
+ */
+zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense, void *workspace,
+                          uint64_t workspace_bytes, void *hip_stream);
 
 /* Synchronous: waits for the stream, reads the status block of a workspace last used by an encode
  * or aggregate call, returns ZEN_OK / ZEN_ERR_CAPACITY and fills *host_info (may be NULL). */

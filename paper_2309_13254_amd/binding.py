@@ -17,6 +17,7 @@ __all__ = [
     "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
     "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
     "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
+    "zen_pull_workspace_bytes", "zen_pull_encode", "zen_pull_encode_batch", "zen_pull_decode", "zen_pull_apply",
     "alloc_encoded", "alloc_aggregated", "alloc_workspace",
 ]
 
@@ -79,6 +80,11 @@ def load_library():
         "zen_status_fetch": [vp, vp, vp, C.POINTER(_StatusInfo)],
         "zen_hash_many": [vp, u64, u32, vp, vp],
         "zen_calibration_copy": [vp, vp, u64, vp],
+        "zen_pull_workspace_bytes": [vp, C.POINTER(u64)],
+        "zen_pull_encode": [vp, vp, vp, u64, u32, vp, vp, u64, vp],
+        "zen_pull_encode_batch": [vp, C.POINTER(_Aggregated), vp, vp, u64, vp],
+        "zen_pull_decode": [vp, vp, u32, vp, u64, vp, vp, u64, vp],
+        "zen_pull_apply": [vp, C.POINTER(_Part), vp, vp, u64, vp],
         "zen_profile_enable": [vp, u32, u32],
         "zen_profile_collect": [vp, u32, C.POINTER(C.c_double), C.POINTER(u32), C.POINTER(u32)],
     }
@@ -255,6 +261,40 @@ def zen_aggregate_batch(ctx, encs, outs, max_in_rows, workspace, stream=None):
     os_ = (_Aggregated * len(outs))(*[o.struct() for o in outs])
     return _check(load_library().zen_aggregate_batch(ctx.handle, es, n, os_, int(max_in_rows), workspace.data_ptr(),
                                                      workspace.numel(), _stream(stream)), "zen_aggregate_batch")
+
+
+def zen_pull_workspace_bytes(ctx):
+    b = C.c_uint64()
+    _check(load_library().zen_pull_workspace_bytes(ctx.handle, C.byref(b)), "zen_pull_workspace_bytes")
+    return int(b.value)
+
+
+def zen_pull_encode(ctx, indices, count, cap_rows, part_id, bitmap_words, workspace, stream=None):
+    return _check(load_library().zen_pull_encode(ctx.handle, indices.data_ptr(), count.data_ptr(), int(cap_rows),
+                                                 int(part_id), bitmap_words.data_ptr(), workspace.data_ptr(),
+                                                 workspace.numel(), _stream(stream)), "zen_pull_encode")
+
+
+def zen_pull_encode_batch(ctx, aggs, bitmap, workspace, stream=None):
+    assert len(aggs) == ctx.n_parts
+    as_ = (_Aggregated * len(aggs))(*[a.struct() for a in aggs])
+    return _check(load_library().zen_pull_encode_batch(ctx.handle, as_, bitmap.data_ptr(), workspace.data_ptr(),
+                                                       workspace.numel(), _stream(stream)), "zen_pull_encode_batch")
+
+
+def zen_pull_decode(ctx, bitmap_words, part_id, out_indices, out_count, workspace, stream=None):
+    return _check(load_library().zen_pull_decode(ctx.handle, bitmap_words.data_ptr(), int(part_id),
+                                                 out_indices.data_ptr(), out_indices.numel(), out_count.data_ptr(),
+                                                 workspace.data_ptr(), workspace.numel(), _stream(stream)),
+                  "zen_pull_decode")
+
+
+def zen_pull_apply(ctx, parts, dense, workspace, stream=None):
+    """parts: n_parts entries (indices|None, bitmap|None, values, count), entry p = partition p."""
+    assert len(parts) == ctx.n_parts
+    ps = (_Part * len(parts))(*[_Part(_ptr(p[0]), _ptr(p[1]), _ptr(p[2]), _ptr(p[3])) for p in parts])
+    return _check(load_library().zen_pull_apply(ctx.handle, ps, dense.data_ptr(), workspace.data_ptr(),
+                                                workspace.numel(), _stream(stream)), "zen_pull_apply")
 
 
 def zen_status_fetch(ctx, workspace, stream=None):

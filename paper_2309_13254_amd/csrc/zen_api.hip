@@ -401,7 +401,9 @@ static const char *const kKernelNames[K_COUNT] = {
     "detect_kernel", "partition_scan_kernel", "scatter_kernel", "agg_clear_kernel", "agg_insert_kernel",
     "agg_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
     "agg_finalize_kernel", "agg_zero_kernel", "agg_accum_kernel", "nonzero_list_kernels", "bitmap_decode_kernel",
-    "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel", "encode_small_kernel", "gather_rows_kernel"};
+    "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel", "encode_small_kernel", "gather_rows_kernel",
+    "pull_encode_kernel", "pull_zero_kernel", "pull_count_kernel", "pull_scan_kernel", "pull_place_kernel",
+    "pull_place_coo_kernel"};
 
 static void prof_release(zen_ctx *ctx)
 {
