@@ -81,6 +81,45 @@ def cpu_baseline(wl, sparse, budget_s=20.0):
     }
 
 
+def pull_leg(zen, torch, wl, ctx, aggs, U, steps):
+    """Pull on its own clock: all servers build the hash bitmap of what they aggregated, then one worker
+    decodes the n bitmaps and places the values in its dense tensor (every worker does the same)."""
+    n, D = wl.n_parts, wl.row_dim
+    pctx = ctx if wl.bitmap else zen.ZenContext(wl.n_rows, D, n, wl.hash_seed, zen.ZEN_INDEX_BITMAP)
+    total, woff, _ = zen.zen_bitmap_layout(pctx)
+    ws = zen.alloc_workspace(zen.zen_pull_workspace_bytes(pctx))
+    bitmap = torch.empty(max(total, 1), dtype=torch.int32, device="cuda")
+    n_buf = 1 if wl.dense_bytes > (8 << 30) else max(2, min(4, (2 << 30) // max(wl.dense_bytes, 1)))
+    dense = [torch.empty((wl.n_rows, D), dtype=torch.float32, device="cuda") for _ in range(n_buf)]
+    parts = [(None, bitmap[woff[p]:], aggs[p].values, aggs[p].count) for p in range(n)]
+
+    def run(k):
+        zen.zen_pull_encode_batch(pctx, aggs, bitmap, ws)
+        zen.zen_pull_apply(pctx, parts, dense[k % n_buf], ws)
+
+    for k in range(3):
+        run(k)
+    torch.cuda.synchronize()
+    assert zen.zen_status_fetch(pctx, ws)[0] == 0
+    t0 = time.perf_counter()
+    for k in range(steps):
+        run(k)
+    torch.cuda.synchronize()
+    t = (time.perf_counter() - t0) / steps
+    zen.zen_profile_enable(pctx, 2, 64)
+    for k in range(5):
+        run(k)
+    torch.cuda.synchronize()
+    kms = {k: round(v[0] / 5, 4) for k, v in zen.zen_profile_collect(pctx).items()}
+    zen.zen_profile_enable(pctx, 0, 0)
+    uu = sum(U)
+    b_alg = 4 * uu + 2 * (wl.n_rows // 8) + 4 * D * uu + wl.dense_bytes      # indices in, bitmap out + in, values in, dense out
+    return {"ms_per_step": round(t * 1e3, 4), "dense_GBps": round(wl.dense_bytes / t / 1e9, 1),
+            "algorithmic_bytes": int(b_alg), "hbm_frac": round(b_alg / t / (HBM_PEAK_GBS * 1e9), 4),
+            "kernel_ms_per_step": kms,
+            "what": "zen_pull_encode_batch over %d servers + zen_pull_apply of one worker" % n}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +128,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-times", action="store_true", help="extra untimed pass timing every kernel")
+    ap.add_argument("--pull", action="store_true",
+                    help="extra leg after the timed region: the servers' hash bitmaps (zen_pull_encode_batch) and one "
+                         "worker's decode + dense placement (zen_pull_apply), timed on their own")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain 1 GiB copy kernel three times (reference for hardware "
                          "byte counters under rocprofv3 --pmc)")
@@ -165,6 +207,10 @@ def main():
         kernel_ms = {k: round(v[0] / 5, 4) for k, v in zen.zen_profile_collect(ctx).items()}
         zen.zen_profile_enable(ctx, 0, 0)
 
+    pull = None
+    if args.pull:
+        pull = pull_leg(zen, torch, wl, ctx, aggs, U, args.steps)
+
     if args.calibrate_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -204,6 +250,8 @@ def main():
     }
     if kernel_ms is not None:
         out["kernel_ms_per_step"] = kernel_ms
+    if pull is not None:
+        out["pull"] = pull
     if not args.no_cpu_baseline:
         del grads
         torch.cuda.empty_cache()

@@ -129,7 +129,8 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
         zen_status st = ok ? ZEN_OK : ZEN_ERR_NOMEM;
         if (ok) {
             if (build_domain_tables(ctx, tmp_mask, tmp_status, nullptr) != hipSuccess ||
-                hipMemcpy(h_off, ctx->d_dom_offsets, (n + 1) * 4, hipMemcpyDeviceToHost) != hipSuccess)
+                hipMemcpy(h_off, ctx->d_dom_offsets, (n + 1) * 4, hipMemcpyDeviceToHost) != hipSuccess ||
+                build_pull_tables(ctx, nullptr) != hipSuccess)
                 st = ZEN_ERR_DEVICE;
         }
         if (st == ZEN_OK) {
@@ -167,6 +168,7 @@ zen_status zen_ctx_destroy(zen_ctx *ctx)
     if (ctx->d_dom_offsets) (void)hipFree(ctx->d_dom_offsets);
     if (ctx->d_dom_tile_base) (void)hipFree(ctx->d_dom_tile_base);
     if (ctx->d_bm_word_off) (void)hipFree(ctx->d_bm_word_off);
+    if (ctx->d_pull_base) (void)hipFree(ctx->d_pull_base);
     free(ctx->h_bm_word_off);
     free(ctx->h_dom_sizes);
     delete ctx;

@@ -120,6 +120,7 @@ struct zen_ctx {
     uint64_t bm_total_words;
     uint64_t max_dom_words;    // largest per-partition bitmap, in words
     uint32_t small_encode;     // 1: few-row encodes take the one-block-per-worker partition path
+    uint32_t *d_pull_base;     // element-level BITMAP contexts: [ceil(n_rows/8192)+1][n_parts] rows of II_p below each tile
 };
 
 namespace zen {
@@ -159,6 +160,7 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs
 hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_rows, uint32_t *count,
                                char *ws, const EncodeLayout &L, hipStream_t s);
 hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info *tmp_status, hipStream_t s);
+hipError_t build_pull_tables(zen_ctx *ctx, hipStream_t s);   // zen_pull.hip
 hipError_t launch_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s);
 hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s);

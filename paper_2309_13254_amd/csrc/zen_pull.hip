@@ -20,6 +20,7 @@ namespace zen {
 static constexpr int PULL_THREADS = 256;
 static constexpr uint32_t PULL_CHUNK_WORDS = 256;                     // bitmap words per block
 static constexpr uint32_t PULL_CHUNK_BITS = PULL_CHUNK_WORDS * 32;    // domain rows per block
+static constexpr uint32_t PULL_TILE_ROWS = 8192;                      // element-level placement: rows per block
 
 // One launch group: partitions first_part .. first_part + n - 1, entry i = partition first_part + i.
 struct PullSrc {
@@ -214,46 +215,20 @@ pull_scan_kernel(PullSrc a, uint32_t *cnt, uint32_t n_chunks, uint32_t *out_coun
     }
 }
 
-// Copies `total` rows src[(kbase + i)] -> dense[s_rows[i]] with groups of `lanes` threads per row.
-__device__ __forceinline__ void place_rows(const float *__restrict__ vals, float *__restrict__ dense, uint32_t D,
-                                           uint32_t lanes, const uint32_t *s_rows, uint32_t kbase, uint32_t total)
-{
-    const uint32_t grp = threadIdx.x / lanes, l = threadIdx.x % lanes, n_grp = PULL_THREADS / lanes;
-    if ((D & 3u) == 0) {
-        const uint32_t V = D >> 2;
-        for (uint32_t i = grp; i < total; i += n_grp) {
-            const u32x4 *src = (const u32x4 *)(vals + (uint64_t)(kbase + i) * D);
-            u32x4 *dst = (u32x4 *)(dense + (uint64_t)s_rows[i] * D);
-            for (uint32_t v = l; v < V; v += lanes) dst[v] = src[v];
-        }
-    } else {
-        for (uint32_t i = grp; i < total; i += n_grp) {
-            const float *src = vals + (uint64_t)(kbase + i) * D;
-            float *dst = dense + (uint64_t)s_rows[i] * D;
-            for (uint32_t v = l; v < D; v += lanes) dst[v] = src[v];
-        }
-    }
-}
-
-// Decode + place.  1-D grid; consecutive blocks of one XCD (block id mod 8) take the SAME chunk of
-// consecutive partitions: the domains are uniform samples of the row range, so those blocks write
-// into the same stretch of the dense tensor and their 4-byte stores meet in that XCD's L2.
-//   INDICES: write the decoded row ids (hash_bitmap_decode proper) instead of placing values.
-template <bool INDICES>
+// hash_bitmap_decode for the bitmap parts of a launch group: out_idx[server][k] = II_p[position of the
+// k-th set bit].  1-D grid, block = (chunk, server).
 __global__ void __launch_bounds__(PULL_THREADS)
-pull_place_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *cnt,
-                  uint32_t n_chunks, uint32_t D, uint32_t lanes, float *dense, uint32_t *out_idx, uint64_t out_cap)
+pull_decode_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *cnt,
+                   uint32_t n_chunks, Arr64<uint32_t *> out_idx, Arr64<uint64_t> out_cap)
 {
     __shared__ uint32_t s_word[PULL_CHUNK_WORDS], s_pre[PULL_CHUNK_WORDS], s_tmp[32];
-    extern __shared__ uint32_t s_rows[];   // [PULL_CHUNK_BITS] unless rows are single elements
-    const uint32_t x = blockIdx.x & 7u, t8 = blockIdx.x >> 3;
-    const uint32_t server = t8 % a.n, chunk = (t8 / a.n) * 8 + x, p = a.first_part + server;
+    __shared__ uint32_t s_rows[PULL_CHUNK_BITS];
+    const uint32_t server = blockIdx.x % a.n, chunk = blockIdx.x / a.n, p = a.first_part + server;
     const uint32_t *__restrict__ bm = a.indices[server] ? nullptr : a.bitmap[server];
     if (!bm) return;
     const uint32_t d0 = dom_offsets[p], n_dom = dom_offsets[p + 1] - d0, n_words = (n_dom + 31) >> 5;
     if (chunk * PULL_CHUNK_WORDS >= n_words) return;
-    const uint32_t k = chunk * PULL_CHUNK_WORDS + threadIdx.x;
-    const uint32_t w = domain_word(bm, k, n_dom);
+    const uint32_t w = domain_word(bm, chunk * PULL_CHUNK_WORDS + threadIdx.x, n_dom);
     s_word[threadIdx.x] = w;
     uint32_t total;
     const uint32_t pre = block_exclusive_scan(__popc(w), s_tmp, &total);
@@ -261,44 +236,33 @@ pull_place_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_offsets
     __syncthreads();
     if (total == 0) return;
     const uint32_t kbase = cnt[(uint64_t)server * (n_chunks + 1) + chunk];
-    const uint32_t count = INDICES ? 0xFFFFFFFFu : *a.count[server];
     const uint32_t *__restrict__ dom = domain + d0;
-    const float *__restrict__ vals = a.values[server];
     const uint32_t j0 = chunk * PULL_CHUNK_BITS, b = threadIdx.x & 31u;
-    const bool direct = !INDICES && D == 1;
 #pragma unroll 4
-    for (uint32_t t = 0; t < PULL_CHUNK_BITS / PULL_THREADS; ++t) {
+    for (uint32_t t = 0; t < PULL_CHUNK_BITS / PULL_THREADS; ++t) {   // coalesced domain reads, compaction in LDS
         const uint32_t wi = t * (PULL_THREADS / 32) + (threadIdx.x >> 5);
         const uint32_t ww = s_word[wi];
-        if (!((ww >> b) & 1u)) continue;
-        const uint32_t j = j0 + wi * 32 + b;
-        const uint32_t kl = s_pre[wi] + __popc(ww & ((1u << b) - 1u));
-        const uint32_t row = dom[j];
-        if (direct) {
-            if (kbase + kl < count) dense[row] = vals[kbase + kl];
-        } else {
-            s_rows[kl] = row;
-        }
+        if ((ww >> b) & 1u) s_rows[s_pre[wi] + __popc(ww & ((1u << b) - 1u))] = dom[j0 + wi * 32 + b];
     }
-    if (direct) return;
     __syncthreads();
-    if (INDICES) {
-        for (uint32_t i = threadIdx.x; i < total; i += PULL_THREADS)
-            if ((uint64_t)kbase + i < out_cap) out_idx[kbase + i] = s_rows[i];
-    } else {
-        const uint32_t usable = kbase >= count ? 0u : min(total, count - kbase);
-        place_rows(vals, dense, D, lanes, s_rows, kbase, usable);
-    }
+    uint32_t *__restrict__ out = out_idx.v[server];
+    const uint64_t cap = out_cap.v[server];
+    for (uint32_t i = threadIdx.x; i < total; i += PULL_THREADS)
+        if ((uint64_t)kbase + i < cap) out[kbase + i] = s_rows[i];
 }
 
-// Parts given as index lists: dense[indices[k]] = values[k].  grid = (x, parts).
+// dense[indices[k]] = values[k] for index-list parts (given, or decoded by pull_decode_kernel: bit
+// `server` of decoded_mask, whose row count is the smaller of *count and the bitmap's set bits).
+// grid = (x, parts); one group of `lanes` threads per row, rows spread over the whole grid.
 __global__ void __launch_bounds__(PULL_THREADS)
-pull_place_coo_kernel(PullSrc a, uint64_t n_rows, uint32_t D, uint32_t lanes, float *dense, zen_status_info *status)
+pull_place_rows_kernel(PullSrc a, uint64_t decoded_mask, const uint32_t *cnt, uint32_t n_chunks, uint64_t n_rows,
+                       uint32_t D, uint32_t lanes, float *dense, zen_status_info *status)
 {
     const uint32_t server = blockIdx.y;
     const uint32_t *__restrict__ idx = a.indices[server];
     if (!idx) return;
-    const uint32_t count = *a.count[server];
+    uint32_t count = *a.count[server];
+    if ((decoded_mask >> server) & 1ull) count = min(count, cnt[(uint64_t)server * (n_chunks + 1) + n_chunks]);
     const float *__restrict__ vals = a.values[server];
     bool bad = false;
     if (D == 1) {
@@ -315,13 +279,140 @@ pull_place_coo_kernel(PullSrc a, uint64_t n_rows, uint32_t D, uint32_t lanes, fl
             if ((D & 3u) == 0) {
                 const u32x4 *src = (const u32x4 *)(vals + k * D);
                 u32x4 *dst = (u32x4 *)(dense + (uint64_t)r * D);
-                for (uint32_t v = l; v < (D >> 2); v += lanes) dst[v] = src[v];
+                const uint32_t V = D >> 2;
+                for (uint32_t v = l; v < V; v += lanes * 4) {
+                    u32x4 x[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (v + lanes * u < V) x[u] = src[v + lanes * u];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (v + lanes * u < V) dst[v + lanes * u] = x[u];
+                }
             } else {
                 for (uint32_t v = l; v < D; v += lanes) dense[(uint64_t)r * D + v] = vals[k * D + v];
             }
         }
     }
     if (bad) atomicOr(&status->flags, 4u);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Element-level tensors (row_dim == 1): placement by tiles of consecutive rows.  The rows of a tile
+// that belong to partition p occupy a CONTIGUOUS stretch [base[tile][p], base[tile+1][p]) of II_p, so
+// their bits, their domain entries and (set bits being consecutive) their values are all read with
+// unit stride; the tile is assembled in LDS and stored once with 16-byte stores -- zeros included,
+// so no zero fill and no scattered 4-byte stores to HBM.
+// ------------------------------------------------------------------------------------------------
+
+// base[t][p] = number of rows of II_p below row t * PULL_TILE_ROWS (built once per context).
+__global__ void pull_base_kernel(const uint32_t *domain, const uint32_t *dom_offsets, uint32_t n_parts,
+                                 uint32_t n_tiles, uint64_t n_rows, uint32_t *base)
+{
+    const uint64_t total = ((uint64_t)n_tiles + 1) * n_parts;
+    for (uint64_t id = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total;
+         id += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t p = (uint32_t)(id % n_parts), t = (uint32_t)(id / n_parts);
+        const uint64_t key = min((uint64_t)t * PULL_TILE_ROWS, n_rows);
+        const uint32_t *dom = domain + dom_offsets[p];
+        uint32_t lo = 0, hi = dom_offsets[p + 1] - dom_offsets[p];
+        while (lo < hi) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if ((uint64_t)dom[mid] < key) lo = mid + 1; else hi = mid;
+        }
+        base[id] = lo;
+    }
+}
+
+// cnt[server][tile] = set bits of the part's bitmap inside the tile's stretch of the domain.
+__global__ void __launch_bounds__(PULL_THREADS)
+pull_tile_count_kernel(PullSrc a, const uint32_t *base, uint32_t n_parts, uint32_t *cnt, uint32_t n_tiles)
+{
+    const uint64_t total = (uint64_t)n_tiles * a.n;
+    for (uint64_t id = (uint64_t)blockIdx.x * PULL_THREADS + threadIdx.x; id < total;
+         id += (uint64_t)gridDim.x * PULL_THREADS) {
+        const uint32_t server = (uint32_t)(id % a.n), tile = (uint32_t)(id / a.n), p = a.first_part + server;
+        const uint32_t b0 = base[(uint64_t)tile * n_parts + p], b1 = base[(uint64_t)(tile + 1) * n_parts + p];
+        const uint32_t *__restrict__ bm = a.indices[server] ? nullptr : a.bitmap[server];
+        uint32_t c = 0;
+        if (bm && b1 > b0) {
+            const uint32_t w0 = b0 >> 5, w1 = (b1 - 1) >> 5;
+            for (uint32_t w = w0; w <= w1; ++w) {
+                uint32_t word = bm[w];
+                if (w == w0) word &= 0xFFFFFFFFu << (b0 & 31u);
+                if (w == w1 && (b1 & 31u)) word &= (1u << (b1 & 31u)) - 1u;
+                c += __popc(word);
+            }
+        }
+        cnt[(uint64_t)server * (n_tiles + 1) + tile] = c;
+    }
+}
+
+// One block per tile; groups of G lanes walk one partition's stretch each.  direct = 0: the whole tile
+// (zeros where no partition of this launch group holds the row) is stored; direct = 1: only the rows
+// this launch group holds are stored (further groups of a context with more than ZEN_MAX_BATCH
+// partitions, after the first group has written every tile).
+template <int G>
+__global__ void __launch_bounds__(PULL_THREADS)
+pull_tile_place_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *base,
+                       uint32_t n_parts, const uint32_t *cnt, uint32_t n_tiles, uint64_t n_rows, float *dense,
+                       uint32_t direct)
+{
+    __shared__ float s_out[PULL_TILE_ROWS];
+    constexpr uint32_t GROUPS = PULL_THREADS / G;
+    constexpr uint64_t GMASK = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
+    const uint32_t tile = blockIdx.x, grp = threadIdx.x / G, gl = threadIdx.x % G;
+    const uint32_t gshift = (lane_id() / G) * G;
+    const uint64_t row0 = (uint64_t)tile * PULL_TILE_ROWS;
+    if (!direct && a.n < n_parts) {   // rows of partitions outside this launch group: zero for now
+        for (uint32_t i = threadIdx.x; i < PULL_TILE_ROWS; i += PULL_THREADS) s_out[i] = 0.f;
+        __syncthreads();
+    }
+    for (uint32_t s0 = 0; s0 < a.n; s0 += GROUPS) {
+        const uint32_t server = s0 + grp;
+        uint32_t b0 = 0, b1 = 0, kbase = 0, count = 0;
+        const uint32_t *__restrict__ bm = nullptr, *__restrict__ dom = nullptr;
+        const float *__restrict__ vals = nullptr;
+        if (server < a.n) {
+            const uint32_t p = a.first_part + server;
+            b0 = base[(uint64_t)tile * n_parts + p];
+            b1 = base[(uint64_t)(tile + 1) * n_parts + p];
+            bm = a.indices[server] ? nullptr : a.bitmap[server];
+            dom = domain + dom_offsets[p];
+            vals = a.values[server];
+            kbase = cnt[(uint64_t)server * (n_tiles + 1) + tile];
+            count = *a.count[server];
+        }
+        uint32_t run = 0;
+        for (uint32_t jb = b0; ballot(jb < b1) != 0; jb += G) {   // uniform per wave: until every group is done
+            const uint32_t j = jb + gl;
+            const bool valid = j < b1;
+            const uint32_t word = (valid && bm) ? bm[j >> 5] : 0u;
+            const bool bit = valid && ((word >> (j & 31u)) & 1u);
+            const uint64_t gbits = (ballot(bit) >> gshift) & GMASK;
+            const uint32_t k = kbase + run + (uint32_t)__popcll(gbits & ((1ull << gl) - 1ull));
+            run += (uint32_t)__popcll(gbits);
+            if (valid) {
+                const uint32_t row = dom[j];
+                const bool take = bit && k < count;
+                const float v = take ? vals[k] : 0.f;
+                if (!direct) s_out[row - row0] = v;
+                else if (take) dense[row] = v;
+            }
+        }
+    }
+    if (direct) return;
+    __syncthreads();
+    const uint32_t here = (uint32_t)min((uint64_t)PULL_TILE_ROWS, n_rows - row0);
+    float *__restrict__ out = dense + row0;   // 16-byte aligned: row0 is a multiple of the tile size
+    for (uint32_t i = threadIdx.x * 4; i < here; i += PULL_THREADS * 4) {
+        if (i + 4 <= here) {
+            const f32x4 v = {s_out[i], s_out[i + 1], s_out[i + 2], s_out[i + 3]};
+            *(f32x4 *)(out + i) = v;
+        } else {
+            for (uint32_t e = i; e < here; ++e) out[e] = s_out[e];
+        }
+    }
 }
 
 #define ZEN_LAUNCH_CHECK()                         \
@@ -331,18 +422,24 @@ pull_place_coo_kernel(PullSrc a, uint64_t n_rows, uint32_t D, uint32_t lanes, fl
     } while (0)
 
 struct PullLayout {
-    uint64_t status_off, cnt_off, n_chunks, total;
+    uint64_t status_off, cnt_off, n_chunks, n_tiles, dec_off, total;
 };
 
 static PullLayout pull_layout(const zen_ctx *ctx)
 {
     PullLayout L{};
-    const uint32_t group = ctx->geo.n_parts < ZEN_MAX_BATCH ? ctx->geo.n_parts : ZEN_MAX_BATCH;
+    const Geometry &g = ctx->geo;
+    const uint32_t group = g.n_parts < ZEN_MAX_BATCH ? g.n_parts : ZEN_MAX_BATCH;
     L.status_off = 0;
     L.cnt_off = 256;
     L.n_chunks = (ctx->max_dom_words + PULL_CHUNK_WORDS - 1) / PULL_CHUNK_WORDS;
     if (L.n_chunks < 1) L.n_chunks = 1;
-    L.total = L.cnt_off + ((uint64_t)group * (L.n_chunks + 1) * 4 + 255) / 256 * 256;
+    L.n_tiles = (g.n_rows + PULL_TILE_ROWS - 1) / PULL_TILE_ROWS;
+    const uint64_t per = (L.n_chunks > L.n_tiles ? L.n_chunks : L.n_tiles) + 1;
+    L.dec_off = L.cnt_off + ((uint64_t)group * per * 4 + 255) / 256 * 256;
+    // wide rows: bitmap parts are decoded into index lists first (at most one entry per row of the tensor)
+    const uint64_t dec_bytes = (ctx->fmt == ZEN_INDEX_BITMAP && g.row_dim > 1) ? g.n_rows * 4 : 0;
+    L.total = L.dec_off + (dec_bytes + 255) / 256 * 256;
     return L;
 }
 
@@ -355,6 +452,23 @@ static uint32_t lanes_per_row(uint32_t D)
     return l;
 }
 
+hipError_t build_pull_tables(zen_ctx *ctx, hipStream_t s)
+{
+    const Geometry &g = ctx->geo;
+    if (ctx->fmt != ZEN_INDEX_BITMAP || g.row_dim != 1) return hipSuccess;
+    const uint64_t n_tiles = (g.n_rows + PULL_TILE_ROWS - 1) / PULL_TILE_ROWS;
+    const uint64_t entries = (n_tiles + 1) * g.n_parts;
+    hipError_t e = hipMalloc(&ctx->d_pull_base, entries * 4);
+    if (e != hipSuccess) return e;
+    uint64_t blocks = (entries + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    pull_base_kernel<<<(uint32_t)blocks, 256, 0, s>>>(ctx->d_domain, ctx->d_dom_offsets, g.n_parts, (uint32_t)n_tiles,
+                                                      g.n_rows, ctx->d_pull_base);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(s);
+}
+
 static hipError_t launch_pull_encode(zen_ctx *ctx, const PullSrc &src, const Arr64<uint64_t> &caps,
                                      const Arr64<uint32_t *> &out_words, zen_status_info *status, hipStream_t s)
 {
@@ -365,11 +479,11 @@ static hipError_t launch_pull_encode(zen_ctx *ctx, const PullSrc &src, const Arr
     return hipGetLastError();
 }
 
-// count -> scan -> place for the bitmap parts of one group.
-static hipError_t launch_pull_bitmap(zen_ctx *ctx, const PullSrc &src, char *ws, float *dense, uint32_t *out_idx,
-                                     uint64_t out_cap, uint32_t *out_count, hipStream_t s)
+// count -> scan -> decode for the bitmap parts of one group; out_count / out_cap0: single-part decode
+// to a caller's list (capacity flag), else lists without a count of their own.
+static hipError_t launch_pull_decode(zen_ctx *ctx, const PullSrc &src, char *ws, const Arr64<uint32_t *> &out_idx,
+                                     const Arr64<uint64_t> &out_cap, uint32_t *out_count, hipStream_t s)
 {
-    const Geometry &g = ctx->geo;
     const PullLayout L = pull_layout(ctx);
     zen_status_info *status = (zen_status_info *)(ws + L.status_off);
     uint32_t *cnt = (uint32_t *)(ws + L.cnt_off);
@@ -381,23 +495,53 @@ static hipError_t launch_pull_bitmap(zen_ctx *ctx, const PullSrc &src, char *ws,
     }
     {
         ProfScope prof(ctx, K_PULL_SCAN, s);
-        pull_scan_kernel<<<src.n, PULL_THREADS, 0, s>>>(src, cnt, n_chunks, out_count, out_cap, status);
+        pull_scan_kernel<<<src.n, PULL_THREADS, 0, s>>>(src, cnt, n_chunks, out_count, out_cap.v[0], status);
         ZEN_LAUNCH_CHECK();
     }
     {
-        const uint64_t chunks8 = (L.n_chunks + 7) / 8 * 8;
-        const uint64_t blocks = chunks8 * src.n;
+        const uint64_t blocks = L.n_chunks * src.n;
         if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
         ProfScope prof(ctx, K_PULL_PLACE, s);
-        if (out_idx) {
-            pull_place_kernel<true><<<(uint32_t)blocks, PULL_THREADS, PULL_CHUNK_BITS * 4, s>>>(
-                src, ctx->d_domain, ctx->d_dom_offsets, cnt, n_chunks, g.row_dim, 1, nullptr, out_idx, out_cap);
-        } else {
-            const size_t lds = g.row_dim == 1 ? 0 : PULL_CHUNK_BITS * 4;
-            pull_place_kernel<false><<<(uint32_t)blocks, PULL_THREADS, lds, s>>>(
-                src, ctx->d_domain, ctx->d_dom_offsets, cnt, n_chunks, g.row_dim, lanes_per_row(g.row_dim), dense,
-                nullptr, 0);
-        }
+        pull_decode_kernel<<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(src, ctx->d_domain, ctx->d_dom_offsets, cnt,
+                                                                     n_chunks, out_idx, out_cap);
+        ZEN_LAUNCH_CHECK();
+    }
+    return hipSuccess;
+}
+
+// Element-level tensors: tile counts -> scan -> tile placement for one group.
+static hipError_t launch_pull_tiles(zen_ctx *ctx, const PullSrc &src, char *ws, float *dense, bool direct,
+                                    hipStream_t s)
+{
+    const Geometry &g = ctx->geo;
+    const PullLayout L = pull_layout(ctx);
+    zen_status_info *status = (zen_status_info *)(ws + L.status_off);
+    uint32_t *cnt = (uint32_t *)(ws + L.cnt_off);
+    const uint32_t n_tiles = (uint32_t)L.n_tiles;
+    {
+        uint64_t blocks = ((uint64_t)n_tiles * src.n + PULL_THREADS - 1) / PULL_THREADS;
+        if (blocks > 65536) blocks = 65536;
+        ProfScope prof(ctx, K_PULL_COUNT, s);
+        pull_tile_count_kernel<<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(src, ctx->d_pull_base, g.n_parts, cnt, n_tiles);
+        ZEN_LAUNCH_CHECK();
+    }
+    {
+        ProfScope prof(ctx, K_PULL_SCAN, s);
+        pull_scan_kernel<<<src.n, PULL_THREADS, 0, s>>>(src, cnt, n_tiles, nullptr, 0, status);
+        ZEN_LAUNCH_CHECK();
+    }
+    {
+        const uint64_t per = PULL_TILE_ROWS / g.n_parts;   // expected rows of one partition in a tile
+        ProfScope prof(ctx, K_PULL_PLACE, s);
+#define ZEN_TILE_PLACE(G_)                                                                                     \
+    pull_tile_place_kernel<G_><<<n_tiles, PULL_THREADS, 0, s>>>(src, ctx->d_domain, ctx->d_dom_offsets,            \
+                                                                ctx->d_pull_base, g.n_parts, cnt, n_tiles, g.n_rows, \
+                                                                dense, direct ? 1u : 0u)
+        if (per > 32) ZEN_TILE_PLACE(64);
+        else if (per > 16) ZEN_TILE_PLACE(32);
+        else if (per > 8) ZEN_TILE_PLACE(16);
+        else ZEN_TILE_PLACE(8);
+#undef ZEN_TILE_PLACE
         ZEN_LAUNCH_CHECK();
     }
     return hipSuccess;
@@ -498,11 +642,17 @@ zen_status zen_pull_decode(zen_ctx *ctx, const uint32_t *bitmap_words, uint32_t 
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(launch_fill_u32((uint32_t *)((char *)workspace + L.status_off), 4, 0u, s));
     PullSrc src;
+    Arr64<uint32_t *> oi;
+    Arr64<uint64_t> oc;
     memset(&src, 0, sizeof(src));
+    memset(&oi, 0, sizeof(oi));
+    memset(&oc, 0, sizeof(oc));
     src.n = 1;
     src.first_part = part_id;
     src.bitmap[0] = bitmap_words;
-    HIP_TRY(launch_pull_bitmap(ctx, src, (char *)workspace, nullptr, out_indices, out_cap_rows, out_count, s));
+    oi.v[0] = out_indices;
+    oc.v[0] = out_cap_rows;
+    HIP_TRY(launch_pull_decode(ctx, src, (char *)workspace, oi, oc, out_count, s));
     return ZEN_OK;
 }
 
@@ -513,10 +663,12 @@ zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense
     if (((uintptr_t)workspace & 255u) || ((uintptr_t)dense & 15u)) return ZEN_ERR_INVALID;
     const Geometry &g = ctx->geo;
     const uint32_t n = g.n_parts;
+    bool any_bitmap_at_all = false;
     for (uint32_t p = 0; p < n; ++p) {
         const zen_part &q = host_parts[p];
         if (!q.count || !q.values || (!q.indices && !q.bitmap) || ((uintptr_t)q.values & 15u)) return ZEN_ERR_INVALID;
         if (!q.indices && ctx->fmt != ZEN_INDEX_BITMAP) return ZEN_ERR_INVALID;   // no domain tables
+        if (!q.indices) any_bitmap_at_all = true;
     }
     const PullLayout L = pull_layout(ctx);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
@@ -524,7 +676,12 @@ zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense
     char *ws = (char *)workspace;
     zen_status_info *status = (zen_status_info *)(ws + L.status_off);
     const uint64_t n_elems = g.n_rows * g.row_dim;
-    {
+    // Element-level tensors with bitmap parts are written tile by tile, zeros included; everything
+    // else starts from a zero fill.
+    const bool tiles = g.row_dim == 1 && any_bitmap_at_all && ctx->d_pull_base;
+    if (tiles) {
+        HIP_TRY(launch_fill_u32((uint32_t *)status, 4, 0u, s));
+    } else {
         uint64_t blocks = ((n_elems >> 2) + PULL_THREADS * 4 - 1) / (PULL_THREADS * 4);
         if (blocks < 1) blocks = 1;
         if (blocks > 16384) blocks = 16384;
@@ -532,26 +689,53 @@ zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense
         pull_zero_kernel<<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);
         HIP_TRY(hipGetLastError());
     }
+    uint32_t *dec = (uint32_t *)(ws + L.dec_off);
+    uint64_t dom_start = 0;   // start of partition p's decoded list = start of its domain
     for (uint32_t p0 = 0; p0 < n; p0 += ZEN_MAX_BATCH) {
         PullSrc src;
         memset(&src, 0, sizeof(src));
         src.n = n - p0 < ZEN_MAX_BATCH ? n - p0 : ZEN_MAX_BATCH;
         src.first_part = p0;
-        bool any_bitmap = false, any_coo = false;
+        bool any_bitmap = false, any_list = false;
         for (uint32_t i = 0; i < src.n; ++i) {
             const zen_part &q = host_parts[p0 + i];
             src.indices[i] = q.indices;
             src.bitmap[i] = q.bitmap;
             src.values[i] = q.values;
             src.count[i] = q.count;
-            if (q.indices) any_coo = true; else any_bitmap = true;
+            if (q.indices) any_list = true; else any_bitmap = true;
         }
-        if (any_bitmap) HIP_TRY(launch_pull_bitmap(ctx, src, ws, dense, nullptr, 0, nullptr, s));
-        if (any_coo) {
+        uint64_t decoded_mask = 0;
+        if (tiles) {
+            // the first group writes every tile in full (also when it holds index lists only)
+            if (any_bitmap || p0 == 0) HIP_TRY(launch_pull_tiles(ctx, src, ws, dense, p0 != 0, s));
+        } else if (any_bitmap) {
+            Arr64<uint32_t *> oi;
+            Arr64<uint64_t> oc;
+            memset(&oi, 0, sizeof(oi));
+            memset(&oc, 0, sizeof(oc));
+            uint64_t d = dom_start;
+            for (uint32_t i = 0; i < src.n; ++i) {
+                oi.v[i] = dec + d;
+                oc.v[i] = ctx->h_dom_sizes[p0 + i];
+                d += ctx->h_dom_sizes[p0 + i];
+            }
+            HIP_TRY(launch_pull_decode(ctx, src, ws, oi, oc, nullptr, s));
+            for (uint32_t i = 0; i < src.n; ++i)
+                if (!src.indices[i]) {
+                    src.indices[i] = oi.v[i];
+                    decoded_mask |= 1ull << i;
+                }
+            any_list = true;
+        }
+        if (ctx->fmt == ZEN_INDEX_BITMAP)
+            for (uint32_t i = 0; i < src.n; ++i) dom_start += ctx->h_dom_sizes[p0 + i];
+        if (any_list) {
             ProfScope prof(ctx, K_PULL_PLACE_COO, s);
             const uint32_t lanes = lanes_per_row(g.row_dim);
-            pull_place_coo_kernel<<<dim3(g.row_dim == 1 ? 512 : 1024, src.n), PULL_THREADS, 0, s>>>(
-                src, g.n_rows, g.row_dim, lanes, dense, status);
+            pull_place_rows_kernel<<<dim3(g.row_dim == 1 ? 512 : 1024, src.n), PULL_THREADS, 0, s>>>(
+                src, decoded_mask, (const uint32_t *)(ws + L.cnt_off), (uint32_t)L.n_chunks, g.n_rows, g.row_dim, lanes,
+                dense, status);
             HIP_TRY(hipGetLastError());
         }
     }

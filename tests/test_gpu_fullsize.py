@@ -99,6 +99,7 @@ def test_full_size_workload(oracle, cid):
     for w in range(wl.n_workers):
         if w not in refs:
             refs[w] = _oracle_partition(oracle, wl, sparse[w][0])
+    agg_refs = {}
     for j in check_servers:
         parts = []
         for w in range(wl.n_workers):
@@ -110,3 +111,39 @@ def test_full_size_workload(oracle, cid):
         U, idx, val = G.aggregated_to_host(aggs[j])
         assert U == ref.U and np.array_equal(idx, ref.indices)
         G.check_sums(val, ref)
+        agg_refs[j] = ref
+        del parts, val
+
+    # Pull: every server's hash bitmap of what it aggregated, then the worker's decode + placement into
+    # the dense synchronized tensor.  Bitmaps: popcount of every partition = its row count, sampled
+    # partitions decoded by the oracle.  Dense tensor: rows of the sampled servers against the
+    # oracle's sums, sampled rows outside the union exactly zero.
+    del grads
+    torch.cuda.empty_cache()
+    pctx = ctx if wl.bitmap else zen.ZenContext(wl.n_rows, D, n, wl.hash_seed, zen.ZEN_INDEX_BITMAP)
+    total, woff, dsz = zen.zen_bitmap_layout(pctx)
+    ws3 = zen.alloc_workspace(zen.zen_pull_workspace_bytes(pctx))
+    bitmap = torch.empty(max(total, 1), dtype=torch.int32, device="cuda")
+    zen.zen_pull_encode_batch(pctx, aggs, bitmap, ws3)
+    assert zen.zen_status_fetch(pctx, ws3) == (0, 0, 0)
+    bm = G.u32(bitmap[:total])
+    pop8 = np.array([bin(i).count("1") for i in range(256)], np.uint8)
+    for p in range(n):
+        assert int(pop8[bm[woff[p]:woff[p + 1]].view(np.uint8)].sum()) == counts[p]
+    owner = oracle.owner_table(wl.n_rows, n, wl.hash_seed)
+    for j in check_servers:
+        assert np.array_equal(oracle.bitmap_decode(owner, j, bm[woff[j]:woff[j + 1]]), agg_refs[j].indices)
+    dense = torch.empty((wl.n_rows, D), dtype=torch.float32, device="cuda")
+    parts = [(None, bitmap[woff[p]:], aggs[p].values, aggs[p].count) for p in range(n)]
+    zen.zen_pull_apply(pctx, parts, dense, ws3)
+    assert zen.zen_status_fetch(pctx, ws3) == (0, 0, 0)
+    for j in check_servers:
+        ref = agg_refs[j]
+        sel = torch.from_numpy(ref.indices.astype(np.int64)).cuda()
+        G.check_sums(dense[sel].cpu().numpy(), ref)
+    rng = np.random.default_rng(cid)
+    probe = np.setdiff1d(np.unique(rng.integers(0, wl.n_rows, size=200000)), union)
+    if probe.size:
+        assert not dense[torch.from_numpy(probe).cuda()].any().item()
+    nz_rows = int((dense != 0).any(dim=1).sum().item())
+    assert nz_rows <= union.size and nz_rows >= union.size - 64          # only exact cancellations may be missing
