@@ -11,6 +11,7 @@
 //            tensor (the outcome of synchronization, section "Elemental Dimensions for
 //            Synchronization"): zero fill, per-chunk popcounts, scan, then every set bit j of
 //            partition p with running number k puts values[p][k] at row II_p[j].
+#include <stdlib.h>
 #include <string.h>
 #include "zen_device.h"
 #include "zen_internal.h"
@@ -80,14 +81,35 @@ __device__ __forceinline__ uint32_t wave_lower_bound(const uint32_t *__restrict_
 // grid = (chunks, servers).  Flag 4 is raised for input that is not an ascending list of distinct
 // rows of II_p (a row of another partition, a duplicate, an index out of order).
 // ------------------------------------------------------------------------------------------------
+// bounds[server][c] = first index of the list that is not below the first domain row of chunk c
+// (c = 0: 0; c = number of chunks: the list's length), found by one wave per (chunk, server).
+__global__ void __launch_bounds__(PULL_THREADS)
+pull_bounds_kernel(PullSrc a, Arr64<uint64_t> cap_rows, const uint32_t *domain, const uint32_t *dom_offsets,
+                   uint32_t *bounds, uint32_t n_chunks)
+{
+    const uint32_t wave_id = blockIdx.x * (PULL_THREADS / ZEN_WAVE) + (threadIdx.x >> 6);
+    const uint32_t server = blockIdx.y, p = a.first_part + server;
+    if (wave_id > n_chunks) return;
+    uint32_t cnt = *a.count[server];
+    if ((uint64_t)cnt > cap_rows.v[server]) cnt = (uint32_t)cap_rows.v[server];
+    const uint32_t d0 = dom_offsets[p], n_dom = dom_offsets[p + 1] - d0, n_words = (n_dom + 31) >> 5;
+    const uint32_t active = (n_words + PULL_CHUNK_WORDS - 1) / PULL_CHUNK_WORDS;
+    uint32_t k;
+    if (wave_id == 0) k = 0;
+    else if (wave_id >= active) k = cnt;
+    else k = wave_lower_bound(a.indices[server], cnt, domain[d0 + wave_id * PULL_CHUNK_BITS]);
+    if (lane_id() == 0) bounds[(uint64_t)server * (n_chunks + 1) + wave_id] = k;
+}
+
 __global__ void __launch_bounds__(PULL_THREADS)
 pull_encode_kernel(PullSrc a, Arr64<uint64_t> cap_rows, Arr64<uint32_t *> out_words, const uint32_t *domain,
-                   const uint32_t *dom_offsets, zen_status_info *status)
+                   const uint32_t *dom_offsets, const uint32_t *bounds, uint32_t n_chunks, zen_status_info *status)
 {
     __shared__ uint32_t s_idx[PULL_CHUNK_BITS];
-    __shared__ uint32_t s_k[3], s_found;
+    __shared__ uint32_t s_dom[PULL_CHUNK_BITS + PULL_CHUNK_WORDS];   // entry e at e + e/32: a thread's 32 entries
+    __shared__ uint32_t s_found;                                     // start in 32 different banks
     const uint32_t chunk = blockIdx.x, server = blockIdx.y, p = a.first_part + server;
-    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t lane = lane_id();
     const uint32_t *__restrict__ idx = a.indices[server];
     uint32_t cnt = *a.count[server];
     if ((uint64_t)cnt > cap_rows.v[server]) cnt = (uint32_t)cap_rows.v[server];
@@ -97,49 +119,58 @@ pull_encode_kernel(PullSrc a, Arr64<uint64_t> cap_rows, Arr64<uint32_t *> out_wo
         if (chunk == 0 && cnt != 0 && threadIdx.x == 0) atomicOr(&status->flags, 4u);
         return;
     }
+    // The chunk's slice of the list: everything from this chunk's first row up to the next chunk's.
+    // An index that is no row of the domain lands in some slice and is noticed there as unmatched.
+    const uint32_t k0 = bounds[(uint64_t)server * (n_chunks + 1) + chunk];
+    const uint32_t k1 = min(cnt, bounds[(uint64_t)server * (n_chunks + 1) + chunk + 1]);
     const uint32_t *__restrict__ dom = domain + d0;
     const uint32_t j0 = chunk * PULL_CHUNK_BITS, j1 = min(j0 + PULL_CHUNK_BITS, n_dom);
-    if (wave == 0) {          // first index that can belong to this chunk
-        const uint32_t k = wave_lower_bound(idx, cnt, dom[j0]);
-        if (lane == 0) s_k[0] = k;
-    } else if (wave == 1) {   // first index past this chunk (row ids stay below 2^32 - 1: no wrap)
-        const uint32_t k = wave_lower_bound(idx, cnt, dom[j1 - 1] + 1u);
-        if (lane == 0) s_k[1] = k;
-    } else if (wave == 2) {   // where the previous chunk ended: indices in between belong to no chunk
-        const uint32_t k = chunk ? wave_lower_bound(idx, cnt, dom[j0 - 1] + 1u) : 0u;
-        if (lane == 0) s_k[2] = k;
+    const bool bad = k1 < k0 || k1 - k0 > PULL_CHUNK_BITS;   // out of order / more indices than domain rows
+    const uint32_t m_all = k1 < k0 ? 0u : k1 - k0;
+    const uint32_t m = min(m_all, PULL_CHUNK_BITS);
+    // Both lists go to LDS; loads are issued in batches of 8 per list so that 16 are in flight per thread.
+    const uint32_t n_here_all = j1 - j0;
+    for (uint32_t t0 = 0; t0 < PULL_CHUNK_BITS / PULL_THREADS; t0 += 8) {
+        uint32_t rd[8], ri[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t e = (t0 + u) * PULL_THREADS + threadIdx.x;
+            rd[u] = e < n_here_all ? dom[j0 + e] : 0u;
+            ri[u] = e < m ? idx[k0 + e] : 0u;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t e = (t0 + u) * PULL_THREADS + threadIdx.x;
+            if (e < n_here_all) s_dom[e + (e >> 5)] = rd[u];
+            if (e < m) s_idx[e] = ri[u];
+        }
     }
     if (threadIdx.x == 0) s_found = 0;
     __syncthreads();
-    const uint32_t k0 = s_k[0], k1 = s_k[1];
-    bool bad = k1 < k0 || s_k[2] != k0 || (chunk == active - 1 && k1 != cnt);
-    const uint32_t m_all = k1 < k0 ? 0u : k1 - k0;
-    if (m_all > PULL_CHUNK_BITS) bad = true;   // more indices than domain rows
-    const uint32_t m = min(m_all, PULL_CHUNK_BITS);
-    for (uint32_t i = threadIdx.x; i < m; i += PULL_THREADS) s_idx[i] = idx[k0 + i];
-    __syncthreads();
-    uint32_t *__restrict__ bm = out_words.v[server];
-    uint32_t found = 0;
-#pragma unroll 4
-    for (uint32_t t = 0; t < PULL_CHUNK_BITS / PULL_THREADS; ++t) {
-        const uint32_t j = j0 + t * PULL_THREADS + threadIdx.x;
-        const bool valid = j < j1;
-        const uint32_t row = valid ? dom[j] : 0u;
-        uint32_t pos = 0;   // number of slice entries below `row`
+    // One bitmap word per thread: locate the word's first row in the slice, then merge 32 rows.
+    const uint32_t e0 = threadIdx.x * 32, word = (j0 >> 5) + threadIdx.x;
+    uint32_t bits = 0;
+    if (j0 + e0 < j1) {
+        const uint32_t n_here = min(32u, j1 - j0 - e0);
+        const uint32_t *rows = s_dom + e0 + threadIdx.x;
+        const uint32_t first = rows[0];
+        uint32_t pos = 0;   // number of slice entries below the word's first row
 #pragma unroll
         for (uint32_t step = PULL_CHUNK_BITS / 2; step; step >>= 1) {
             const uint32_t q = pos + step;
-            if (q <= m && s_idx[q - 1] < row) pos = q;
+            if (q <= m && s_idx[q - 1] < first) pos = q;
         }
-        if (pos < m && s_idx[pos] < row) ++pos;   // a full slice (m = 8,192) needs one more step
-        const bool member = valid && pos < m && s_idx[pos] == row;
-        const uint64_t bal = ballot(member);
-        const uint32_t word = (j0 >> 5) + t * (PULL_THREADS / 32) + wave * 2;
-        if (lane == 0 && word < n_words) bm[word] = (uint32_t)bal;
-        if (lane == 32 && word + 1 < n_words) bm[word + 1] = (uint32_t)(bal >> 32);
-        found += (uint32_t)__popcll(bal);
+        if (pos < m && s_idx[pos] < first) ++pos;   // a full slice (m = 8,192) needs one more step
+        for (uint32_t b = 0; b < n_here && pos < m; ++b) {
+            const uint32_t row = rows[b];
+            uint32_t v = s_idx[pos];
+            while (v < row && ++pos < m) v = s_idx[pos];   // entries that are no row of this domain, or repeats
+            if (pos < m && v == row) { bits |= 1u << b; ++pos; }
+        }
     }
-    if (lane == 0) atomicAdd(&s_found, found);
+    if (word < n_words) out_words.v[server][word] = bits;
+    const uint32_t found = wave_sum_u32(__popc(bits));
+    if (lane == 0 && found) atomicAdd(&s_found, found);
     __syncthreads();
     if (threadIdx.x == 0 && (bad || s_found != m_all)) atomicOr(&status->flags, 4u);
 }
@@ -149,6 +180,7 @@ pull_encode_kernel(PullSrc a, Arr64<uint64_t> cap_rows, Arr64<uint32_t *> out_wo
 // ------------------------------------------------------------------------------------------------
 
 // dense = 0 (16-byte streaming stores) and a clean status block.
+template <bool NT>
 __global__ void __launch_bounds__(PULL_THREADS)
 pull_zero_kernel(float *dense, uint64_t n_elems, zen_status_info *status)
 {
@@ -160,7 +192,10 @@ pull_zero_kernel(float *dense, uint64_t n_elems, zen_status_info *status)
     for (uint64_t i = (uint64_t)blockIdx.x * PULL_THREADS * 4 + threadIdx.x; i < n_vec; i += stride) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            if (i + (uint64_t)u * PULL_THREADS < n_vec) __builtin_nontemporal_store(z, d + i + (uint64_t)u * PULL_THREADS);
+            if (i + (uint64_t)u * PULL_THREADS < n_vec) {
+                if (NT) __builtin_nontemporal_store(z, d + i + (uint64_t)u * PULL_THREADS);
+                else d[i + (uint64_t)u * PULL_THREADS] = z;
+            }
     }
     if (blockIdx.x == 0 && threadIdx.x < (n_elems & 3u)) dense[(n_vec << 2) + threadIdx.x] = 0.f;
 }
@@ -348,57 +383,114 @@ pull_tile_count_kernel(PullSrc a, const uint32_t *base, uint32_t n_parts, uint32
     }
 }
 
-// One block per tile; groups of G lanes walk one partition's stretch each.  direct = 0: the whole tile
-// (zeros where no partition of this launch group holds the row) is stored; direct = 1: only the rows
-// this launch group holds are stored (further groups of a context with more than ZEN_MAX_BATCH
-// partitions, after the first group has written every tile).
-template <int G>
+// One block per tile.  Phase 1: the tile's stretch of every partition (start, length, words).  Phase 2:
+// the stretches' bitmap words, masked to the stretch, go to LDS with a running popcount.  Phase 3: the
+// tile's rows are walked as ONE flat list (partition after partition), so every thread's domain and
+// value loads are independent of each other and of all other threads': a handful of dependent memory
+// round trips per block instead of one per partition.  Phase 4: the tile is stored.
+// direct = 0: the whole tile (zeros where no partition of this launch group holds the row) is stored;
+// direct = 1: only the rows this launch group holds are stored (further groups of a context with more
+// than ZEN_MAX_BATCH partitions, after the first group has written every tile).
+static constexpr uint32_t PULL_TILE_WORDS = PULL_TILE_ROWS / 32 + 2 * ZEN_MAX_BATCH;   // words of all stretches
+
+__device__ __forceinline__ uint32_t stretch_of(const uint32_t *s_off, uint32_t n, uint32_t e)
+{
+    uint32_t pos = 0;   // largest p with s_off[p] <= e (offsets ascend, s_off[0] = 0)
+#pragma unroll
+    for (uint32_t step = ZEN_MAX_BATCH; step; step >>= 1) {
+        const uint32_t q = pos + step;
+        if (q <= n && s_off[q] <= e) pos = q;
+    }
+    return pos;
+}
+
 __global__ void __launch_bounds__(PULL_THREADS)
 pull_tile_place_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *base,
                        uint32_t n_parts, const uint32_t *cnt, uint32_t n_tiles, uint64_t n_rows, float *dense,
                        uint32_t direct)
 {
     __shared__ float s_out[PULL_TILE_ROWS];
-    constexpr uint32_t GROUPS = PULL_THREADS / G;
-    constexpr uint64_t GMASK = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
-    const uint32_t tile = blockIdx.x, grp = threadIdx.x / G, gl = threadIdx.x % G;
-    const uint32_t gshift = (lane_id() / G) * G;
+    __shared__ uint32_t s_b0[ZEN_MAX_BATCH], s_kb[ZEN_MAX_BATCH], s_cn[ZEN_MAX_BATCH], s_d0[ZEN_MAX_BATCH];
+    __shared__ uint32_t s_eoff[ZEN_MAX_BATCH + 1], s_woff[ZEN_MAX_BATCH + 1];
+    __shared__ const float *s_vals[ZEN_MAX_BATCH];
+    __shared__ const uint32_t *s_bm[ZEN_MAX_BATCH];
+    __shared__ uint32_t s_w[PULL_TILE_WORDS], s_wpre[PULL_TILE_WORDS], s_tmp[32];
+    const uint32_t tile = blockIdx.x;
     const uint64_t row0 = (uint64_t)tile * PULL_TILE_ROWS;
-    if (!direct && a.n < n_parts) {   // rows of partitions outside this launch group: zero for now
-        for (uint32_t i = threadIdx.x; i < PULL_TILE_ROWS; i += PULL_THREADS) s_out[i] = 0.f;
-        __syncthreads();
-    }
-    for (uint32_t s0 = 0; s0 < a.n; s0 += GROUPS) {
-        const uint32_t server = s0 + grp;
-        uint32_t b0 = 0, b1 = 0, kbase = 0, count = 0;
-        const uint32_t *__restrict__ bm = nullptr, *__restrict__ dom = nullptr;
-        const float *__restrict__ vals = nullptr;
-        if (server < a.n) {
-            const uint32_t p = a.first_part + server;
-            b0 = base[(uint64_t)tile * n_parts + p];
-            b1 = base[(uint64_t)(tile + 1) * n_parts + p];
-            bm = a.indices[server] ? nullptr : a.bitmap[server];
-            dom = domain + dom_offsets[p];
-            vals = a.values[server];
-            kbase = cnt[(uint64_t)server * (n_tiles + 1) + tile];
-            count = *a.count[server];
+    if (threadIdx.x < ZEN_WAVE) {   // wave 0: one lane per partition of the launch group
+        const uint32_t sv = threadIdx.x;
+        uint32_t len = 0, nw = 0;
+        if (sv < a.n) {
+            const uint32_t p = a.first_part + sv;
+            const uint32_t b0 = base[(uint64_t)tile * n_parts + p], b1 = base[(uint64_t)(tile + 1) * n_parts + p];
+            len = b1 - b0;
+            nw = len ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0u;
+            s_b0[sv] = b0;
+            s_kb[sv] = cnt[(uint64_t)sv * (n_tiles + 1) + tile];
+            s_cn[sv] = *a.count[sv];
+            s_d0[sv] = dom_offsets[p];
+            s_vals[sv] = a.values[sv];
+            s_bm[sv] = a.indices[sv] ? nullptr : a.bitmap[sv];
         }
-        uint32_t run = 0;
-        for (uint32_t jb = b0; ballot(jb < b1) != 0; jb += G) {   // uniform per wave: until every group is done
-            const uint32_t j = jb + gl;
-            const bool valid = j < b1;
-            const uint32_t word = (valid && bm) ? bm[j >> 5] : 0u;
-            const bool bit = valid && ((word >> (j & 31u)) & 1u);
-            const uint64_t gbits = (ballot(bit) >> gshift) & GMASK;
-            const uint32_t k = kbase + run + (uint32_t)__popcll(gbits & ((1ull << gl) - 1ull));
-            run += (uint32_t)__popcll(gbits);
-            if (valid) {
-                const uint32_t row = dom[j];
-                const bool take = bit && k < count;
-                const float v = take ? vals[k] : 0.f;
-                if (!direct) s_out[row - row0] = v;
-                else if (take) dense[row] = v;
-            }
+        const uint32_t e_inc = wave_inclusive_scan(len), w_inc = wave_inclusive_scan(nw);
+        if (sv == 0) { s_eoff[0] = 0; s_woff[0] = 0; }
+        if (sv < a.n) { s_eoff[sv + 1] = e_inc; s_woff[sv + 1] = w_inc; }
+    }
+    if (!direct && a.n < n_parts)   // rows of partitions outside this launch group: zero for now
+        for (uint32_t i = threadIdx.x; i < PULL_TILE_ROWS; i += PULL_THREADS) s_out[i] = 0.f;
+    __syncthreads();
+    const uint32_t total_e = s_eoff[a.n], total_w = s_woff[a.n];   // <= PULL_TILE_ROWS, <= PULL_TILE_WORDS
+
+    uint32_t run = 0;
+    for (uint32_t w0 = 0; w0 < total_w; w0 += PULL_THREADS) {   // uniform trip count
+        const uint32_t w = w0 + threadIdx.x;
+        uint32_t word = 0;
+        if (w < total_w) {
+            const uint32_t sv = stretch_of(s_woff, a.n, w);
+            const uint32_t b0 = s_b0[sv], b1 = b0 + (s_eoff[sv + 1] - s_eoff[sv]);
+            const uint32_t wi = (b0 >> 5) + (w - s_woff[sv]);
+            const uint32_t *__restrict__ bm = s_bm[sv];
+            word = bm ? bm[wi] : 0u;
+            if (wi == (b0 >> 5)) word &= 0xFFFFFFFFu << (b0 & 31u);
+            if (wi == ((b1 - 1) >> 5) && (b1 & 31u)) word &= (1u << (b1 & 31u)) - 1u;
+            s_w[w] = word;
+        }
+        uint32_t total;
+        const uint32_t pre = block_exclusive_scan(__popc(word), s_tmp, &total);
+        if (w < total_w) s_wpre[w] = run + pre;
+        run += total;
+    }
+    __syncthreads();
+
+    // Batches of 8 rows per thread: all positions first (LDS only), then 16 independent global loads.
+    for (uint32_t e0 = 0; e0 < total_e; e0 += PULL_THREADS * 8) {
+        uint32_t sv[8], k[8], row[8];
+        float v[8];
+        bool take[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t e = e0 + u * PULL_THREADS + threadIdx.x;
+            sv[u] = stretch_of(s_eoff, a.n, e < total_e ? e : 0u);
+            const uint32_t b0 = s_b0[sv[u]], j = b0 + (e - s_eoff[sv[u]]);
+            const uint32_t wq0 = s_woff[sv[u]], wq = wq0 + (j >> 5) - (b0 >> 5);
+            const uint32_t word = e < total_e ? s_w[wq] : 0u;
+            const bool bit = (word >> (j & 31u)) & 1u;
+            k[u] = s_kb[sv[u]] + (s_wpre[e < total_e ? wq : 0u] - s_wpre[wq0]) + __popc(word & ((1u << (j & 31u)) - 1u));
+            take[u] = bit && k[u] < s_cn[sv[u]];
+            row[u] = s_d0[sv[u]] + j;   // position in the domain table for now
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t e = e0 + u * PULL_THREADS + threadIdx.x;
+            row[u] = e < total_e ? domain[row[u]] : 0u;
+            v[u] = take[u] ? s_vals[sv[u]][k[u]] : 0.f;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t e = e0 + u * PULL_THREADS + threadIdx.x;
+            if (e >= total_e) continue;
+            if (!direct) s_out[row[u] - row0] = v[u];
+            else if (take[u]) dense[row[u]] = v[u];
         }
     }
     if (direct) return;
@@ -470,12 +562,18 @@ hipError_t build_pull_tables(zen_ctx *ctx, hipStream_t s)
 }
 
 static hipError_t launch_pull_encode(zen_ctx *ctx, const PullSrc &src, const Arr64<uint64_t> &caps,
-                                     const Arr64<uint32_t *> &out_words, zen_status_info *status, hipStream_t s)
+                                     const Arr64<uint32_t *> &out_words, char *ws, zen_status_info *status,
+                                     hipStream_t s)
 {
     const PullLayout L = pull_layout(ctx);
+    uint32_t *bounds = (uint32_t *)(ws + L.cnt_off);
+    const uint32_t n_chunks = (uint32_t)L.n_chunks;
     ProfScope prof(ctx, K_PULL_ENCODE, s);
-    pull_encode_kernel<<<dim3((uint32_t)L.n_chunks, src.n), PULL_THREADS, 0, s>>>(
-        src, caps, out_words, ctx->d_domain, ctx->d_dom_offsets, status);
+    pull_bounds_kernel<<<dim3(n_chunks / (PULL_THREADS / ZEN_WAVE) + 1, src.n), PULL_THREADS, 0, s>>>(
+        src, caps, ctx->d_domain, ctx->d_dom_offsets, bounds, n_chunks);
+    ZEN_LAUNCH_CHECK();
+    pull_encode_kernel<<<dim3(n_chunks, src.n), PULL_THREADS, 0, s>>>(
+        src, caps, out_words, ctx->d_domain, ctx->d_dom_offsets, bounds, n_chunks, status);
     return hipGetLastError();
 }
 
@@ -531,17 +629,10 @@ static hipError_t launch_pull_tiles(zen_ctx *ctx, const PullSrc &src, char *ws, 
         ZEN_LAUNCH_CHECK();
     }
     {
-        const uint64_t per = PULL_TILE_ROWS / g.n_parts;   // expected rows of one partition in a tile
         ProfScope prof(ctx, K_PULL_PLACE, s);
-#define ZEN_TILE_PLACE(G_)                                                                                     \
-    pull_tile_place_kernel<G_><<<n_tiles, PULL_THREADS, 0, s>>>(src, ctx->d_domain, ctx->d_dom_offsets,            \
-                                                                ctx->d_pull_base, g.n_parts, cnt, n_tiles, g.n_rows, \
-                                                                dense, direct ? 1u : 0u)
-        if (per > 32) ZEN_TILE_PLACE(64);
-        else if (per > 16) ZEN_TILE_PLACE(32);
-        else if (per > 8) ZEN_TILE_PLACE(16);
-        else ZEN_TILE_PLACE(8);
-#undef ZEN_TILE_PLACE
+        pull_tile_place_kernel<<<n_tiles, PULL_THREADS, 0, s>>>(src, ctx->d_domain, ctx->d_dom_offsets,
+                                                                ctx->d_pull_base, g.n_parts, cnt, n_tiles, g.n_rows,
+                                                                dense, direct ? 1u : 0u);
         ZEN_LAUNCH_CHECK();
     }
     return hipSuccess;
@@ -594,7 +685,7 @@ zen_status zen_pull_encode_batch(zen_ctx *ctx, const zen_aggregated *host_aggs, 
             caps.v[i] = host_aggs[j0 + i].cap_rows;
             words.v[i] = bitmap + ctx->h_bm_word_off[j0 + i];
         }
-        HIP_TRY(launch_pull_encode(ctx, src, caps, words, status, s));
+        HIP_TRY(launch_pull_encode(ctx, src, caps, words, (char *)workspace, status, s));
     }
     return ZEN_OK;
 }
@@ -624,7 +715,7 @@ zen_status zen_pull_encode(zen_ctx *ctx, const uint32_t *indices, const uint32_t
     src.count[0] = count;
     caps.v[0] = cap_rows;
     words.v[0] = bitmap_words;
-    HIP_TRY(launch_pull_encode(ctx, src, caps, words, status, s));
+    HIP_TRY(launch_pull_encode(ctx, src, caps, words, (char *)workspace, status, s));
     return ZEN_OK;
 }
 
@@ -684,9 +775,12 @@ zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense
     } else {
         uint64_t blocks = ((n_elems >> 2) + PULL_THREADS * 4 - 1) / (PULL_THREADS * 4);
         if (blocks < 1) blocks = 1;
-        if (blocks > 16384) blocks = 16384;
+        static const int nt = getenv("ZEN_PULL_ZERO_NT") ? atoi(getenv("ZEN_PULL_ZERO_NT")) : 1;   // tuning knobs
+        static const long cap = getenv("ZEN_PULL_ZERO_BLOCKS") ? atol(getenv("ZEN_PULL_ZERO_BLOCKS")) : (1 << 20);
+        if (blocks > (uint64_t)cap && cap > 0) blocks = (uint64_t)cap;
         ProfScope prof(ctx, K_PULL_ZERO, s);
-        pull_zero_kernel<<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);
+        if (nt) pull_zero_kernel<true><<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);
+        else pull_zero_kernel<false><<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);
         HIP_TRY(hipGetLastError());
     }
     uint32_t *dec = (uint32_t *)(ws + L.dec_off);
