@@ -62,6 +62,8 @@ EncodeLayout encode_layout(const Geometry &g, uint32_t batch)
     L.hist_off = off; off += L.hist_stride * batch;
     L.flag_stride = align_up((uint64_t)g.n_tiles * 4, 256);
     L.flag_off = off; off += L.flag_stride * batch;
+    L.list_stride = align_up(((uint64_t)g.n_tiles + 1) * 4, 256);
+    L.list_off = off; off += L.list_stride * batch;
     L.total = off;
     return L;
 }
@@ -124,7 +126,7 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
         ok = ok && hipMalloc(&ctx->d_dom_offsets, (n + 1) * 4) == hipSuccess;
         ok = ok && hipMalloc(&ctx->d_bm_word_off, (n + 1) * 4) == hipSuccess;
         ok = ok && hipMalloc(&ctx->d_dom_tile_base, ((uint64_t)g.n_tiles + 1) * n * 4) == hipSuccess;
-        ok = ok && hipMalloc(&tmp_mask, ((uint64_t)g.n_tiles * g.tile_words + g.n_tiles) * 4) == hipSuccess;   // mask + tile flags
+        ok = ok && hipMalloc(&tmp_mask, ((uint64_t)g.n_tiles * g.tile_words + 2 * (uint64_t)g.n_tiles + 1) * 4) == hipSuccess;   // mask + tile flags + tile list
         ok = ok && hipMalloc(&tmp_status, 256) == hipSuccess;
         zen_status st = ok ? ZEN_OK : ZEN_ERR_NOMEM;
         if (ok) {

@@ -253,7 +253,8 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(SCAN_THREADS)
 partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_t hist_stride_words,
-                      const uint32_t *tflag_base, uint64_t tflag_stride, zen_status_info *status)
+                      const uint32_t *tflag_base, uint64_t tflag_stride, uint32_t *tlist_base, uint64_t tlist_stride,
+                      zen_status_info *status)
 {
     __shared__ uint32_t s_part[SCAN_THREADS];   // [grp][p] partial sums
     __shared__ uint32_t s_off[ZEN_MAX_PARTS + 1];
@@ -311,6 +312,21 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
             run += h;
         }
     }
+    // For the scatter of element-level inputs: ascending list of the worker's non-empty tiles (all
+    // tiles when the input carries no tile flags), its length behind it.
+    if (tlist_base) {
+        uint32_t *tlist = tlist_base + worker * tlist_stride;
+        uint32_t listed = 0;
+        for (uint32_t t0b = 0; t0b < g.n_tiles; t0b += blockDim.x) {
+            const uint32_t t = t0b + threadIdx.x;
+            const uint32_t f = (t < g.n_tiles && (!g.sparse_mask || tflag[t])) ? 1u : 0u;
+            uint32_t total;
+            const uint32_t pre = block_exclusive_scan(f, s_tmp, &total);
+            if (f) tlist[listed + pre] = t;
+            listed += total;
+        }
+        if (threadIdx.x == 0) tlist[g.n_tiles] = listed;
+    }
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -336,7 +352,7 @@ template <bool ELEM>
 __global__ void __launch_bounds__(SCATTER_THREADS)
 scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
-               const uint32_t *tflag_base, uint64_t tflag_stride, BitmapTables bt)
+               const uint32_t *tlist_base, uint64_t tlist_stride, BitmapTables bt)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t n = g.n_parts, D = g.row_dim;
@@ -344,9 +360,11 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     const uint32_t n_waves = blockDim.x >> 6;
     uint32_t *s_cnt = s_run + n;                     // [n_waves][n]
     uint32_t *s_list = s_cnt + n_waves * n;                // [SEG_ROWS] row ids of the segment, ascending
-    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row
-    uint32_t *s_tmp = s_pos + SEG_ROWS;              // [32]
-    uint32_t *s_b0 = s_tmp + 32;                     // bitmap only: [n] first bit of (tile, p)
+    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row (row copies only)
+    uint32_t *s_tmp = s_pos + (ELEM ? 0 : SEG_ROWS); // [32]
+    uint32_t *s_mask = s_tmp + 32;                   // [tile_words] the tile's mask
+    uint32_t *s_seg = s_mask + g.tile_words;         // [ceil(tile_words / SEG_WORDS)] 1 = the segment holds rows
+    uint32_t *s_b0 = s_seg + (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;   // bitmap only: [n] first bit of (tile, p)
     uint32_t *s_b1 = s_b0 + n;                       //              [n] end bit of (tile, p)
     uint32_t *s_boff = s_b1 + n;                     //              [n+1] LDS word offset of p's range
     uint32_t *s_bm = s_boff + n + 1;                 //              [tile_words + 2n] assembled words
@@ -360,13 +378,65 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 
     for (uint32_t i = threadIdx.x; i < n_waves * n; i += blockDim.x) s_cnt[i] = 0;
 
-    for (uint32_t tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
-        const uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
-        if (ELEM) {   // element-level inputs carry per-tile flags (sparse_mask)
-            const uint32_t flag = tflag_base[worker * tflag_stride + tile];
+    // Tiles to visit: element-level inputs come with the ascending list of their non-empty tiles (empty
+    // ones have no mask words at all); the mask of the next tile is fetched into registers while the
+    // current one is processed, its id one visit earlier still.  Otherwise every tile is visited and
+    // tested (tiles of wide rows have a handful of mask words).
+    const uint32_t *tlist = ELEM ? tlist_base + worker * tlist_stride : nullptr;
+    const uint32_t n_visit = ELEM ? min(tlist[g.n_tiles], g.n_tiles) : g.n_tiles;
+    const uint32_t *wmask = mask_base + worker * mask_stride_words;
+    const bool pf_ok = g.tile_words <= 8 * SCATTER_THREADS;   // 8 registers per thread hold a tile's mask
+    uint32_t mw[8];
+#pragma unroll
+    for (uint32_t q = 0; q < 8; ++q) mw[q] = 0;
+    uint32_t k = blockIdx.x;
+    uint32_t nxt_tile = k < n_visit ? (ELEM ? min(tlist[k], g.n_tiles - 1) : k) : 0u;
+    uint32_t nxt2_tile = (ELEM && k + gridDim.x < n_visit) ? min(tlist[k + gridDim.x], g.n_tiles - 1) : 0u;
+    if (ELEM && pf_ok && k < n_visit) {
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) {
+            const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+            if (i < g.tile_words) mw[q] = wmask[(uint64_t)nxt_tile * g.tile_words + i];
+        }
+    }
+    for (; k < n_visit; k += gridDim.x) {
+        const uint32_t tile = nxt_tile;
+        const uint32_t *gmask = wmask + (uint64_t)tile * g.tile_words;
+        if (ELEM) {
             __syncthreads();                                   // the barrier between tiles
-            if (!flag) continue;                               // empty tile: its mask words were never written
+            // The tile's mask goes to LDS with a flag per 64-word segment, so that empty segments cost
+            // neither a memory access nor a barrier.
+            for (uint32_t q0 = 0; q0 * SCATTER_THREADS < g.tile_words; q0 += 8) {
+                if (!pf_ok) {
+#pragma unroll
+                    for (uint32_t q = 0; q < 8; ++q) {
+                        const uint32_t i = (q0 + q) * SCATTER_THREADS + threadIdx.x;
+                        mw[q] = i < g.tile_words ? gmask[i] : 0u;
+                    }
+                }
+#pragma unroll
+                for (uint32_t q = 0; q < 8; ++q) {
+                    const uint32_t i = (q0 + q) * SCATTER_THREADS + threadIdx.x;
+                    const uint32_t first = i - lane_id();      // the wave's 64 words are one segment
+                    if (first >= g.tile_words) continue;       // uniform per wave
+                    if (i < g.tile_words) s_mask[i] = mw[q];
+                    const bool seg_any = ballot(mw[q] != 0) != 0;
+                    if (lane_id() == 0) s_seg[first / SEG_WORDS] = seg_any;
+                }
+            }
+            nxt_tile = nxt2_tile;
+            const uint32_t k2 = k + 2 * gridDim.x;
+            nxt2_tile = k2 < n_visit ? min(tlist[k2], g.n_tiles - 1) : 0u;
+            if (pf_ok && k + gridDim.x < n_visit) {
+#pragma unroll
+                for (uint32_t q = 0; q < 8; ++q) {
+                    const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                    mw[q] = i < g.tile_words ? wmask[(uint64_t)nxt_tile * g.tile_words + i] : 0u;
+                }
+            }
+            __syncthreads();
         } else {
+            nxt_tile = k + gridDim.x;
             uint32_t any = 0;
             for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= gmask[i];
             if (!__syncthreads_or((int)(any != 0))) continue;  // empty tile (also the barrier between tiles)
@@ -401,8 +471,10 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 
         for (uint32_t w0 = 0; w0 < g.tile_words; w0 += SEG_WORDS) {
             // (a) expand up to 64 mask words into the ascending row list
+            if (ELEM && !s_seg[w0 / SEG_WORDS]) continue;   // uniform
             uint32_t word = 0;
-            if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words) word = gmask[w0 + threadIdx.x];
+            if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words)
+                word = ELEM ? s_mask[w0 + threadIdx.x] : gmask[w0 + threadIdx.x];
             uint32_t total;
             const uint32_t pre = block_exclusive_scan(threadIdx.x < SEG_WORDS ? __popc(word) : 0u, s_tmp, &total);
             if (total == 0) continue;   // uniform: total comes from LDS
@@ -449,8 +521,8 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     if (pos < cap) {
                         if (out_idx) out_idx[pos] = row;
                         if (ELEM && out_val) out_val[pos] = pf_val[q];
-                        s_pos[i] = pos;
-                    } else {
+                        if (!ELEM) s_pos[i] = pos;
+                    } else if (!ELEM) {
                         s_pos[i] = 0xFFFFFFFFu;
                     }
                     if (bitmap) {
@@ -680,7 +752,9 @@ hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t
     ProfScope prof(ctx, K_PARTITION_SCAN, s);
     partition_scan_kernel<<<batch, SCAN_THREADS, 0, s>>>(g, outs, (uint32_t *)(ws + L.hist_off),
                                                          L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
-                                                         L.flag_stride / 4, (zen_status_info *)(ws + L.status_off));
+                                                         L.flag_stride / 4,
+                                                         g.row_dim == 1 ? (uint32_t *)(ws + L.list_off) : nullptr,
+                                                         L.list_stride / 4, (zen_status_info *)(ws + L.status_off));
     return hipGetLastError();
 }
 
@@ -712,13 +786,20 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
     }
     ProfScope prof(ctx, K_SCATTER, s);
     const uint32_t threads = scatter_threads(g);
-    size_t words = (1 + threads / 64) * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
+    size_t words = (1 + threads / 64) * (size_t)g.n_parts + (g.row_dim == 1 ? 1 : 2) * SEG_ROWS + 32 + g.tile_words +
+                   (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;
     if (g.bitmap) words += 3 * (size_t)g.n_parts + 1 + g.tile_words + 2 * (size_t)g.n_parts;
+    if (words * 4 > 160 * 1024) return hipErrorInvalidValue;
+    if (words * 4 > 48 * 1024) {   // beyond the default dynamic LDS limit
+        (void)hipFuncSetAttribute((const void *)scatter_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipFuncSetAttribute((const void *)scatter_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipGetLastError();
+    }
     if (g.row_dim == 1)
         scatter_kernel<true><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
             g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
-            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
-            L.flag_stride / 4, bt);
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.list_off),
+            L.list_stride / 4, bt);
     else
         scatter_kernel<false><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
             g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
@@ -1011,14 +1092,20 @@ hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info
     outs.offsets[0] = ctx->d_dom_offsets;
     outs.indices[0] = ctx->d_domain;
     outs.cap_rows[0] = g.n_rows;
-    partition_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(g, outs, ctx->d_dom_tile_base, 0, tflag, 0, tmp_status);
+    uint32_t *tlist = tflag + g.n_tiles;    // ... and n_tiles + 1 list words behind the flags
+    partition_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(g, outs, ctx->d_dom_tile_base, 0, tflag, 0, tlist, 0, tmp_status);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     GradPtrs grads;
     memset(&grads, 0, sizeof(grads));
     BitmapTables bt{nullptr, nullptr, nullptr};
-    const size_t words = 5 * (size_t)g.n_parts + 2 * SEG_ROWS + 32;
+    const size_t words = 5 * (size_t)g.n_parts + SEG_ROWS + 32 + g.tile_words + (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;
+    if (words * 4 > 160 * 1024) return hipErrorInvalidValue;
+    if (words * 4 > 48 * 1024) {
+        (void)hipFuncSetAttribute((const void *)scatter_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipGetLastError();
+    }
     scatter_kernel<true><<<dim3(scatter_grid_x(g, 1), 1), SCATTER_THREADS, words * 4, s>>>(
-        g, grads, outs, tmp_mask, 0, ctx->d_dom_tile_base, 0, tflag, 0, bt);
+        g, grads, outs, tmp_mask, 0, ctx->d_dom_tile_base, 0, tlist, 0, bt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     domain_rank_kernel<<<4096, 256, 0, s>>>(g, ctx->d_domain, ctx->d_dom_offsets, ctx->d_rank);
     if ((e = hipGetLastError()) != hipSuccess) return e;

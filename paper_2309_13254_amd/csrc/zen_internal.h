@@ -38,6 +38,8 @@ struct EncodeLayout {
     uint64_t hist_stride;
     uint64_t flag_off;       // per worker: n_tiles u32, 1 = the tile has a non-zero row (its mask words and
     uint64_t flag_stride;    //             histogram row exist), 0 = empty tile (nothing else was written)
+    uint64_t list_off;       // per worker: n_tiles + 1 u32, ascending ids of the flagged tiles, then their number
+    uint64_t list_stride;
     uint64_t total;
 };
 

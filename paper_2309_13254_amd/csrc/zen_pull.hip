@@ -128,18 +128,18 @@ pull_encode_kernel(PullSrc a, Arr64<uint64_t> cap_rows, Arr64<uint32_t *> out_wo
     const bool bad = k1 < k0 || k1 - k0 > PULL_CHUNK_BITS;   // out of order / more indices than domain rows
     const uint32_t m_all = k1 < k0 ? 0u : k1 - k0;
     const uint32_t m = min(m_all, PULL_CHUNK_BITS);
-    // Both lists go to LDS; loads are issued in batches of 8 per list so that 16 are in flight per thread.
+    // Both lists go to LDS; loads are issued in batches of 16 per list so that 32 are in flight per thread.
     const uint32_t n_here_all = j1 - j0;
-    for (uint32_t t0 = 0; t0 < PULL_CHUNK_BITS / PULL_THREADS; t0 += 8) {
-        uint32_t rd[8], ri[8];
+    for (uint32_t t0 = 0; t0 < PULL_CHUNK_BITS / PULL_THREADS; t0 += 16) {
+        uint32_t rd[16], ri[16];
 #pragma unroll
-        for (uint32_t u = 0; u < 8; ++u) {
+        for (uint32_t u = 0; u < 16; ++u) {
             const uint32_t e = (t0 + u) * PULL_THREADS + threadIdx.x;
             rd[u] = e < n_here_all ? dom[j0 + e] : 0u;
             ri[u] = e < m ? idx[k0 + e] : 0u;
         }
 #pragma unroll
-        for (uint32_t u = 0; u < 8; ++u) {
+        for (uint32_t u = 0; u < 16; ++u) {
             const uint32_t e = (t0 + u) * PULL_THREADS + threadIdx.x;
             if (e < n_here_all) s_dom[e + (e >> 5)] = rd[u];
             if (e < m) s_idx[e] = ri[u];
@@ -462,13 +462,13 @@ pull_tile_place_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_of
     }
     __syncthreads();
 
-    // Batches of 8 rows per thread: all positions first (LDS only), then 16 independent global loads.
-    for (uint32_t e0 = 0; e0 < total_e; e0 += PULL_THREADS * 8) {
-        uint32_t sv[8], k[8], row[8];
-        float v[8];
-        bool take[8];
+    // Batches of 16 rows per thread: all positions first (LDS only), then 32 independent global loads.
+    for (uint32_t e0 = 0; e0 < total_e; e0 += PULL_THREADS * 16) {
+        uint32_t sv[16], k[16], row[16];
+        float v[16];
+        bool take[16];
 #pragma unroll
-        for (uint32_t u = 0; u < 8; ++u) {
+        for (uint32_t u = 0; u < 16; ++u) {
             const uint32_t e = e0 + u * PULL_THREADS + threadIdx.x;
             sv[u] = stretch_of(s_eoff, a.n, e < total_e ? e : 0u);
             const uint32_t b0 = s_b0[sv[u]], j = b0 + (e - s_eoff[sv[u]]);
@@ -480,13 +480,13 @@ pull_tile_place_kernel(PullSrc a, const uint32_t *domain, const uint32_t *dom_of
             row[u] = s_d0[sv[u]] + j;   // position in the domain table for now
         }
 #pragma unroll
-        for (uint32_t u = 0; u < 8; ++u) {
+        for (uint32_t u = 0; u < 16; ++u) {
             const uint32_t e = e0 + u * PULL_THREADS + threadIdx.x;
             row[u] = e < total_e ? domain[row[u]] : 0u;
             v[u] = take[u] ? s_vals[sv[u]][k[u]] : 0.f;
         }
 #pragma unroll
-        for (uint32_t u = 0; u < 8; ++u) {
+        for (uint32_t u = 0; u < 16; ++u) {
             const uint32_t e = e0 + u * PULL_THREADS + threadIdx.x;
             if (e >= total_e) continue;
             if (!direct) s_out[row[u] - row0] = v[u];
