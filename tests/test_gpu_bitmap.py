@@ -144,3 +144,57 @@ def test_single_server_bitmap_parts(oracle, zen, mixed, D):
     U, idx, val = G.aggregated_to_host(out)
     assert U == ref.U and np.array_equal(idx, ref.indices)
     G.check_sums(val, ref)
+
+
+@pytest.mark.parametrize("R,n", [(1, 1), (33, 3), (5000, 4), (70001, 64), (300000, 100), (5000, 1024), (1 << 20, 7)])
+def test_elementwise_bitmap_encode_without_index_list(oracle, zen, R, n):
+    """Element-level inputs, hash-bitmap output and no index list: the call the clustered-runs benchmark
+    makes (uniform densities and long unaligned runs of consecutive non-zeros)."""
+    import gpu_util as G
+
+    rng = np.random.default_rng(R + n)
+    wl = Workload("t", 0, R, 1, n, int(rng.integers(0, 2**32)), "uniform")
+    ctx = zen.ZenContext(R, 1, n, wl.hash_seed, zen.ZEN_INDEX_BITMAP)
+    total, woff, _ = zen.zen_bitmap_layout(ctx)
+    owner = oracle.owner_table(R, n, wl.hash_seed)
+    _, word_off = oracle.bitmap_layout(owner, n)
+    hosts, rowsets = [], []
+    for density in (0.0, 0.02, 0.5, 1.0, "runs"):
+        if density == "runs":      # long runs of consecutive non-zeros at unaligned offsets
+            m = np.zeros(R, bool)
+            for start in rng.integers(0, max(R - 1, 1), size=5):
+                m[int(start):int(start) + 4096 + 37] = True
+            rows = np.flatnonzero(m).astype(np.uint32)
+        else:
+            rows = np.flatnonzero(rng.random(R) < density).astype(np.uint32)
+        vals = rng.standard_normal((rows.size, 1)).astype(np.float32) + 4.0
+        hosts.append(dense_from_sparse(wl, rows, vals))
+        rowsets.append(rows)
+    grads = [torch.from_numpy(h).cuda() for h in hosts]
+    encs = [zen.alloc_encoded(ctx, r.size, with_indices=False) for r in rowsets]
+    for e in encs:
+        e.values.fill_(-1.0)
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, len(grads)))
+    zen.zen_encode_batch(ctx, grads, encs, ws)
+    assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+    for h, rows, enc in zip(hosts, rowsets, encs):
+        ref = oracle.encode(h, R, 1, n, wl.hash_seed)
+        assert np.array_equal(G.u32(enc.offsets), ref.offsets)
+        assert np.array_equal(G.u32(enc.bitmap[:total]), oracle.bitmap_encode(owner, n, oracle.member_mask(rows, R), word_off))
+        assert np.array_equal(enc.values[:ref.nnz].cpu().numpy().view(np.uint32), ref.values.view(np.uint32))
+    # capacity smaller than nnz: offsets complete, flag raised, nothing written past the capacity
+    big = max(range(len(rowsets)), key=lambda i: rowsets[i].size)
+    nnz = rowsets[big].size
+    if nnz >= 4:
+        cap = nnz // 2
+        small = zen.alloc_encoded(ctx, nnz, with_indices=False)
+        small.values.fill_(-1.0)
+        small.cap_rows = cap
+        zen.zen_encode_batch(ctx, [grads[big]], [small], ws)
+        st, flags, needed = zen.zen_status_fetch(ctx, ws)
+        assert st == zen.ZEN_ERR_CAPACITY and flags & 1 and needed == nnz
+        ref = oracle.encode(hosts[big], R, 1, n, wl.hash_seed)
+        assert np.array_equal(G.u32(small.offsets), ref.offsets)
+        got = small.values.cpu().numpy()
+        assert np.array_equal(got[:cap].view(np.uint32), ref.values[:cap].view(np.uint32))
+        assert (got[cap:] == -1.0).all()

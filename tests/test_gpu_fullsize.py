@@ -81,6 +81,14 @@ def test_full_size_workload(oracle, cid):
                 dec = oracle.bitmap_decode(owner, p, bm[woff[p]:woff[p + 1]])
                 assert np.array_equal(dec, r_idx[int(r_off[p]):int(r_off[p + 1])])
         del owner
+        # the benchmark passes no index arrays: same offsets, bitmaps and values
+        encs2 = [zen.alloc_encoded(ctx, c, with_indices=False) for c in nnz]
+        zen.zen_encode_batch(ctx, grads, encs2, ws)
+        assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+        for e1, e2, c in zip(encs, encs2, nnz):
+            assert torch.equal(e1.offsets, e2.offsets) and torch.equal(e1.bitmap[:total], e2.bitmap[:total])
+            assert torch.equal(e1.values[:c].view(torch.int32), e2.values[:c].view(torch.int32))
+        del encs2
 
     per_server = np.diff(offs, axis=1).sum(axis=0)
     max_in = int(per_server.max() * 1.05) + 16
