@@ -22,5 +22,7 @@ from .zen_ref import (  # noqa: F401
     member_mask,
     densify,
     pull_apply,
+    hash_slots,
+    hierarchical_hash,
     imbalance,
 )

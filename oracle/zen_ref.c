@@ -361,6 +361,88 @@ int zen_ref_pull_apply(const uint16_t *owner, uint64_t n_rows, uint32_t n, uint3
 }
 
 /*
+ * Algorithm 1 ("Hierarchical Hashing Algorithm") as a mechanism, step by step,
+ * for the indices taken ONE AFTER THE OTHER in the given order (the paper runs
+ * them in parallel; any serial order is one of its possible executions).
+ *
+ *   x      n partitions of r1 + r2 cells, all empty (the paper's zeros; here
+ *          0xFFFFFFFF because row ids start at 0)
+ *   c      n counters, all r1
+ *   for every idx:  p = part[t];  for i = 1..k: q = slot[i-1][t] (in [0, r1));
+ *          if x[p][q] is empty, write idx there and stop;  after k occupied
+ *          cells: q = c[p]++ and x[p][q] = idx (serial memory).
+ *
+ * part[t] = h0(I[t]) and slot[i][t] = h_{i+1}(I[t]) are handed in as tables, so
+ * that a test can inject the collisions of a worked example; zen_ref_hash_slots
+ * fills them with the seeded hash.  The read-after-write check (Technique #4)
+ * guards against two threads writing one cell at the same time; with one index
+ * at a time it never fires and is left out.
+ *
+ * Returns 0, or ZEN_REF_ERR_CAPACITY if some partition's serial memory (r2
+ * cells) overflows -- the paper does not say what happens then; reading taken:
+ * an error, with *needed_r2 = the largest serial count any partition reached.
+ * serial_count[p] = indices of partition p that went to serial memory.
+ */
+int zen_ref_hierarchical_hash(const uint32_t *I, uint64_t nnz, const uint16_t *part, const uint32_t *const *slot,
+                              uint32_t k, uint32_t n, uint64_t r1, uint64_t r2, uint32_t *x,
+                              uint64_t *serial_count, uint64_t *needed_r2)
+{
+    const uint64_t cells = r1 + r2;
+    uint64_t *c = (uint64_t *)malloc((size_t)n * 8);
+    if (!c) return ZEN_REF_ERR_NOMEM;
+    for (uint64_t a = 0; a < (uint64_t)n * cells; ++a) x[a] = 0xffffffffu;
+    for (uint32_t p = 0; p < n; ++p) c[p] = r1;
+    for (uint64_t t = 0; t < nnz; ++t) {
+        const uint32_t p = part[t];
+        if (p >= n) { free(c); return ZEN_REF_ERR_INVALID; }
+        int placed = 0;
+        for (uint32_t i = 0; i < k && !placed; ++i) {
+            const uint64_t q = slot[i][t];
+            if (q >= r1) { free(c); return ZEN_REF_ERR_INVALID; }
+            if (x[p * cells + q] == 0xffffffffu) { x[p * cells + q] = I[t]; placed = 1; }
+        }
+        if (!placed) {
+            const uint64_t q = c[p]++;
+            if (q < cells) x[p * cells + q] = I[t];
+        }
+    }
+    uint64_t worst = 0;
+    for (uint32_t p = 0; p < n; ++p) {
+        if (serial_count) serial_count[p] = c[p] - r1;
+        if (c[p] - r1 > worst) worst = c[p] - r1;
+    }
+    free(c);
+    if (needed_r2) *needed_r2 = worst;
+    return worst > r2 ? ZEN_REF_ERR_CAPACITY : ZEN_REF_OK;
+}
+
+/* slot[t] = h_i(I[t]) = MurmurHash3_x86_32(I[t], seed_i) mod r1 -- the second-level hash functions,
+ * which a worker may choose freely (Technique #3), here the same seeded family as h0. */
+void zen_ref_hash_slots(const uint32_t *I, uint64_t nnz, uint32_t seed_i, uint64_t r1, uint32_t *slot)
+{
+    for (uint64_t t = 0; t < nnz; ++t) slot[t] = (uint32_t)(zen_ref_hash(I[t], seed_i) % r1);
+}
+
+/*
+ * Extraction (Algorithm 1, output loop): indices = nonzero(x[p]) in memory
+ * order for every partition, concatenated partition-major with an exclusive
+ * prefix; the values are then G[indices] (zen_ref_gather).  Returns the number
+ * of indices.
+ */
+int64_t zen_ref_hash_memory_extract(const uint32_t *x, uint32_t n, uint64_t cells, uint32_t *offsets,
+                                    uint32_t *indices)
+{
+    int64_t out = 0;
+    for (uint32_t p = 0; p < n; ++p) {
+        offsets[p] = (uint32_t)out;
+        for (uint64_t q = 0; q < cells; ++q)
+            if (x[p * cells + q] != 0xffffffffu) indices[out++] = x[p * cells + q];
+    }
+    offsets[n] = (uint32_t)out;
+    return out;
+}
+
+/*
  * Imbalance ratio (Definition "The imbalance ratio"): max_j n*|part_j| / total.
  * Push uses one worker's partition sizes; Pull uses the servers' set sizes
  * after aggregation.  Returns 1.0 for an empty input (nothing to balance).

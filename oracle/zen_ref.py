@@ -87,6 +87,13 @@ def lib():
         L.zen_ref_pull_apply.restype = C.c_int
         L.zen_ref_pull_apply.argtypes = [_u16p, C.c_uint64, C.c_uint32, C.c_uint32, _u64p, _u32p,
                                          C.POINTER(_f32p), _u64p, _f32p]
+        L.zen_ref_hierarchical_hash.restype = C.c_int
+        L.zen_ref_hierarchical_hash.argtypes = [_u32p, C.c_uint64, _u16p, C.POINTER(_u32p), C.c_uint32, C.c_uint32,
+                                                C.c_uint64, C.c_uint64, _u32p, _u64p, _u64p]
+        L.zen_ref_hash_slots.restype = None
+        L.zen_ref_hash_slots.argtypes = [_u32p, C.c_uint64, C.c_uint32, C.c_uint64, _u32p]
+        L.zen_ref_hash_memory_extract.restype = C.c_int64
+        L.zen_ref_hash_memory_extract.argtypes = [_u32p, C.c_uint32, C.c_uint64, _u32p, _u32p]
         L.zen_ref_imbalance.restype = C.c_double
         L.zen_ref_imbalance.argtypes = [_u64p, C.c_uint32]
         _lib = L
@@ -276,6 +283,38 @@ def pull_apply(owner, n, row_dim, word_off, bitmap, values):
     if rc != 0:
         raise ValueError("zen_ref_pull_apply: rc=%d" % rc)
     return dense
+
+
+def hash_slots(I, seed_i, r1):
+    I = _c(I, np.uint32).reshape(-1)
+    out = np.empty(I.size, np.uint32)
+    lib().zen_ref_hash_slots(_p(I, _u32p), I.size, int(seed_i) & 0xFFFFFFFF, int(r1), _p(out, _u32p))
+    return out
+
+
+def hierarchical_hash(I, part, slots, n, r1, r2):
+    """Algorithm 1's hash memory for the indices I taken in order.  part: u16[nnz] = h0(I); slots: list
+    of k arrays u32[nnz] = h_1(I) .. h_k(I).  -> SimpleNamespace(rc, x[n, r1+r2], serial_count[n],
+    needed_r2, offsets, indices) with indices = nonzero(x[p]) in memory order."""
+    I = _c(I, np.uint32).reshape(-1)
+    part = _c(part, np.uint16).reshape(-1)
+    slots = [_c(s, np.uint32).reshape(-1) for s in slots]
+    assert part.size == I.size and all(s.size == I.size for s in slots)
+    k = len(slots)
+    cells = int(r1) + int(r2)
+    x = np.empty((int(n), cells), np.uint32)
+    serial = np.zeros(int(n), np.uint64)
+    needed = C.c_uint64(0)
+    slot_arr = (_u32p * max(k, 1))(*[_p(s, _u32p) for s in slots])
+    rc = lib().zen_ref_hierarchical_hash(_p(I, _u32p), I.size, _p(part, _u16p), slot_arr, k, int(n), int(r1),
+                                         int(r2), _p(x, _u32p), _p(serial, _u64p), C.byref(needed))
+    offsets = np.zeros(int(n) + 1, np.uint32)
+    indices = np.empty(I.size, np.uint32)
+    cnt = 0
+    if rc == 0:
+        cnt = int(lib().zen_ref_hash_memory_extract(_p(x, _u32p), int(n), cells, _p(offsets, _u32p), _p(indices, _u32p)))
+    return SimpleNamespace(rc=rc, x=x, serial_count=serial, needed_r2=int(needed.value), offsets=offsets,
+                           indices=indices[:cnt])
 
 
 def imbalance(sizes):

@@ -68,3 +68,23 @@ def densify(parts, n_rows, row_dim):
         for k, r in enumerate(idx):
             out[int(r)] = np.asarray(val[k], np.float32)
     return out
+
+
+def hier_hash(I, part, slots, n, r1, r2):
+    """Algorithm 1's hash memory with Python lists, indices taken in order.  -> (memory as list of
+    lists with None for empty cells, serial counts)."""
+    mem = [[None] * (r1 + r2) for _ in range(n)]
+    counter = [r1] * n
+    for t, idx in enumerate(I):
+        p = int(part[t])
+        for h in slots:
+            q = int(h[t])
+            if mem[p][q] is None:
+                mem[p][q] = int(idx)
+                break
+        else:
+            q = counter[p]
+            counter[p] += 1
+            if q < r1 + r2:
+                mem[p][q] = int(idx)
+    return mem, [c - r1 for c in counter]

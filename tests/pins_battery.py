@@ -100,6 +100,24 @@ def battery(oracle):
         raise AssertionError("count mismatch accepted")
     except ValueError:
         pass
+    # Algorithm 1's hash memory: the figure's example (first location taken, re-hash to the fourth, taken
+    # too, serial cell right behind the parallel memory), brute force, losslessness
+    hh = oracle.hierarchical_hash(np.array([10, 20, 30], np.uint32), [1, 1, 1], [[0, 3, 0], [2, 2, 3]], 2, 4, 2)
+    assert hh.rc == 0 and hh.x[1].tolist() == [10, 0xFFFFFFFF, 0xFFFFFFFF, 20, 30, 0xFFFFFFFF]
+    assert hh.serial_count.tolist() == [0, 1] and hh.indices.tolist() == [10, 20, 30] and hh.offsets.tolist() == [0, 0, 3]
+    Ih = np.flatnonzero(rng.random(3000) < 0.3).astype(np.uint32)
+    ph = (oracle.hash_many(Ih, 5) % np.uint32(4)).astype(np.uint16)
+    r1h = Ih.size // 4 // 2 + 1
+    sl = [oracle.hash_slots(Ih, 100 + i, r1h) for i in range(3)]
+    assert np.array_equal(sl[0], oracle.hash_many(Ih, 100) % np.uint32(r1h))
+    hh = oracle.hierarchical_hash(Ih, ph, sl, 4, r1h, Ih.size)
+    mem, ser = brute.hier_hash(Ih, ph, sl, 4, r1h, Ih.size)
+    assert hh.rc == 0 and hh.serial_count.tolist() == ser
+    assert all([None if v == 0xFFFFFFFF else int(v) for v in hh.x[q]] == mem[q] for q in range(4))
+    offh, idxh = oracle.partition(Ih, ph, 4)
+    assert np.array_equal(hh.offsets, offh)
+    assert all(np.array_equal(np.sort(hh.indices[offh[q]:offh[q + 1]]), idxh[offh[q]:offh[q + 1]]) for q in range(4))
+    assert oracle.hierarchical_hash(np.arange(9, dtype=np.uint32), [0] * 9, [[0] * 9], 1, 2, 7).rc == 2
     # imbalance-ratio example of section "Balance dimension"
     assert abs(oracle.imbalance([1, 4, 1]) - 2.0) < 1e-12
 

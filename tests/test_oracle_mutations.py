@@ -54,6 +54,17 @@ MUTANTS = [
     ("pull apply: value of the next set bit", "val[p] + (uint64_t)i * row_dim, (size_t)row_dim * 4);",
      "val[p] + (uint64_t)(i + 1 < k ? i + 1 : i) * row_dim, (size_t)row_dim * 4);"),
     ("pull apply: count not checked", "if ((uint64_t)k != counts[p]) { free(idx); return ZEN_REF_ERR_INVALID; }", ""),
+    ("hash memory: serial counter starts at 0", "for (uint32_t p = 0; p < n; ++p) c[p] = r1;", "for (uint32_t p = 0; p < n; ++p) c[p] = 0;"),
+    ("hash memory: occupied cell overwritten", "if (x[p * cells + q] == 0xffffffffu) { x[p * cells + q] = I[t]; placed = 1; }",
+     "{ x[p * cells + q] = I[t]; placed = 1; }"),
+    ("hash memory: only the first hash function tried", "for (uint32_t i = 0; i < k && !placed; ++i) {\n            const uint64_t q = slot[i][t];",
+     "for (uint32_t i = 0; i < 1 && !placed; ++i) {\n            const uint64_t q = slot[i][t];"),
+    ("hash memory: partition ignored", "const uint32_t p = part[t];\n        if (p >= n) { free(c); return ZEN_REF_ERR_INVALID; }\n        int placed = 0;",
+     "const uint32_t p = 0;\n        int placed = 0;"),
+    ("hash memory: overflow not reported", "return worst > r2 ? ZEN_REF_ERR_CAPACITY : ZEN_REF_OK;", "return ZEN_REF_OK;"),
+    ("hash slots: seed ignored", "(uint32_t)(zen_ref_hash(I[t], seed_i) % r1);", "(uint32_t)(zen_ref_hash(I[t], 0) % r1);"),
+    ("extract: a cell skipped", "for (uint64_t q = 0; q < cells; ++q)\n            if (x[p * cells + q] != 0xffffffffu)",
+     "for (uint64_t q = 1; q < cells; ++q)\n            if (x[p * cells + q] != 0xffffffffu)"),
     ("imbalance: factor n missing", "return (double)n * (double)mx / (double)total;", "return (double)mx / (double)total;"),
 ]
 
