@@ -211,6 +211,41 @@ zen_status zen_pull_decode(zen_ctx *ctx, const uint32_t *bitmap_words, uint32_t 
 zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense, void *workspace,
                           uint64_t workspace_bytes, void *hip_stream);
 
+/*
+ * ---- Algorithm 1 as the paper runs it: the hash memory ---------------------------------------
+ *
+ * zen_encode computes Algorithm 1's RESULT with a histogram, a scan and a stable scatter.
+ * zen_encode_hashed computes the same partitions with the algorithm's own mechanism [Algorithm 1,
+ * Techniques #1-#4]: a memory of n_parts partitions, each with r1 cells of parallel memory and r2 of
+ * serial memory; an index goes to partition h0(idx), tries the cells h_1(idx) .. h_k(idx) of the
+ * parallel memory and, if all are taken, is appended to the serial memory through an atomic
+ * counter; each partition is then extracted (nonzero) and its values gathered.
+ *   h_i(idx) = MurmurHash3_x86_32(idx, level2_seed + i) mod r1 -- second-level functions are a
+ *   worker's own choice (Technique #3); h0 is the context's.
+ *   A cell is claimed with one compare-and-swap, which decides in one step what the listing's test,
+ *   store and read-back (Technique #4) decide in three.
+ * Output: host_out->offsets / indices / values as zen_encode writes them, except that inside a
+ * partition the indices come in memory order (the paper: "random order ... no need to sort"); which
+ * index wins a contested cell depends on timing, so only the SET per partition is reproducible.
+ * serial_counts (device, [n_parts], may be NULL): indices of each partition that went to serial memory.
+ * Errors through the workspace status: bit 0 = nnz > cap_rows (needed_rows = nnz); bit 1 = some
+ * partition's serial memory overflowed and indices were dropped (needed_rows = the r2 that would
+ * have sufficed).  hash_memory: zen_hash_memory_bytes, 256-byte aligned, overwritten.
+ */
+typedef struct {
+    uint32_t k;           /* second-level hash functions, 1..8 (the paper uses 3) */
+    uint32_t level2_seed; /* seeds of h_1..h_k are level2_seed + 1 .. level2_seed + k */
+    uint64_t r1;          /* parallel cells per partition, >= 1 (the paper: 2|G|d_G over all partitions) */
+    uint64_t r2;          /* serial cells per partition (the paper: r1 / 10) */
+} zen_hash_params;
+
+zen_status zen_hash_memory_bytes(const zen_ctx *ctx, const zen_hash_params *host_params, uint64_t *host_bytes);
+zen_status zen_encode_hashed_workspace_bytes(const zen_ctx *ctx, const zen_hash_params *host_params,
+                                             uint64_t *host_bytes);
+zen_status zen_encode_hashed(zen_ctx *ctx, const float *grad, const zen_hash_params *host_params, void *hash_memory,
+                             uint64_t hash_memory_bytes, const zen_encoded *host_out, uint32_t *serial_counts,
+                             void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
 /* Synchronous: waits for the stream, reads the status block of a workspace last used by an encode
  * or aggregate call, returns ZEN_OK / ZEN_ERR_CAPACITY and fills *host_info (may be NULL). */
 zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream,

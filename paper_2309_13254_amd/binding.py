@@ -18,6 +18,7 @@ __all__ = [
     "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
     "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "zen_pull_workspace_bytes", "zen_pull_encode", "zen_pull_encode_batch", "zen_pull_decode", "zen_pull_apply",
+    "zen_hash_memory_bytes", "zen_encode_hashed_workspace_bytes", "zen_encode_hashed",
     "alloc_encoded", "alloc_aggregated", "alloc_workspace",
 ]
 
@@ -47,6 +48,10 @@ class _Part(C.Structure):
 
 class _Aggregated(C.Structure):
     _fields_ = [("indices", C.c_void_p), ("values", C.c_void_p), ("count", C.c_void_p), ("cap_rows", C.c_uint64)]
+
+
+class _HashParams(C.Structure):
+    _fields_ = [("k", C.c_uint32), ("level2_seed", C.c_uint32), ("r1", C.c_uint64), ("r2", C.c_uint64)]
 
 
 class _StatusInfo(C.Structure):
@@ -85,6 +90,9 @@ def load_library():
         "zen_pull_encode_batch": [vp, C.POINTER(_Aggregated), vp, vp, u64, vp],
         "zen_pull_decode": [vp, vp, u32, vp, u64, vp, vp, u64, vp],
         "zen_pull_apply": [vp, C.POINTER(_Part), vp, vp, u64, vp],
+        "zen_hash_memory_bytes": [vp, C.POINTER(_HashParams), C.POINTER(u64)],
+        "zen_encode_hashed_workspace_bytes": [vp, C.POINTER(_HashParams), C.POINTER(u64)],
+        "zen_encode_hashed": [vp, vp, C.POINTER(_HashParams), vp, u64, C.POINTER(_Encoded), vp, vp, u64, vp],
         "zen_profile_enable": [vp, u32, u32],
         "zen_profile_collect": [vp, u32, C.POINTER(C.c_double), C.POINTER(u32), C.POINTER(u32)],
     }
@@ -295,6 +303,34 @@ def zen_pull_apply(ctx, parts, dense, workspace, stream=None):
     ps = (_Part * len(parts))(*[_Part(_ptr(p[0]), _ptr(p[1]), _ptr(p[2]), _ptr(p[3])) for p in parts])
     return _check(load_library().zen_pull_apply(ctx.handle, ps, dense.data_ptr(), workspace.data_ptr(),
                                                 workspace.numel(), _stream(stream)), "zen_pull_apply")
+
+
+def _hash_params(k, level2_seed, r1, r2):
+    return _HashParams(int(k), int(level2_seed) & 0xFFFFFFFF, int(r1), int(r2))
+
+
+def zen_hash_memory_bytes(ctx, k, level2_seed, r1, r2):
+    b = C.c_uint64()
+    hp = _hash_params(k, level2_seed, r1, r2)
+    _check(load_library().zen_hash_memory_bytes(ctx.handle, C.byref(hp), C.byref(b)), "zen_hash_memory_bytes")
+    return int(b.value)
+
+
+def zen_encode_hashed_workspace_bytes(ctx, k, level2_seed, r1, r2):
+    b = C.c_uint64()
+    hp = _hash_params(k, level2_seed, r1, r2)
+    _check(load_library().zen_encode_hashed_workspace_bytes(ctx.handle, C.byref(hp), C.byref(b)),
+           "zen_encode_hashed_workspace_bytes")
+    return int(b.value)
+
+
+def zen_encode_hashed(ctx, grad, k, level2_seed, r1, r2, hash_memory, out, serial_counts, workspace, stream=None):
+    hp = _hash_params(k, level2_seed, r1, r2)
+    st = out.struct()
+    return _check(load_library().zen_encode_hashed(ctx.handle, grad.data_ptr(), C.byref(hp), hash_memory.data_ptr(),
+                                                   hash_memory.numel(), C.byref(st), _ptr(serial_counts),
+                                                   workspace.data_ptr(), workspace.numel(), _stream(stream)),
+                  "zen_encode_hashed")
 
 
 def zen_status_fetch(ctx, workspace, stream=None):

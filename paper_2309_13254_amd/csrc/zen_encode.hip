@@ -1016,6 +1016,21 @@ hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const Encode
     return hipSuccess;
 }
 
+// values[pos] = grad[indices[pos]] for the first min(offsets[n_parts], capacity) rows of every worker.
+hipError_t launch_gather_rows(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs, uint32_t batch,
+                              uint64_t max_cap, hipStream_t s)
+{
+    const Geometry &g = ctx->geo;
+    uint64_t gx;
+    if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) gx = (max_cap + 3) / 4;
+    else gx = (max_cap * g.row_dim / 4 + 255) / 256;
+    if (gx < 1) gx = 1;
+    if (gx > 8192) gx = 8192;
+    ProfScope prof(ctx, K_GATHER_ROWS, s);
+    gather_rows_kernel<<<dim3((uint32_t)gx, batch), 256, 0, s>>>(g, grads, outs);
+    return hipGetLastError();
+}
+
 // ----------------------------------------------------------------------------------------------
 // Hash-domain tables of a BITMAP context ("computed and sorted offline", section "Hash Bitmap"):
 // the domains are the partition of ALL rows by h0, i.e. the encode pipeline run on an all-ones mask.

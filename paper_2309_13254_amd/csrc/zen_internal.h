@@ -98,6 +98,7 @@ enum KernelId : uint32_t {
     K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_ZERO, K_AGG_ACCUM, K_NONZERO_LIST, K_BITMAP_DECODE,
     K_AGG_GATHER, K_BM_COUNT, K_BM_SCAN, K_BM_MERGE, K_ENCODE_SMALL, K_GATHER_ROWS,
     K_PULL_ENCODE, K_PULL_ZERO, K_PULL_COUNT, K_PULL_SCAN, K_PULL_PLACE, K_PULL_PLACE_COO,
+    K_HM_CLEAR, K_HM_INSERT, K_HM_EXTRACT,
     K_COUNT
 };
 struct ProfRecord { hipEvent_t start, stop; uint32_t kernel; };
@@ -163,6 +164,8 @@ hipError_t launch_nonzero_list(zen_ctx *ctx, uint32_t *indices, uint64_t cap_row
                                char *ws, const EncodeLayout &L, hipStream_t s);
 hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info *tmp_status, hipStream_t s);
 hipError_t build_pull_tables(zen_ctx *ctx, hipStream_t s);   // zen_pull.hip
+hipError_t launch_gather_rows(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs, uint32_t batch,
+                              uint64_t max_cap, hipStream_t s);
 hipError_t launch_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint64_t n, uint32_t v, hipStream_t s);
 hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out, hipStream_t s);
