@@ -120,6 +120,56 @@ def pull_leg(zen, torch, wl, ctx, aggs, U, steps):
             "what": "zen_pull_encode_batch over %d servers + zen_pull_apply of one worker" % n}
 
 
+def hashmem_leg(zen, torch, n_elems=214_000_000, density=0.028, n_parts=16):
+    """Section "Understanding Zen", parameter study: one tensor of 214 M elements (the size of DeepFM's
+    embedding gradient), uniformly random non-zeros; r1 = {1, 2, 4} x nnz over all partitions at k = 3,
+    then k = 1..4 at r1 = 2 x nnz; r2 = r1 / 10 unless that overflows.  Times are ms for the whole
+    zen_encode_hashed call minus its dense scan, i.e. clear + insert + extract + gather."""
+    g = torch.zeros((n_elems, 1), dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20230913)
+    pos = torch.randint(0, n_elems, (int(n_elems * density * 1.02),), device="cuda", generator=gen).unique()
+    g[pos] = 1.0 + torch.rand((pos.numel(), 1), device="cuda", generator=gen)
+    nnz = int(pos.numel())
+    del pos
+    ctx = zen.ZenContext(n_elems, 1, n_parts, 7, zen.ZEN_INDEX_COO)
+    out = zen.alloc_encoded(ctx, nnz)
+    serial = torch.zeros(n_parts, dtype=torch.int32, device="cuda")
+
+    def run(mult, k):
+        r1 = mult * nnz // n_parts
+        for r2 in (r1 // 10, r1):
+            mem = zen.alloc_workspace(zen.zen_hash_memory_bytes(ctx, k, 99, r1, r2))
+            ws = zen.alloc_workspace(zen.zen_encode_hashed_workspace_bytes(ctx, k, 99, r1, r2))
+            zen.zen_encode_hashed(ctx, g, k, 99, r1, r2, mem, out, serial, ws)
+            if zen.zen_status_fetch(ctx, ws)[0] == 0:
+                break
+        zen.zen_profile_enable(ctx, 2, 64)
+        for _ in range(3):
+            zen.zen_encode_hashed(ctx, g, k, 99, r1, r2, mem, out, serial, ws)
+        torch.cuda.synchronize()
+        t = {a: b[0] / 3 for a, b in zen.zen_profile_collect(ctx).items()}
+        zen.zen_profile_enable(ctx, 0, 0)
+        return {"r1_over_nnz": mult, "k": k, "r2_over_r1": round(r2 / r1, 2),
+                "ms": round(sum(v for a, v in t.items() if a != "detect_kernel"), 3),
+                "insert_ms": round(t.get("hm_insert_kernel", 0.0), 3),
+                "extract_ms": round(t.get("hm_extract_kernels", 0.0) + t.get("hm_clear_kernel", 0.0), 3),
+                "serial_share": round(float(serial.sum().item()) / nnz, 4)}
+
+    rows = [run(m, 3) for m in (1, 2, 4)] + [run(2, k) for k in (1, 2, 4)]
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, 1))
+    zen.zen_encode(ctx, g, n_parts, 7, out, ws)
+    zen.zen_profile_enable(ctx, 2, 64)
+    for _ in range(3):
+        zen.zen_encode(ctx, g, n_parts, 7, out, ws)
+    torch.cuda.synchronize()
+    t = {a: b[0] / 3 for a, b in zen.zen_profile_collect(ctx).items()}
+    zen.zen_profile_enable(ctx, 0, 0)
+    return {"n_elems": n_elems, "nnz": nnz, "n_parts": n_parts, "study": rows,
+            "histogram_scan_scatter_ms": round(sum(v for a, v in t.items() if a != "detect_kernel"), 3),
+            "dense_scan_ms": round(t.get("detect_kernel", 0.0), 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,6 +181,9 @@ def main():
     ap.add_argument("--pull", action="store_true",
                     help="extra leg after the timed region: the servers' hash bitmaps (zen_pull_encode_batch) and one "
                          "worker's decode + dense placement (zen_pull_apply), timed on their own")
+    ap.add_argument("--hashmem", action="store_true",
+                    help="extra leg: the paper's parameter study of Algorithm 1's hash memory (r1, k) on a synthetic "
+                         "214 M-element tensor, next to the histogram/scan/scatter encode of the same tensor")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain 1 GiB copy kernel three times (reference for hardware "
                          "byte counters under rocprofv3 --pmc)")
@@ -211,6 +264,13 @@ def main():
     if args.pull:
         pull = pull_leg(zen, torch, wl, ctx, aggs, U, args.steps)
 
+    hashmem = None
+    if args.hashmem:
+        del grads
+        grads = None
+        torch.cuda.empty_cache()
+        hashmem = hashmem_leg(zen, torch)
+
     if args.calibrate_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -252,8 +312,10 @@ def main():
         out["kernel_ms_per_step"] = kernel_ms
     if pull is not None:
         out["pull"] = pull
+    if hashmem is not None:
+        out["hashmem_study"] = hashmem
     if not args.no_cpu_baseline:
-        del grads
+        grads = None
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(wl, sparse)
     print(json.dumps(out), flush=True)

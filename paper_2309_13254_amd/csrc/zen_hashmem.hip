@@ -32,34 +32,87 @@ hm_clear_kernel(uint32_t *x, uint64_t n_cells, uint32_t *counters, uint32_t n_pa
     for (uint64_t i = tid; i < n_parts; i += nt) counters[i] = r1;   // "atomic counters c <- r1^n"
 }
 
-// One block per tile of the row mask; every set bit is one idx of I, inserted by its own thread.
+// Blocks walk the tiles of the row mask; every set bit is one idx of I, inserted by its own thread.
+// Indices that found all k cells taken are parked in LDS and appended to the serial memory in
+// batches: the block counts its parked indices per partition and moves each partition's counter ONCE
+// per batch (n counters shared by the whole chip are the algorithm's serial bottleneck; the result
+// is the same as one atomicAdd per index, the cells handed out are just consecutive per block).
+static constexpr uint32_t HM_PARK = 4096;
+
+__device__ __forceinline__ void hm_flush_parked(const HashParams &hp, uint32_t n_parts, uint32_t *x, uint32_t *counters,
+                                                uint32_t *s_idx, uint32_t *s_slot, uint32_t *s_n, uint32_t *s_pc,
+                                                uint32_t seed, uint32_t pow2_mask)
+{
+    __syncthreads();
+    const uint32_t parked = min(*s_n, HM_PARK);
+    for (uint32_t i = threadIdx.x; i < parked; i += HM_THREADS) {   // rank of each parked index inside its partition
+        const uint32_t p = owner_of(s_idx[i], seed, n_parts, pow2_mask);
+        s_slot[i] = atomicAdd(&s_pc[p], 1u);
+    }
+    __syncthreads();
+    for (uint32_t p = threadIdx.x; p < n_parts; p += HM_THREADS) {   // one counter update per partition
+        const uint32_t c = s_pc[p];
+        s_pc[p] = c ? atomicAdd(&counters[p], c) : 0u;
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < parked; i += HM_THREADS) {
+        const uint32_t idx = s_idx[i], p = owner_of(idx, seed, n_parts, pow2_mask);
+        const uint32_t q = s_pc[p] + s_slot[i];
+        if (q < hp.cells) x[(uint64_t)p * hp.cells + q] = idx;
+    }
+    __syncthreads();
+    for (uint32_t p = threadIdx.x; p < n_parts; p += HM_THREADS) s_pc[p] = 0;
+    if (threadIdx.x == 0) *s_n = 0;
+    __syncthreads();
+}
+
 __global__ void __launch_bounds__(HM_THREADS)
 hm_insert_kernel(Geometry g, HashParams hp, const uint32_t *mask, const uint32_t *tflag, uint32_t *x,
                  uint32_t *counters)
 {
-    const uint32_t tile = blockIdx.x;
-    if (g.sparse_mask && !tflag[tile]) return;   // empty tile: its mask words were never written
-    const uint32_t *m = mask + (uint64_t)tile * g.tile_words;
-    const uint64_t row0 = (uint64_t)tile * g.tile_rows;
-    for (uint32_t wi = threadIdx.x; wi < g.tile_words; wi += HM_THREADS) {
-        uint32_t word = m[wi];
-        while (word) {
-            const uint32_t b = __ffs(word) - 1;
-            word &= word - 1;
-            const uint32_t idx = (uint32_t)(row0 + wi * 32 + b);
-            const uint32_t p = owner_of(idx, g.seed, g.n_parts, g.pow2_mask);
-            uint32_t *xp = x + (uint64_t)p * hp.cells;
-            bool placed = false;
-            for (uint32_t i = 1; i <= hp.k && !placed; ++i) {
-                const uint32_t q = murmur3_u32(idx, hp.seed2 + i) % hp.r1;
-                placed = atomicCAS(&xp[q], ZEN_EMPTY_KEY, idx) == ZEN_EMPTY_KEY;
+    __shared__ uint32_t s_idx[HM_PARK], s_slot[HM_PARK], s_pc[ZEN_MAX_PARTS], s_n;
+    for (uint32_t p = threadIdx.x; p < g.n_parts; p += HM_THREADS) s_pc[p] = 0;
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    uint32_t parked = 0;
+    for (uint32_t tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
+        if (g.sparse_mask && !tflag[tile]) continue;   // empty tile: its mask words were never written (uniform)
+        const uint32_t *m = mask + (uint64_t)tile * g.tile_words;
+        const uint64_t row0 = (uint64_t)tile * g.tile_rows;
+        for (uint32_t w0 = 0; w0 < g.tile_words; w0 += HM_THREADS) {
+            if (parked > HM_PARK / 2) {   // uniform: `parked` was read between two barriers
+                hm_flush_parked(hp, g.n_parts, x, counters, s_idx, s_slot, &s_n, s_pc, g.seed, g.pow2_mask);
+                parked = 0;
             }
-            if (!placed) {   // serial memory: the counter hands out the cells behind the parallel memory
-                const uint32_t q = atomicAdd(&counters[p], 1u);
-                if (q < hp.cells) xp[q] = idx;
+            const uint32_t wi = w0 + threadIdx.x;
+            uint32_t word = wi < g.tile_words ? m[wi] : 0u;
+            while (word) {
+                const uint32_t b = __ffs(word) - 1;
+                word &= word - 1;
+                const uint32_t idx = (uint32_t)(row0 + wi * 32 + b);
+                const uint32_t p = owner_of(idx, g.seed, g.n_parts, g.pow2_mask);
+                uint32_t *xp = x + (uint64_t)p * hp.cells;
+                bool placed = false;
+                for (uint32_t i = 1; i <= hp.k && !placed; ++i) {
+                    const uint32_t q = murmur3_u32(idx, hp.seed2 + i) % hp.r1;
+                    placed = atomicCAS(&xp[q], ZEN_EMPTY_KEY, idx) == ZEN_EMPTY_KEY;
+                }
+                if (!placed) {   // serial memory
+                    const uint32_t slot = atomicAdd(&s_n, 1u);
+                    if (slot < HM_PARK) {
+                        s_idx[slot] = idx;
+                    } else {     // no room to park: take a cell right away
+                        const uint32_t q = atomicAdd(&counters[p], 1u);
+                        if (q < hp.cells) xp[q] = idx;
+                    }
+                }
             }
+            __syncthreads();
+            parked = s_n;      // the same value in every thread ...
+            __syncthreads();   // ... because nobody parks again before all have read it
         }
     }
+    hm_flush_parked(hp, g.n_parts, x, counters, s_idx, s_slot, &s_n, s_pc, g.seed, g.pow2_mask);
 }
 
 // cnt[p * chunks + c] = occupied cells of chunk c of partition p (flat order = output order).
@@ -231,7 +284,8 @@ zen_status zen_encode_hashed(zen_ctx *ctx, const float *grad, const zen_hash_par
     }
     {
         ProfScope prof(ctx, K_HM_INSERT, s);
-        hm_insert_kernel<<<g.n_tiles, HM_THREADS, 0, s>>>(g, hp, (const uint32_t *)(ws + L.mask_off),
+        const uint32_t blocks = g.n_tiles < 2048 ? g.n_tiles : 2048;
+        hm_insert_kernel<<<blocks, HM_THREADS, 0, s>>>(g, hp, (const uint32_t *)(ws + L.mask_off),
                                                          (const uint32_t *)(ws + L.flag_off), x, counters);
         HIP_TRY(hipGetLastError());
     }

@@ -87,7 +87,7 @@ def test_hashed_encode_matches_oracle(oracle, zen, R, D, n, k, load):
         else:   # the order of insertion moves a few indices between the regions, no more
             one = oracle.hierarchical_hash(rows, part, slots[:1], n, r1, r2).serial_count
             assert (ser.astype(np.uint64) <= one).all()
-            assert abs(int(ser.sum()) - int(ref.serial_count.sum())) <= 0.1 * ref.serial_count.sum() + 16
+            assert abs(int(ser.sum()) - int(ref.serial_count.sum())) <= 0.25 * ref.serial_count.sum() + 32
 
 
 def test_hashed_encode_overflows_are_reported(oracle, zen):
