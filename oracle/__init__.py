@@ -24,5 +24,10 @@ from .zen_ref import (  # noqa: F401
     pull_apply,
     hash_slots,
     hierarchical_hash,
+    overlap_ratio,
+    union_sizes,
+    skewness,
+    time_balanced_parallelism,
+    time_hierarchical_centralization,
     imbalance,
 )

@@ -443,6 +443,97 @@ int64_t zen_ref_hash_memory_extract(const uint32_t *x, uint32_t n, uint64_t cell
 }
 
 /*
+ * Overlap ratio (Definition "The overlap ratio"): |I1 n I2| / min(|I1|, |I2|)
+ * for two index sets given as lists without repeats.  0 if either set is empty.
+ */
+double zen_ref_overlap_ratio(const uint32_t *I1, uint64_t n1, const uint32_t *I2, uint64_t n2, uint64_t n_rows)
+{
+    if (n1 == 0 || n2 == 0) return 0.0;
+    uint8_t *in1 = (uint8_t *)calloc((size_t)n_rows + 1, 1);
+    if (!in1) return -1.0;
+    for (uint64_t k = 0; k < n1; ++k) in1[I1[k]] = 1;
+    uint64_t both = 0;
+    for (uint64_t k = 0; k < n2; ++k) both += in1[I2[k]];
+    free(in1);
+    return (double)both / (double)(n1 < n2 ? n1 : n2);
+}
+
+/*
+ * Sizes of the unions of the first k index sets, k = 1..n_sets: union_size[k-1]
+ * = |I_1 u ... u I_k|.  With |G| rows the density after aggregating k tensors
+ * is d_G^k = union_size[k-1] / |G| and the densification ratio (Definition
+ * "The densification ratio") gamma_G^k = d_G^k / d_G.
+ */
+int zen_ref_union_sizes(uint32_t n_sets, const uint32_t *const *idx, const uint64_t *counts, uint64_t n_rows,
+                        uint64_t *union_size)
+{
+    uint8_t *seen = (uint8_t *)calloc((size_t)n_rows + 1, 1);
+    if (!seen) return ZEN_REF_ERR_NOMEM;
+    uint64_t u = 0;
+    for (uint32_t w = 0; w < n_sets; ++w) {
+        for (uint64_t k = 0; k < counts[w]; ++k) {
+            if (idx[w][k] >= n_rows) { free(seen); return ZEN_REF_ERR_INVALID; }
+            if (!seen[idx[w][k]]) { seen[idx[w][k]] = 1; ++u; }
+        }
+        union_size[w] = u;
+    }
+    free(seen);
+    return ZEN_REF_OK;
+}
+
+/*
+ * Skewness ratio (Definition "The skewness ratio"): G is split evenly into n
+ * consecutive partitions G_1..G_n; the ratio is max_i d_{G_i} / d_G.  Reading
+ * taken for |G| not divisible by n: every partition has ceil(|G|/n) rows except
+ * the last non-empty one, which has the rest; empty partitions are skipped.
+ * part_nnz (may be NULL) receives the non-zero count of every partition.
+ */
+double zen_ref_skewness(const uint32_t *I, uint64_t nnz, uint64_t n_rows, uint32_t n, uint64_t *part_nnz)
+{
+    if (n == 0 || n_rows == 0) return 0.0;
+    const uint64_t size = (n_rows + n - 1) / n;
+    uint64_t *c = (uint64_t *)calloc(n, 8);
+    if (!c) return -1.0;
+    for (uint64_t k = 0; k < nnz; ++k) c[I[k] / size]++;
+    double worst = 0.0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint64_t lo = (uint64_t)i * size;
+        if (part_nnz) part_nnz[i] = c[i];
+        if (lo >= n_rows) continue;
+        const uint64_t rows = (lo + size <= n_rows ? size : n_rows - lo);
+        const double d_i = (double)c[i] / (double)rows;
+        if (d_i > worst) worst = d_i;
+    }
+    free(c);
+    if (nnz == 0) return 0.0;
+    return worst / ((double)nnz / (double)n_rows);
+}
+
+/*
+ * Theoretical communication time of Balanced Parallelism, Equation (1):
+ *     T_bp = (n-1)/n * (gamma_G^n + 1) * 2 M d_G / b
+ * (each GPU receives 2(n-1)/n d_G M in Push and gamma_G^n times that in Pull).
+ */
+double zen_ref_time_balanced_parallelism(uint32_t n, double gamma_n, double d_G, double M, double b)
+{
+    return (double)(n - 1) / (double)n * (gamma_n + 1.0) * 2.0 * M * d_G / b;
+}
+
+/*
+ * Theoretical communication time of Hierarchical Centralization, Equation (2):
+ *     T_sm = sum_{i=1}^{log2 n} gamma_G^{2^(i-1)} * 2 M d_G / b,   n a power of two;
+ * gamma_pow2[i-1] = gamma_G^{2^(i-1)}, so gamma_pow2[0] = gamma_G^1 = 1.
+ */
+double zen_ref_time_hierarchical_centralization(uint32_t n, const double *gamma_pow2, double d_G, double M, double b)
+{
+    double sum = 0.0;
+    uint32_t stages = 0;
+    while ((1u << stages) < n) ++stages;
+    for (uint32_t i = 0; i < stages; ++i) sum += gamma_pow2[i];
+    return sum * 2.0 * M * d_G / b;
+}
+
+/*
  * Imbalance ratio (Definition "The imbalance ratio"): max_j n*|part_j| / total.
  * Push uses one worker's partition sizes; Pull uses the servers' set sizes
  * after aggregation.  Returns 1.0 for an empty input (nothing to balance).

@@ -94,6 +94,16 @@ def lib():
         L.zen_ref_hash_slots.argtypes = [_u32p, C.c_uint64, C.c_uint32, C.c_uint64, _u32p]
         L.zen_ref_hash_memory_extract.restype = C.c_int64
         L.zen_ref_hash_memory_extract.argtypes = [_u32p, C.c_uint32, C.c_uint64, _u32p, _u32p]
+        L.zen_ref_overlap_ratio.restype = C.c_double
+        L.zen_ref_overlap_ratio.argtypes = [_u32p, C.c_uint64, _u32p, C.c_uint64, C.c_uint64]
+        L.zen_ref_union_sizes.restype = C.c_int
+        L.zen_ref_union_sizes.argtypes = [C.c_uint32, C.POINTER(_u32p), _u64p, C.c_uint64, _u64p]
+        L.zen_ref_skewness.restype = C.c_double
+        L.zen_ref_skewness.argtypes = [_u32p, C.c_uint64, C.c_uint64, C.c_uint32, _u64p]
+        L.zen_ref_time_balanced_parallelism.restype = C.c_double
+        L.zen_ref_time_balanced_parallelism.argtypes = [C.c_uint32, C.c_double, C.c_double, C.c_double, C.c_double]
+        L.zen_ref_time_hierarchical_centralization.restype = C.c_double
+        L.zen_ref_time_hierarchical_centralization.argtypes = [C.c_uint32, _f64p, C.c_double, C.c_double, C.c_double]
         L.zen_ref_imbalance.restype = C.c_double
         L.zen_ref_imbalance.argtypes = [_u64p, C.c_uint32]
         _lib = L
@@ -315,6 +325,40 @@ def hierarchical_hash(I, part, slots, n, r1, r2):
         cnt = int(lib().zen_ref_hash_memory_extract(_p(x, _u32p), int(n), cells, _p(offsets, _u32p), _p(indices, _u32p)))
     return SimpleNamespace(rc=rc, x=x, serial_count=serial, needed_r2=int(needed.value), offsets=offsets,
                            indices=indices[:cnt])
+
+
+def overlap_ratio(I1, I2, n_rows):
+    I1, I2 = _c(I1, np.uint32).reshape(-1), _c(I2, np.uint32).reshape(-1)
+    return float(lib().zen_ref_overlap_ratio(_p(I1, _u32p), I1.size, _p(I2, _u32p), I2.size, int(n_rows)))
+
+
+def union_sizes(index_sets, n_rows):
+    idx = [_c(i, np.uint32).reshape(-1) for i in index_sets]
+    counts = np.array([i.size for i in idx], np.uint64)
+    arr = (_u32p * max(len(idx), 1))(*[_p(i, _u32p) for i in idx])
+    out = np.zeros(len(idx), np.uint64)
+    rc = lib().zen_ref_union_sizes(len(idx), arr, _p(counts, _u64p), int(n_rows), _p(out, _u64p))
+    if rc != 0:
+        raise ValueError("zen_ref_union_sizes: rc=%d" % rc)
+    return out
+
+
+def skewness(I, n_rows, n):
+    """-> (skewness ratio, non-zero count of each of the n even partitions)"""
+    I = _c(I, np.uint32).reshape(-1)
+    part = np.zeros(int(n), np.uint64)
+    r = float(lib().zen_ref_skewness(_p(I, _u32p), I.size, int(n_rows), int(n), _p(part, _u64p)))
+    return r, part
+
+
+def time_balanced_parallelism(n, gamma_n, d_G, M, b):
+    return float(lib().zen_ref_time_balanced_parallelism(int(n), float(gamma_n), float(d_G), float(M), float(b)))
+
+
+def time_hierarchical_centralization(n, gamma_pow2, d_G, M, b):
+    g = _c(gamma_pow2, np.float64).reshape(-1)
+    assert (1 << g.size) >= int(n)
+    return float(lib().zen_ref_time_hierarchical_centralization(int(n), _p(g, _f64p), float(d_G), float(M), float(b)))
 
 
 def imbalance(sizes):

@@ -118,6 +118,18 @@ def battery(oracle):
     assert np.array_equal(hh.offsets, offh)
     assert all(np.array_equal(np.sort(hh.indices[offh[q]:offh[q + 1]]), idxh[offh[q]:offh[q + 1]]) for q in range(4))
     assert oracle.hierarchical_hash(np.arange(9, dtype=np.uint32), [0] * 9, [[0] * 9], 1, 2, 7).rc == 2
+    # sparsity metrics and the two communication-time formulas: definitions on tiny sets, the extreme
+    # cases of section "Balanced Parallelism as the practical optimal scheme"
+    assert oracle.overlap_ratio([1, 4, 7, 9], [4, 9, 2, 3, 5, 6], 10) == 0.5 and oracle.overlap_ratio([4], [1, 4], 10) == 1.0
+    assert oracle.union_sizes([[0, 1, 2], [2, 3], [0, 3], [9]], 10).tolist() == [3, 4, 4, 5]
+    sk, sp = oracle.skewness(np.array([0, 9], np.uint32), 10, 3)
+    assert sp.tolist() == [1, 0, 1] and abs(sk - 2.5) < 1e-12
+    assert oracle.skewness(np.arange(10, dtype=np.uint32), 400, 4)[0] == 4.0
+    unit = 2 * 4e9 * 0.01 / 12.5e9
+    assert abs(oracle.time_balanced_parallelism(16, 1.0, 0.01, 4e9, 12.5e9) - 2 * 15 / 16 * unit) < 1e-12
+    assert abs(oracle.time_balanced_parallelism(16, 16.0, 0.01, 4e9, 12.5e9) - 15 * (1 + 1 / 16) * unit) < 1e-12
+    assert abs(oracle.time_hierarchical_centralization(16, [1, 2, 4, 8], 0.01, 4e9, 12.5e9) - 15 * unit) < 1e-12
+    assert abs(oracle.time_hierarchical_centralization(4, [1, 1.5, 99, 99], 0.01, 4e9, 12.5e9) - 2.5 * unit) < 1e-12
     # imbalance-ratio example of section "Balance dimension"
     assert abs(oracle.imbalance([1, 4, 1]) - 2.0) < 1e-12
 

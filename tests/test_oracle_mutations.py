@@ -65,6 +65,15 @@ MUTANTS = [
     ("hash slots: seed ignored", "(uint32_t)(zen_ref_hash(I[t], seed_i) % r1);", "(uint32_t)(zen_ref_hash(I[t], 0) % r1);"),
     ("extract: a cell skipped", "for (uint64_t q = 0; q < cells; ++q)\n            if (x[p * cells + q] != 0xffffffffu)",
      "for (uint64_t q = 1; q < cells; ++q)\n            if (x[p * cells + q] != 0xffffffffu)"),
+    ("overlap: divided by the larger set", "return (double)both / (double)(n1 < n2 ? n1 : n2);",
+     "return (double)both / (double)(n1 > n2 ? n1 : n2);"),
+    ("union sizes: repeats counted again", "if (!seen[idx[w][k]]) { seen[idx[w][k]] = 1; ++u; }", "{ seen[idx[w][k]] = 1; ++u; }"),
+    ("skewness: last partition taken as full", "const uint64_t rows = (lo + size <= n_rows ? size : n_rows - lo);",
+     "const uint64_t rows = size;"),
+    ("skewness: not divided by the density", "return worst / ((double)nnz / (double)n_rows);", "return worst;"),
+    ("time BP: the Pull term forgotten", "(gamma_n + 1.0) * 2.0 * M * d_G / b;", "(1.0) * 2.0 * M * d_G / b;"),
+    ("time BP: factor (n-1)/n missing", "return (double)(n - 1) / (double)n * (gamma_n + 1.0)", "return (gamma_n + 1.0)"),
+    ("time HC: one stage too many", "while ((1u << stages) < n) ++stages;", "while ((1u << stages) <= n) ++stages;"),
     ("imbalance: factor n missing", "return (double)n * (double)mx / (double)total;", "return (double)mx / (double)total;"),
 ]
 
