@@ -246,6 +246,41 @@ zen_status zen_encode_hashed(zen_ctx *ctx, const float *grad, const zen_hash_par
                              uint64_t hash_memory_bytes, const zen_encoded *host_out, uint32_t *serial_counts,
                              void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
+/*
+ * ---- Sparsity metrics and the choice of the scheme ------------------------------------------
+ *
+ * Counts behind the metrics of section "Characteristics of Sparse Tensors" for n_workers <=
+ * ZEN_MAX_BATCH gradients (device arrays of u64, all overwritten):
+ *   nnz[w]             |I_w|                          -> density d_G = nnz / n_rows
+ *   union_prefix[w]    |I_0 u ... u I_w|              -> d_G^k, densification ratio gamma_G^k = d_G^k / d_G
+ *   overlap[a][b]      |I_a n I_b| (diagonal = nnz)   -> overlap ratio = overlap / min(nnz_a, nnz_b)
+ *   even_split[w][i]   non-zero rows of worker w in the i-th of n_parts even consecutive partitions of
+ *                      ceil(n_rows / n_parts) rows     -> skewness ratio = max_i d_{G_i} / d_G
+ * (the hash partitions' sizes, for the imbalance ratio, are the offsets zen_encode writes).
+ * workspace: zen_encode_workspace_bytes(ctx, n_workers).
+ */
+typedef struct {
+    uint64_t *nnz;          /* [n_workers] */
+    uint64_t *union_prefix; /* [n_workers] */
+    uint64_t *overlap;      /* [n_workers][n_workers] */
+    uint64_t *even_split;   /* [n_workers][n_parts] */
+} zen_sparsity_counts;
+
+zen_status zen_sparsity_count(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                              const zen_sparsity_counts *host_out, void *workspace, uint64_t workspace_bytes,
+                              void *hip_stream);
+
+/*
+ * Theoretical communication times of the two candidate schemes (host arithmetic, no GPU work):
+ *   Balanced Parallelism,        Equation (1): t_bp = (n-1)/n * (gamma^n + 1) * 2 M d_G / b
+ *   Hierarchical Centralization, Equation (2): t_sm = sum_{i=1..log2 n} gamma^(2^(i-1)) * 2 M d_G / b
+ * host_gamma_pow2 = { gamma^1, gamma^2, gamma^4, ..., gamma^n } (log2 n + 1 entries, gamma^1 = 1);
+ * n a power of two >= 2; M = size of the dense tensor, b = bandwidth (same units).  The scheme with the
+ * smaller time is the optimal one (Theorem "Optimal schemes").
+ */
+zen_status zen_scheme_times(uint32_t n, const double *host_gamma_pow2, double d_G, double M, double b,
+                            double *host_t_bp, double *host_t_sm);
+
 /* Synchronous: waits for the stream, reads the status block of a workspace last used by an encode
  * or aggregate call, returns ZEN_OK / ZEN_ERR_CAPACITY and fills *host_info (may be NULL). */
 zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream,

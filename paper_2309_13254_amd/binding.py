@@ -19,6 +19,7 @@ __all__ = [
     "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "zen_pull_workspace_bytes", "zen_pull_encode", "zen_pull_encode_batch", "zen_pull_decode", "zen_pull_apply",
     "zen_hash_memory_bytes", "zen_encode_hashed_workspace_bytes", "zen_encode_hashed",
+    "zen_sparsity_count", "zen_scheme_times",
     "alloc_encoded", "alloc_aggregated", "alloc_workspace",
 ]
 
@@ -52,6 +53,10 @@ class _Aggregated(C.Structure):
 
 class _HashParams(C.Structure):
     _fields_ = [("k", C.c_uint32), ("level2_seed", C.c_uint32), ("r1", C.c_uint64), ("r2", C.c_uint64)]
+
+
+class _SparsityCounts(C.Structure):
+    _fields_ = [("nnz", C.c_void_p), ("union_prefix", C.c_void_p), ("overlap", C.c_void_p), ("even_split", C.c_void_p)]
 
 
 class _StatusInfo(C.Structure):
@@ -93,6 +98,9 @@ def load_library():
         "zen_hash_memory_bytes": [vp, C.POINTER(_HashParams), C.POINTER(u64)],
         "zen_encode_hashed_workspace_bytes": [vp, C.POINTER(_HashParams), C.POINTER(u64)],
         "zen_encode_hashed": [vp, vp, C.POINTER(_HashParams), vp, u64, C.POINTER(_Encoded), vp, vp, u64, vp],
+        "zen_sparsity_count": [vp, C.POINTER(vp), u32, C.POINTER(_SparsityCounts), vp, u64, vp],
+        "zen_scheme_times": [u32, C.POINTER(C.c_double), C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double),
+                             C.POINTER(C.c_double)],
         "zen_profile_enable": [vp, u32, u32],
         "zen_profile_collect": [vp, u32, C.POINTER(C.c_double), C.POINTER(u32), C.POINTER(u32)],
     }
@@ -331,6 +339,32 @@ def zen_encode_hashed(ctx, grad, k, level2_seed, r1, r2, hash_memory, out, seria
                                                    hash_memory.numel(), C.byref(st), _ptr(serial_counts),
                                                    workspace.data_ptr(), workspace.numel(), _stream(stream)),
                   "zen_encode_hashed")
+
+
+def zen_sparsity_count(ctx, grads, workspace, stream=None):
+    """-> dict of int64 device tensors: nnz[W], union_prefix[W], overlap[W, W], even_split[W, n_parts]."""
+    W = len(grads)
+    out = {"nnz": torch.empty(W, dtype=torch.int64, device=grads[0].device),
+           "union_prefix": torch.empty(W, dtype=torch.int64, device=grads[0].device),
+           "overlap": torch.empty((W, W), dtype=torch.int64, device=grads[0].device),
+           "even_split": torch.empty((W, ctx.n_parts), dtype=torch.int64, device=grads[0].device)}
+    st = _SparsityCounts(out["nnz"].data_ptr(), out["union_prefix"].data_ptr(), out["overlap"].data_ptr(),
+                         out["even_split"].data_ptr())
+    gp = (C.c_void_p * W)(*[g.data_ptr() for g in grads])
+    _check(load_library().zen_sparsity_count(ctx.handle, gp, W, C.byref(st), workspace.data_ptr(), workspace.numel(),
+                                             _stream(stream)), "zen_sparsity_count")
+    return out
+
+
+def zen_scheme_times(n, gamma_pow2, d_G, M, b):
+    """-> (t_bp, t_sm): Equations (1) and (2); gamma_pow2 = [gamma^1, gamma^2, gamma^4, ..., gamma^n]."""
+    g = (C.c_double * len(gamma_pow2))(*[float(x) for x in gamma_pow2])
+    t_bp, t_sm = C.c_double(), C.c_double()
+    if len(gamma_pow2) != int(n).bit_length():
+        raise ZenError(ZEN_ERR_INVALID, "zen_scheme_times")
+    _check(load_library().zen_scheme_times(int(n), g, float(d_G), float(M), float(b), C.byref(t_bp), C.byref(t_sm)),
+           "zen_scheme_times")
+    return float(t_bp.value), float(t_sm.value)
 
 
 def zen_status_fetch(ctx, workspace, stream=None):
