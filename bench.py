@@ -120,6 +120,37 @@ def pull_leg(zen, torch, wl, ctx, aggs, U, steps):
             "what": "zen_pull_encode_batch over %d servers + zen_pull_apply of one worker" % n}
 
 
+def metrics_leg(zen, torch, wl, ctx, grads, offs, U):
+    """Section "Characteristics of Sparse Tensors" on the benchmark's own gradients."""
+    W, n, R = wl.n_workers, wl.n_parts, wl.n_rows
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, W))
+    zen.zen_sparsity_count(ctx, grads, ws)
+    zen.zen_profile_enable(ctx, 2, 16)
+    c = {k: v.cpu().numpy() for k, v in zen.zen_sparsity_count(ctx, grads, ws).items()}
+    torch.cuda.synchronize()
+    t = zen.zen_profile_collect(ctx)
+    zen.zen_profile_enable(ctx, 0, 0)
+    nnz = c["nnz"].astype(np.float64)
+    d = float(nnz.mean()) / R
+    gam = {k: float(c["union_prefix"][k - 1]) / R / d for k in [1 << i for i in range(W.bit_length()) if (1 << i) <= W]}
+    ov = [c["overlap"][a][b] / min(nnz[a], nnz[b]) for a in range(W) for b in range(a + 1, W)]
+    size = -(-R // n)
+    skew = [max(c["even_split"][w][i] / min(size, R - i * size) for i in range(n) if i * size < R) / (nnz[w] / R)
+            for w in range(W)]
+    sizes = np.diff(offs, axis=1)
+    out = {"density": d, "densification": gam, "overlap_ratio_mean": float(np.mean(ov)) if ov else None,
+           "skewness_ratio_mean": float(np.mean(skew)),
+           "imbalance_push_max": float((sizes.max(axis=1) * n / sizes.sum(axis=1)).max()),
+           "imbalance_pull": float(max(U) * n / sum(U)),
+           "imbalance_push_even_split": float((c["even_split"].max(axis=1) * n / nnz).max()),
+           "stats_kernel_ms": round(t.get("stats_kernel", (0.0, 0))[0], 4)}
+    if W >= 2 and W & (W - 1) == 0:
+        t_bp, t_sm = zen.zen_scheme_times(W, [gam[1 << i] for i in range(W.bit_length())], d, float(wl.dense_bytes), 1.0)
+        out["t_bp_over_t_sm"] = t_bp / t_sm
+        out["scheme"] = "balanced parallelism" if t_bp <= t_sm else "hierarchical centralization"
+    return out
+
+
 def hashmem_leg(zen, torch, n_elems=214_000_000, density=0.028, n_parts=16):
     """Section "Understanding Zen", parameter study: one tensor of 214 M elements (the size of DeepFM's
     embedding gradient), uniformly random non-zeros; r1 = {1, 2, 4} x nnz over all partitions at k = 3,
@@ -181,6 +212,9 @@ def main():
     ap.add_argument("--pull", action="store_true",
                     help="extra leg after the timed region: the servers' hash bitmaps (zen_pull_encode_batch) and one "
                          "worker's decode + dense placement (zen_pull_apply), timed on their own")
+    ap.add_argument("--metrics", action="store_true",
+                    help="extra leg: the workload's sparsity metrics (density, densification, overlap, skewness, "
+                         "imbalance ratios) from zen_sparsity_count, and the scheme Equations (1) / (2) choose")
     ap.add_argument("--hashmem", action="store_true",
                     help="extra leg: the paper's parameter study of Algorithm 1's hash memory (r1, k) on a synthetic "
                          "214 M-element tensor, next to the histogram/scan/scatter encode of the same tensor")
@@ -264,6 +298,10 @@ def main():
     if args.pull:
         pull = pull_leg(zen, torch, wl, ctx, aggs, U, args.steps)
 
+    metrics = None
+    if args.metrics:
+        metrics = metrics_leg(zen, torch, wl, ctx, grads, offs, U)
+
     hashmem = None
     if args.hashmem:
         del grads
@@ -314,6 +352,8 @@ def main():
         out["pull"] = pull
     if hashmem is not None:
         out["hashmem_study"] = hashmem
+    if metrics is not None:
+        out["sparsity_metrics"] = metrics
     if not args.no_cpu_baseline:
         grads = None
         torch.cuda.empty_cache()
