@@ -29,5 +29,9 @@ from .zen_ref import (  # noqa: F401
     skewness,
     time_balanced_parallelism,
     time_hierarchical_centralization,
+    topk_threshold,
+    threshold_apply,
+    format_bytes,
+    nonzero_blocks,
     imbalance,
 )

@@ -534,6 +534,95 @@ double zen_ref_time_hierarchical_centralization(uint32_t n, const double *gamma_
 }
 
 /*
+ * Top-k threshold of a sparsifier in the style the paper uses in front of the
+ * synchronization (section "Implementation": sample the gradients, take the
+ * top-k threshold of the sample, apply it to the whole tensor; section
+ * "Characteristics": the top 5 % are kept).  The sample is every `stride`-th
+ * element starting at `first` (stride 1, first 0 = the whole tensor: exact
+ * top-k); magnitudes are compared as integers, mag(x) = bits(x) & 0x7fffffff,
+ * which orders non-NaN floats like |x| and puts NaN above Inf.  keep = number of
+ * sample elements to keep, 1 <= keep <= sample size; the threshold is the
+ * keep-th largest magnitude of the sample.  An element of the tensor is then
+ * kept iff mag(x) >= threshold and mag(x) != 0 (zen_ref_threshold_apply).
+ * Returns the threshold's bit pattern, or 0xffffffff on a bad argument.
+ */
+static int cmp_u32_desc(const void *a, const void *b)
+{
+    const uint32_t x = *(const uint32_t *)a, y = *(const uint32_t *)b;
+    return x < y ? 1 : (x > y ? -1 : 0);
+}
+
+uint32_t zen_ref_topk_threshold(const float *g, uint64_t n, uint64_t first, uint64_t stride, uint64_t keep)
+{
+    if (stride == 0 || first >= n) return 0xffffffffu;
+    const uint64_t m = (n - first + stride - 1) / stride;
+    if (keep == 0 || keep > m) return 0xffffffffu;
+    uint32_t *mag = (uint32_t *)malloc((size_t)m * 4);
+    if (!mag) return 0xffffffffu;
+    for (uint64_t t = 0; t < m; ++t) {
+        uint32_t bits;
+        memcpy(&bits, g + first + t * stride, 4);
+        mag[t] = bits & 0x7fffffffu;
+    }
+    qsort(mag, (size_t)m, 4, cmp_u32_desc);
+    const uint32_t thr = mag[keep - 1];
+    free(mag);
+    return thr;
+}
+
+/* out[i] = g[i] if mag(g[i]) >= max(threshold, 1) else +0.0; returns the number kept. */
+uint64_t zen_ref_threshold_apply(const float *g, uint64_t n, uint32_t threshold, float *out)
+{
+    uint64_t kept = 0;
+    const uint32_t thr = threshold ? threshold : 1u;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t bits;
+        memcpy(&bits, g + i, 4);
+        if ((bits & 0x7fffffffu) >= thr) { out[i] = g[i]; ++kept; } else { out[i] = 0.0f; }
+    }
+    return kept;
+}
+
+/*
+ * Bytes needed to send an aggregated fp32 sparse tensor of |G| elements with
+ * nnz non-zeros to a worker in each format of section "Sparse Formats" when the
+ * tensor is hash-partitioned over n servers (figure "tensor data size with
+ * different sparse formats": 16 servers):
+ *   dense        4|G|
+ *   COO          8 nnz                      (a 4-byte index per 4-byte value)
+ *   bitmap       4 nnz + n * |G|/8          (every server's non-zeros are spread over the whole
+ *                                            range, so every server sends a |G|-bit bitmap)
+ *   hash bitmap  4 nnz + |G|/8              (appendix "Proof of The Property of Hash Bitmap")
+ *   tensor block nonzero_blocks * (4*block + 4)   (OmniReduce: whole blocks of `block` gradients,
+ *                                            plus a 4-byte block id each)
+ * out[0..4] in that order.
+ */
+void zen_ref_format_bytes(uint64_t G, uint64_t nnz, uint32_t n, uint64_t nonzero_blocks, uint32_t block, double *out)
+{
+    out[0] = 4.0 * (double)G;
+    out[1] = 8.0 * (double)nnz;
+    out[2] = 4.0 * (double)nnz + (double)n * (double)G / 8.0;
+    out[3] = 4.0 * (double)nnz + (double)G / 8.0;
+    out[4] = (double)nonzero_blocks * (4.0 * (double)block + 4.0);
+}
+
+/* Number of blocks of `block` consecutive elements that hold at least one non-zero index. */
+uint64_t zen_ref_nonzero_blocks(const uint32_t *I, uint64_t nnz, uint64_t n_rows, uint32_t block)
+{
+    if (block == 0) return 0;
+    const uint64_t nb = (n_rows + block - 1) / block;
+    uint8_t *hit = (uint8_t *)calloc((size_t)nb + 1, 1);
+    if (!hit) return 0;
+    uint64_t c = 0;
+    for (uint64_t k = 0; k < nnz; ++k) {
+        const uint64_t b = I[k] / block;
+        if (!hit[b]) { hit[b] = 1; ++c; }
+    }
+    free(hit);
+    return c;
+}
+
+/*
  * Imbalance ratio (Definition "The imbalance ratio"): max_j n*|part_j| / total.
  * Push uses one worker's partition sizes; Pull uses the servers' set sizes
  * after aggregation.  Returns 1.0 for an empty input (nothing to balance).

@@ -104,6 +104,14 @@ def lib():
         L.zen_ref_time_balanced_parallelism.argtypes = [C.c_uint32, C.c_double, C.c_double, C.c_double, C.c_double]
         L.zen_ref_time_hierarchical_centralization.restype = C.c_double
         L.zen_ref_time_hierarchical_centralization.argtypes = [C.c_uint32, _f64p, C.c_double, C.c_double, C.c_double]
+        L.zen_ref_topk_threshold.restype = C.c_uint32
+        L.zen_ref_topk_threshold.argtypes = [_f32p, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64]
+        L.zen_ref_threshold_apply.restype = C.c_uint64
+        L.zen_ref_threshold_apply.argtypes = [_f32p, C.c_uint64, C.c_uint32, _f32p]
+        L.zen_ref_format_bytes.restype = None
+        L.zen_ref_format_bytes.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, _f64p]
+        L.zen_ref_nonzero_blocks.restype = C.c_uint64
+        L.zen_ref_nonzero_blocks.argtypes = [_u32p, C.c_uint64, C.c_uint64, C.c_uint32]
         L.zen_ref_imbalance.restype = C.c_double
         L.zen_ref_imbalance.argtypes = [_u64p, C.c_uint32]
         _lib = L
@@ -359,6 +367,35 @@ def time_hierarchical_centralization(n, gamma_pow2, d_G, M, b):
     g = _c(gamma_pow2, np.float64).reshape(-1)
     assert (1 << g.size) >= int(n)
     return float(lib().zen_ref_time_hierarchical_centralization(int(n), _p(g, _f64p), float(d_G), float(M), float(b)))
+
+
+def topk_threshold(g, keep, first=0, stride=1):
+    """Bit pattern of the keep-th largest magnitude among g[first::stride]."""
+    g = _c(g, np.float32).reshape(-1)
+    t = int(lib().zen_ref_topk_threshold(_p(g, _f32p), g.size, int(first), int(stride), int(keep)))
+    if t == 0xFFFFFFFF:
+        raise ValueError("zen_ref_topk_threshold: bad argument")
+    return t
+
+
+def threshold_apply(g, threshold):
+    """-> (g with every element of magnitude below the threshold replaced by +0.0, number kept)"""
+    g = _c(g, np.float32).reshape(-1)
+    out = np.empty_like(g)
+    kept = int(lib().zen_ref_threshold_apply(_p(g, _f32p), g.size, int(threshold), _p(out, _f32p)))
+    return out, kept
+
+
+def format_bytes(G, nnz, n, nonzero_blocks, block=256):
+    """-> dict of bytes per format: dense, coo, bitmap, hash_bitmap, tensor_block"""
+    out = np.zeros(5, np.float64)
+    lib().zen_ref_format_bytes(int(G), int(nnz), int(n), int(nonzero_blocks), int(block), _p(out, _f64p))
+    return dict(zip(("dense", "coo", "bitmap", "hash_bitmap", "tensor_block"), out.tolist()))
+
+
+def nonzero_blocks(I, n_rows, block=256):
+    I = _c(I, np.uint32).reshape(-1)
+    return int(lib().zen_ref_nonzero_blocks(_p(I, _u32p), I.size, int(n_rows), int(block)))
 
 
 def imbalance(sizes):

@@ -130,6 +130,17 @@ def battery(oracle):
     assert abs(oracle.time_balanced_parallelism(16, 16.0, 0.01, 4e9, 12.5e9) - 15 * (1 + 1 / 16) * unit) < 1e-12
     assert abs(oracle.time_hierarchical_centralization(16, [1, 2, 4, 8], 0.01, 4e9, 12.5e9) - 15 * unit) < 1e-12
     assert abs(oracle.time_hierarchical_centralization(4, [1, 1.5, 99, 99], 0.01, 4e9, 12.5e9) - 2.5 * unit) < 1e-12
+    # top-k threshold sparsifier and format sizes
+    gt = np.array([0.5, -3.0, 0.0, 2.0, -0.25, 7.0, -7.5, 1.0], np.float32)
+    fb = lambda v: int(np.float32(v).view(np.uint32))
+    assert oracle.topk_threshold(gt, 1) == fb(7.5) and oracle.topk_threshold(gt, 3) == fb(3.0) and oracle.topk_threshold(gt, 8) == 0
+    assert oracle.topk_threshold(gt, 2, first=1, stride=2) == fb(3.0)
+    ot, kt = oracle.threshold_apply(gt, fb(2.0))
+    assert kt == 4 and ot.tolist() == [0, -3.0, 0, 2.0, 0, 7.0, -7.5, 0] and oracle.threshold_apply(gt, 0)[1] == 7
+    fs = oracle.format_bytes(1 << 20, 1 << 19, 16, 10, 256)
+    assert fs == {"dense": 4.0 * (1 << 20), "coo": 8.0 * (1 << 19), "bitmap": 4.0 * (1 << 19) + 16 * (1 << 20) / 8,
+                  "hash_bitmap": 4.0 * (1 << 19) + (1 << 20) / 8, "tensor_block": 10 * 1028.0}
+    assert oracle.nonzero_blocks([0, 1, 255, 256, 1000], 1024, 256) == 3
     # imbalance-ratio example of section "Balance dimension"
     assert abs(oracle.imbalance([1, 4, 1]) - 2.0) < 1e-12
 

@@ -74,6 +74,14 @@ MUTANTS = [
     ("time BP: the Pull term forgotten", "(gamma_n + 1.0) * 2.0 * M * d_G / b;", "(1.0) * 2.0 * M * d_G / b;"),
     ("time BP: factor (n-1)/n missing", "return (double)(n - 1) / (double)n * (gamma_n + 1.0)", "return (gamma_n + 1.0)"),
     ("time HC: one stage too many", "while ((1u << stages) < n) ++stages;", "while ((1u << stages) <= n) ++stages;"),
+    ("top-k: ascending instead of descending", "return x < y ? 1 : (x > y ? -1 : 0);", "return x > y ? 1 : (x < y ? -1 : 0);"),
+    ("top-k: sign bit compared", "mag[t] = bits & 0x7fffffffu;", "mag[t] = bits;"),
+    ("top-k: sample offset ignored", "memcpy(&bits, g + first + t * stride, 4);", "memcpy(&bits, g + t * stride, 4);"),
+    ("threshold: strictly greater", "if ((bits & 0x7fffffffu) >= thr) { out[i] = g[i]; ++kept; }", "if ((bits & 0x7fffffffu) > thr) { out[i] = g[i]; ++kept; }"),
+    ("threshold: zeros kept at threshold 0", "const uint32_t thr = threshold ? threshold : 1u;", "const uint32_t thr = threshold;"),
+    ("format bytes: hash bitmap charged per server", "out[3] = 4.0 * (double)nnz + (double)G / 8.0;", "out[3] = 4.0 * (double)nnz + (double)n * (double)G / 8.0;"),
+    ("format bytes: block id forgotten", "(4.0 * (double)block + 4.0);", "(4.0 * (double)block);"),
+    ("nonzero blocks: every index counted", "if (!hit[b]) { hit[b] = 1; ++c; }", "{ hit[b] = 1; ++c; }"),
     ("imbalance: factor n missing", "return (double)n * (double)mx / (double)total;", "return (double)mx / (double)total;"),
 ]
 
