@@ -281,6 +281,43 @@ zen_status zen_sparsity_count(zen_ctx *ctx, const float *const *host_grads, uint
 zen_status zen_scheme_times(uint32_t n, const double *host_gamma_pow2, double d_G, double M, double b,
                             double *host_t_bp, double *host_t_sm);
 
+/*
+ * ---- Gradient sparsifier in front of the encode, and the sparse formats' sizes ----------------
+ *
+ * zen_topk_threshold: the top-k threshold of a sparsifier in the style of DGC as the paper deploys it
+ * [section "Implementation": sample the gradients, compute the top-k threshold of the sample, apply
+ * it to the tensor; section "Characteristics of Sparse Tensors": the top 5 % are kept].  The sample
+ * is g[first], g[first+stride], ... (first = 0, stride = 1: exact top-k of all n elements);
+ * *threshold (device) = the keep-th largest magnitude of the sample as a bit pattern
+ * (bits & 0x7fffffff; NaN ranks above Inf).  1 <= keep <= sample size.  workspace:
+ * zen_topk_workspace_bytes, 256-byte aligned.  Nothing synchronises.
+ *
+ * zen_encode_batch_sparsified: zen_encode_batch of the tensors with every element whose magnitude is
+ * below thresholds[w] (device array, one per worker; 0 and 1 both mean "every non-zero") treated as
+ * zero -- the sparsifier is applied inside the dense scan, the tensor is neither copied nor
+ * modified.  Element-level contexts (row_dim == 1) only.
+ */
+zen_status zen_topk_workspace_bytes(uint64_t *host_bytes);
+zen_status zen_topk_threshold(const float *g, uint64_t n, uint64_t first, uint64_t stride, uint64_t keep,
+                              uint32_t *threshold, void *workspace, uint64_t workspace_bytes, void *hip_stream);
+zen_status zen_encode_batch_sparsified(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                                       const uint32_t *thresholds, const zen_encoded *host_outs, void *workspace,
+                                       uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * Sizes of the sparse formats of section "Sparse Formats".  zen_format_count: counts[0] = non-zero
+ * rows of grad, counts[1] = blocks of `block` consecutive rows holding at least one (device u64[2];
+ * block a multiple of 32 that divides the context's tile; workspace: zen_encode_workspace_bytes(ctx, 1)).
+ * zen_format_bytes (host arithmetic): bytes to send a tensor of n_elems fp32 elements with nnz
+ * non-zeros, hash-partitioned over n_servers, as host_out[0..4] = dense 4|G|, COO 8 nnz, one |G|-bit
+ * bitmap per server 4 nnz + n|G|/8, hash bitmap 4 nnz + |G|/8, tensor blocks nonzero_blocks *
+ * (4 block + 4).
+ */
+zen_status zen_format_count(zen_ctx *ctx, const float *grad, uint32_t block, uint64_t *counts, void *workspace,
+                            uint64_t workspace_bytes, void *hip_stream);
+zen_status zen_format_bytes(uint64_t n_elems, uint64_t nnz, uint32_t n_servers, uint64_t nonzero_blocks, uint32_t block,
+                            double *host_out);
+
 /* Synchronous: waits for the stream, reads the status block of a workspace last used by an encode
  * or aggregate call, returns ZEN_OK / ZEN_ERR_CAPACITY and fills *host_info (may be NULL). */
 zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream,

@@ -19,7 +19,8 @@ __all__ = [
     "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "zen_pull_workspace_bytes", "zen_pull_encode", "zen_pull_encode_batch", "zen_pull_decode", "zen_pull_apply",
     "zen_hash_memory_bytes", "zen_encode_hashed_workspace_bytes", "zen_encode_hashed",
-    "zen_sparsity_count", "zen_scheme_times",
+    "zen_sparsity_count", "zen_scheme_times", "zen_topk_workspace_bytes", "zen_topk_threshold",
+    "zen_encode_batch_sparsified", "zen_format_count", "zen_format_bytes",
     "alloc_encoded", "alloc_aggregated", "alloc_workspace",
 ]
 
@@ -101,6 +102,11 @@ def load_library():
         "zen_sparsity_count": [vp, C.POINTER(vp), u32, C.POINTER(_SparsityCounts), vp, u64, vp],
         "zen_scheme_times": [u32, C.POINTER(C.c_double), C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double),
                              C.POINTER(C.c_double)],
+        "zen_topk_workspace_bytes": [C.POINTER(u64)],
+        "zen_topk_threshold": [vp, u64, u64, u64, u64, vp, vp, u64, vp],
+        "zen_encode_batch_sparsified": [vp, C.POINTER(vp), u32, vp, C.POINTER(_Encoded), vp, u64, vp],
+        "zen_format_count": [vp, vp, u32, vp, vp, u64, vp],
+        "zen_format_bytes": [u64, u64, u32, u64, u32, C.POINTER(C.c_double)],
         "zen_profile_enable": [vp, u32, u32],
         "zen_profile_collect": [vp, u32, C.POINTER(C.c_double), C.POINTER(u32), C.POINTER(u32)],
     }
@@ -365,6 +371,43 @@ def zen_scheme_times(n, gamma_pow2, d_G, M, b):
     _check(load_library().zen_scheme_times(int(n), g, float(d_G), float(M), float(b), C.byref(t_bp), C.byref(t_sm)),
            "zen_scheme_times")
     return float(t_bp.value), float(t_sm.value)
+
+
+def zen_topk_workspace_bytes():
+    b = C.c_uint64()
+    _check(load_library().zen_topk_workspace_bytes(C.byref(b)), "zen_topk_workspace_bytes")
+    return int(b.value)
+
+
+def zen_topk_threshold(g, keep, threshold, workspace, first=0, stride=1, stream=None):
+    """threshold: int32 device tensor with one element (receives the bit pattern)."""
+    return _check(load_library().zen_topk_threshold(g.data_ptr(), g.numel(), int(first), int(stride), int(keep),
+                                                    threshold.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                                    _stream(stream)), "zen_topk_threshold")
+
+
+def zen_encode_batch_sparsified(ctx, grads, thresholds, outs, workspace, stream=None):
+    n = len(grads)
+    assert len(outs) == n and thresholds.numel() >= n
+    gp = (C.c_void_p * n)(*[g.data_ptr() for g in grads])
+    es = (_Encoded * n)(*[o.struct() for o in outs])
+    return _check(load_library().zen_encode_batch_sparsified(ctx.handle, gp, n, thresholds.data_ptr(), es,
+                                                             workspace.data_ptr(), workspace.numel(), _stream(stream)),
+                  "zen_encode_batch_sparsified")
+
+
+def zen_format_count(ctx, grad, block, counts, workspace, stream=None):
+    """counts: int64 device tensor [2] -> (non-zero rows, non-zero blocks)."""
+    return _check(load_library().zen_format_count(ctx.handle, grad.data_ptr(), int(block), counts.data_ptr(),
+                                                  workspace.data_ptr(), workspace.numel(), _stream(stream)),
+                  "zen_format_count")
+
+
+def zen_format_bytes(n_elems, nnz, n_servers, nonzero_blocks, block=256):
+    out = (C.c_double * 5)()
+    _check(load_library().zen_format_bytes(int(n_elems), int(nnz), int(n_servers), int(nonzero_blocks), int(block), out),
+           "zen_format_bytes")
+    return dict(zip(("dense", "coo", "bitmap", "hash_bitmap", "tensor_block"), list(out)))
 
 
 def zen_status_fetch(ctx, workspace, stream=None):

@@ -216,11 +216,12 @@ static zen_status check_encoded(const zen_ctx *ctx, const zen_encoded &e)
     return ZEN_OK;
 }
 
-zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
-                            const zen_encoded *host_outs, void *workspace, uint64_t workspace_bytes,
-                            void *hip_stream)
+static zen_status encode_batch_impl(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                                    const uint32_t *thresholds, const zen_encoded *host_outs, void *workspace,
+                                    uint64_t workspace_bytes, void *hip_stream)
 {
     if (!ctx || !host_grads || !host_outs || n_workers == 0 || !workspace) return ZEN_ERR_INVALID;
+    if (thresholds && (ctx->geo.row_dim != 1 || ((uintptr_t)thresholds & 3u))) return ZEN_ERR_INVALID;
     if ((uintptr_t)workspace & 255u) return ZEN_ERR_INVALID;
     const Geometry &g = ctx->geo;
     for (uint32_t w = 0; w < n_workers; ++w) {
@@ -247,16 +248,32 @@ zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32
             outs.bitmap[i] = host_outs[w0 + i].bitmap;
             outs.cap_rows[i] = host_outs[w0 + i].cap_rows;
         }
+        const uint32_t *thr = thresholds ? thresholds + w0 : nullptr;
         if (encode_small_applies(ctx, outs, nb)) {
-            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, false, s));
+            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, false, s, thr));
             HIP_TRY(launch_encode_small(ctx, grads, outs, nb, ws, L, s));
         } else {
-            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, true, s));
+            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, true, s, thr));
             HIP_TRY(launch_partition_scan(ctx, outs, nb, ws, L, s));
             HIP_TRY(launch_scatter(ctx, grads, outs, nb, ws, L, s));
         }
     }
     return ZEN_OK;
+}
+
+zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                            const zen_encoded *host_outs, void *workspace, uint64_t workspace_bytes,
+                            void *hip_stream)
+{
+    return encode_batch_impl(ctx, host_grads, n_workers, nullptr, host_outs, workspace, workspace_bytes, hip_stream);
+}
+
+zen_status zen_encode_batch_sparsified(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
+                                       const uint32_t *thresholds, const zen_encoded *host_outs, void *workspace,
+                                       uint64_t workspace_bytes, void *hip_stream)
+{
+    if (!thresholds) return ZEN_ERR_INVALID;
+    return encode_batch_impl(ctx, host_grads, n_workers, thresholds, host_outs, workspace, workspace_bytes, hip_stream);
 }
 
 zen_status zen_encode(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_t hash_seed,
@@ -408,7 +425,7 @@ static const char *const kKernelNames[K_COUNT] = {
     "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel", "encode_small_kernel", "gather_rows_kernel",
     "pull_encode_kernel", "pull_zero_kernel", "pull_count_kernel", "pull_scan_kernel", "pull_place_kernel",
     "pull_place_coo_kernel", "hm_clear_kernel", "hm_insert_kernel", "hm_extract_kernels",
-    "stats_kernel"};
+    "stats_kernel", "topk_select_kernels"};
 
 static void prof_release(zen_ctx *ctx)
 {

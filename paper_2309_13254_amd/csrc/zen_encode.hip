@@ -41,8 +41,8 @@ __device__ __forceinline__ u32x4 load_stream(const u32x4 *p)
 // row_dim == 1.  A wave-load of 64 x 16 B covers 256 rows = 8 mask words.
 template <int UNROLL>
 __device__ __forceinline__ void detect_elem(const float *__restrict__ g, uint64_t n_rows, uint64_t row0,
-                                            uint32_t tile_rows, uint32_t *s_mask)
-{
+                                            uint32_t tile_rows, uint32_t *s_mask, uint32_t thr)
+{   // thr >= 1: smallest magnitude (as an integer) that counts as present; 1 = every non-zero
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const uint32_t n_chunks = tile_rows >> 8;
     for (uint32_t c0 = wave * UNROLL; c0 < n_chunks; c0 += nw * UNROLL) {
@@ -68,8 +68,8 @@ __device__ __forceinline__ void detect_elem(const float *__restrict__ g, uint64_
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t c = c0 + u;
             if (c < n_chunks && ballot(nonzero_mag(v[u]) != 0) != 0) {   // s_mask starts zeroed
-                uint32_t nib = ((v[u].x & 0x7fffffffu) ? 1u : 0u) | ((v[u].y & 0x7fffffffu) ? 2u : 0u) |
-                               ((v[u].z & 0x7fffffffu) ? 4u : 0u) | ((v[u].w & 0x7fffffffu) ? 8u : 0u);
+                uint32_t nib = ((v[u].x & 0x7fffffffu) >= thr ? 1u : 0u) | ((v[u].y & 0x7fffffffu) >= thr ? 2u : 0u) |
+                               ((v[u].z & 0x7fffffffu) >= thr ? 4u : 0u) | ((v[u].w & 0x7fffffffu) >= thr ? 8u : 0u);
                 uint32_t word = nib << (4 * (lane & 7));
                 word |= __shfl_xor(word, 1, ZEN_WAVE);
                 word |= __shfl_xor(word, 2, ZEN_WAVE);
@@ -184,8 +184,10 @@ template <int PATH>
 __global__ void __launch_bounds__(DETECT_THREADS)
 detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
               uint32_t *hist_base, uint64_t hist_stride_words, uint32_t *tflag_base, uint64_t tflag_stride,
-              zen_status_info *reset_status)
+              zen_status_info *reset_status, const uint32_t *min_mag)
 {
+    // min_mag (element-level inputs only, may be NULL): per worker, the magnitude threshold of a top-k
+    // sparsifier applied on the fly -- elements below it are treated as zeros
     extern __shared__ uint32_t smem[];
     uint32_t *s_mask = smem;                  // [tile_words]
     uint32_t *s_hist = smem + g.tile_words;   // [n_parts]
@@ -202,7 +204,7 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
         __syncthreads();
     }
 
-    if (PATH == 0) detect_elem<8>(grad, g.n_rows, row0, g.tile_rows, s_mask);
+    if (PATH == 0) detect_elem<8>(grad, g.n_rows, row0, g.tile_rows, s_mask, min_mag ? max(min_mag[worker], 1u) : 1u);
     else if (PATH <= 6) detect_sub<(PATH >= 1 && PATH <= 6) ? (1 << (PATH - 1)) : 1>(grad, g.n_rows, row0, g.tile_rows, s_mask);
     else if (PATH == 7) detect_row<4>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
     else detect_row<1>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
@@ -719,8 +721,10 @@ hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, 
 }
 
 hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
-                         const EncodeLayout &L, bool reset_status, bool want_hist, hipStream_t s)
+                         const EncodeLayout &L, bool reset_status, bool want_hist, hipStream_t s,
+                         const uint32_t *min_mag)
 {
+    if (min_mag && ctx->geo.mode != MODE_ELEM) return hipErrorInvalidValue;
     const Geometry &g = ctx->geo;
     const size_t lds = (size_t)(g.tile_words + g.n_parts) * 4;
     ProfScope prof(ctx, K_DETECT, s);
@@ -735,7 +739,8 @@ hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, ch
 #define ZEN_DETECT_CASE(P)                                                                                 \
     case P:                                                                                                \
         detect_kernel<P><<<grid, DETECT_THREADS, lds, s>>>(g, grads, mask, L.mask_stride / 4, hist,        \
-                                                          L.hist_stride / 4, tflag, L.flag_stride / 4, rs); \
+                                                          L.hist_stride / 4, tflag, L.flag_stride / 4, rs, \
+                                                          min_mag);                                        \
         break;
     switch (path) {
         ZEN_DETECT_CASE(0) ZEN_DETECT_CASE(1) ZEN_DETECT_CASE(2) ZEN_DETECT_CASE(3) ZEN_DETECT_CASE(4)
