@@ -151,6 +151,49 @@ def metrics_leg(zen, torch, wl, ctx, grads, offs, U):
     return out
 
 
+def sparsify_leg(zen, torch, n_elems=1 << 28, n_parts=16, keep_share=0.05, stride=100):
+    """A dense gradient (every element non-zero, N(0,1)), the paper's sparsifier set-up: the threshold of
+    the top 5 % from a 1-in-100 sample, then zen_encode with that threshold applied inside the dense scan
+    (hash-bitmap format), and what the result would cost on the wire in each sparse format."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    g = torch.randn((n_elems, 1), dtype=torch.float32, device="cuda", generator=gen)
+    ctx = zen.ZenContext(n_elems, 1, n_parts, 7, zen.ZEN_INDEX_BITMAP)
+    thr = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws_t = zen.alloc_workspace(zen.zen_topk_workspace_bytes())
+    m = (n_elems + stride - 1) // stride
+    cap = int(n_elems * keep_share * 1.2)
+    out = zen.alloc_encoded(ctx, cap, with_indices=False)
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, 1))
+
+    def run():
+        zen.zen_topk_threshold(g, int(m * keep_share), thr, ws_t, first=0, stride=stride)
+        zen.zen_encode_batch_sparsified(ctx, [g], thr, [out], ws)
+
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    assert zen.zen_status_fetch(ctx, ws)[0] == 0
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record()
+    for _ in range(5):
+        zen.zen_topk_threshold(g, int(m * keep_share), thr, ws_t, first=0, stride=stride)
+    ev[1].record()
+    for _ in range(5):
+        zen.zen_encode_batch_sparsified(ctx, [g], thr, [out], ws)
+    ev[2].record()
+    torch.cuda.synchronize()
+    nnz = int(out.offsets[-1].item())
+    # the kept elements of a dense random tensor hit nearly every block of 256
+    sizes = zen.zen_format_bytes(n_elems, nnz, n_parts, -(-n_elems // 256), 256)
+    t_enc = ev[1].elapsed_time(ev[2]) / 5
+    return {"n_elems": n_elems, "kept": nnz, "kept_share": round(nnz / n_elems, 5),
+            "threshold": float(thr.view(torch.float32).item()),
+            "threshold_ms": round(ev[0].elapsed_time(ev[1]) / 5, 4), "encode_ms": round(t_enc, 4),
+            "encode_dense_GBps": round(4 * n_elems / t_enc / 1e6, 1),
+            "format_bytes_over_dense": {k: round(v / sizes["dense"], 4) for k, v in sizes.items()}}
+
+
 def hashmem_leg(zen, torch, n_elems=214_000_000, density=0.028, n_parts=16):
     """Section "Understanding Zen", parameter study: one tensor of 214 M elements (the size of DeepFM's
     embedding gradient), uniformly random non-zeros; r1 = {1, 2, 4} x nnz over all partitions at k = 3,
@@ -215,6 +258,9 @@ def main():
     ap.add_argument("--metrics", action="store_true",
                     help="extra leg: the workload's sparsity metrics (density, densification, overlap, skewness, "
                          "imbalance ratios) from zen_sparsity_count, and the scheme Equations (1) / (2) choose")
+    ap.add_argument("--sparsify", action="store_true",
+                    help="extra leg: top-5 %% sparsifier (sampled threshold + encode with the threshold applied in "
+                         "the dense scan) on a dense 2^28-element tensor, and the format sizes of the result")
     ap.add_argument("--hashmem", action="store_true",
                     help="extra leg: the paper's parameter study of Algorithm 1's hash memory (r1, k) on a synthetic "
                          "214 M-element tensor, next to the histogram/scan/scatter encode of the same tensor")
@@ -302,6 +348,12 @@ def main():
     if args.metrics:
         metrics = metrics_leg(zen, torch, wl, ctx, grads, offs, U)
 
+    sparsify = None
+    if args.sparsify:
+        grads = None
+        torch.cuda.empty_cache()
+        sparsify = sparsify_leg(zen, torch)
+
     hashmem = None
     if args.hashmem:
         del grads
@@ -354,6 +406,8 @@ def main():
         out["hashmem_study"] = hashmem
     if metrics is not None:
         out["sparsity_metrics"] = metrics
+    if sparsify is not None:
+        out["sparsifier"] = sparsify
     if not args.no_cpu_baseline:
         grads = None
         torch.cuda.empty_cache()
