@@ -365,7 +365,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row (row copies only)
     uint32_t *s_tmp = s_pos + (ELEM ? 0 : SEG_ROWS); // [32]
     uint32_t *s_mask = s_tmp + 32;                   // [tile_words] the tile's mask
-    uint32_t *s_seg = s_mask + g.tile_words;         // [ceil(tile_words / SEG_WORDS)] 1 = the segment holds rows
+    uint32_t *s_seg = s_mask + g.tile_words;         // [ceil(tile_words / SEG_WORDS)] rows of each 64-word segment
     uint32_t *s_b0 = s_seg + (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;   // bitmap only: [n] first bit of (tile, p)
     uint32_t *s_b1 = s_b0 + n;                       //              [n] end bit of (tile, p)
     uint32_t *s_boff = s_b1 + n;                     //              [n+1] LDS word offset of p's range
@@ -406,8 +406,8 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
         const uint32_t *gmask = wmask + (uint64_t)tile * g.tile_words;
         if (ELEM) {
             __syncthreads();                                   // the barrier between tiles
-            // The tile's mask goes to LDS with a flag per 64-word segment, so that empty segments cost
-            // neither a memory access nor a barrier.
+            // The tile's mask goes to LDS with a row count per 64-word segment: empty segments then cost
+            // neither a memory access nor a barrier, and sparse neighbours are expanded together.
             for (uint32_t q0 = 0; q0 * SCATTER_THREADS < g.tile_words; q0 += 8) {
                 if (!pf_ok) {
 #pragma unroll
@@ -422,8 +422,10 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     const uint32_t first = i - lane_id();      // the wave's 64 words are one segment
                     if (first >= g.tile_words) continue;       // uniform per wave
                     if (i < g.tile_words) s_mask[i] = mw[q];
-                    const bool seg_any = ballot(mw[q] != 0) != 0;
-                    if (lane_id() == 0) s_seg[first / SEG_WORDS] = seg_any;
+                    uint32_t seg_cnt = __popc(mw[q]);   // rows of the segment
+#pragma unroll
+                    for (int d = 32; d > 0; d >>= 1) seg_cnt += __shfl_xor(seg_cnt, d, ZEN_WAVE);
+                    if (lane_id() == 0) s_seg[first / SEG_WORDS] = seg_cnt;
                 }
             }
             nxt_tile = nxt2_tile;
@@ -471,22 +473,46 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             for (uint32_t i = threadIdx.x; i < bm_words; i += blockDim.x) s_bm[i] = 0;
         }
 
-        for (uint32_t w0 = 0; w0 < g.tile_words; w0 += SEG_WORDS) {
-            // (a) expand up to 64 mask words into the ascending row list
-            if (ELEM && !s_seg[w0 / SEG_WORDS]) continue;   // uniform
-            uint32_t word = 0;
-            if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words)
-                word = ELEM ? s_mask[w0 + threadIdx.x] : gmask[w0 + threadIdx.x];
-            uint32_t total;
-            const uint32_t pre = block_exclusive_scan(threadIdx.x < SEG_WORDS ? __popc(word) : 0u, s_tmp, &total);
-            if (total == 0) continue;   // uniform: total comes from LDS
-            if (threadIdx.x < SEG_WORDS) {
-                uint32_t k = pre;
-                const uint32_t rbase = (uint32_t)(row0 + (uint64_t)(w0 + threadIdx.x) * 32);
-                while (word) {
-                    const uint32_t b = __ffs(word) - 1;
-                    word &= word - 1;
-                    s_list[k++] = rbase + b;
+        const uint32_t n_seg = (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;
+        for (uint32_t sg = 0; sg < n_seg;) {
+            // (a) expand mask words into the ascending row list: 64 words at a time, or -- element-level
+            // inputs -- as many consecutive 64-word segments as together hold at most SEG_ROWS rows (a
+            // uniformly sparse tile is then one pass instead of sixteen)
+            uint32_t w0 = sg * SEG_WORDS, w1 = min(w0 + SEG_WORDS, g.tile_words), total;
+            if (ELEM) {
+                uint32_t merged = s_seg[sg];   // uniform: LDS
+                ++sg;
+                while (sg < n_seg && merged + s_seg[sg] <= SEG_ROWS) merged += s_seg[sg++];
+                w1 = min(sg * SEG_WORDS, g.tile_words);
+                if (merged == 0) continue;
+                const uint32_t wpt = (w1 - w0 + SCATTER_THREADS - 1) / SCATTER_THREADS;   // consecutive words per thread
+                const uint32_t wa = min(w0 + threadIdx.x * wpt, w1), wb = min(wa + wpt, w1);
+                uint32_t mine = 0;
+                for (uint32_t wi = wa; wi < wb; ++wi) mine += __popc(s_mask[wi]);
+                uint32_t k = block_exclusive_scan(mine, s_tmp, &total);
+                for (uint32_t wi = wa; wi < wb; ++wi) {
+                    uint32_t word = s_mask[wi];
+                    const uint32_t rbase = (uint32_t)(row0 + (uint64_t)wi * 32);
+                    while (word) {
+                        const uint32_t b = __ffs(word) - 1;
+                        word &= word - 1;
+                        s_list[k++] = rbase + b;
+                    }
+                }
+            } else {
+                ++sg;
+                uint32_t word = 0;
+                if (threadIdx.x < SEG_WORDS && w0 + threadIdx.x < g.tile_words) word = gmask[w0 + threadIdx.x];
+                const uint32_t pre = block_exclusive_scan(threadIdx.x < SEG_WORDS ? __popc(word) : 0u, s_tmp, &total);
+                if (total == 0) continue;   // uniform: total comes from LDS
+                if (threadIdx.x < SEG_WORDS) {
+                    uint32_t k = pre;
+                    const uint32_t rbase = (uint32_t)(row0 + (uint64_t)(w0 + threadIdx.x) * 32);
+                    while (word) {
+                        const uint32_t b = __ffs(word) - 1;
+                        word &= word - 1;
+                        s_list[k++] = rbase + b;
+                    }
                 }
             }
             __syncthreads();
