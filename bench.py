@@ -329,6 +329,20 @@ def main():
     det_ms, det_n = prof.get("detect_kernel", (0.0, 0))
     det_avg_s = det_ms / max(det_n, 1) / 1e3
 
+    # per-step and per-stage times from events on the launch stream, in a pass of its own
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for e0, e1, e2 in evs:
+        e0.record()
+        zen.zen_encode_batch(ctx, grads, encs, ws_enc)
+        e1.record()
+        zen.zen_aggregate_batch(ctx, encs, aggs, max_in, ws_agg)
+        e2.record()
+    torch.cuda.synchronize()
+    enc_ms = sorted(e0.elapsed_time(e1) for e0, e1, _ in evs)
+    agg_ms = sorted(e1.elapsed_time(e2) for _, e1, e2 in evs)
+    step_ms = sorted(e0.elapsed_time(e2) for e0, _, e2 in evs)
+    med = lambda v: v[len(v) // 2]
+
     U = [int(a.count.item()) for a in aggs]
     dense_bytes = wl.n_workers * wl.dense_bytes
     idx_bytes = (wl.n_rows // 8) if wl.bitmap else None
@@ -391,6 +405,8 @@ def main():
         "config": {"workload": wl.name, "config_id": wl.config_id, "n_rows": wl.n_rows, "row_dim": D,
                    "n_workers": wl.n_workers, "n_parts": n, "index_format": "bitmap" if wl.bitmap else "coo",
                    "nnz_total": int(sum(nnz)), "unique_total": int(sum(U)), "max_in_rows": max_in},
+        "ms_per_step_events": {"median": round(med(step_ms), 4), "min": round(step_ms[0], 4),
+                               "encode_median": round(med(enc_ms), 4), "aggregate_median": round(med(agg_ms), 4)},
         "nnz_per_s": round(sum(nnz) / t, 1),
         "algorithmic_bytes": int(b_alg),
         "hbm_frac_whole_path": round(b_alg / t / (HBM_PEAK_GBS * 1e9), 4),
