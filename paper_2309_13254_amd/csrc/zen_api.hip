@@ -425,7 +425,7 @@ static const char *const kKernelNames[K_COUNT] = {
     "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel", "encode_small_kernel", "gather_rows_kernel",
     "pull_encode_kernel", "pull_zero_kernel", "pull_count_kernel", "pull_scan_kernel", "pull_place_kernel",
     "pull_place_coo_kernel", "hm_clear_kernel", "hm_insert_kernel", "hm_extract_kernels",
-    "stats_kernel", "topk_select_kernels"};
+    "stats_kernel"};
 
 static void prof_release(zen_ctx *ctx)
 {
