@@ -350,8 +350,11 @@ struct BitmapTables {
 
 // ELEM = (row_dim == 1): values are single floats fetched ahead of the ranking loop; otherwise rows
 // are copied after it.  Two instantiations so that each keeps its own register budget.
+#ifndef ZEN_SCATTER_WAVES
+#define ZEN_SCATTER_WAVES 6   // waves per SIMD the register allocation must allow: 6 measured best (8 spills)
+#endif
 template <bool ELEM>
-__global__ void __launch_bounds__(SCATTER_THREADS)
+__global__ void __launch_bounds__(SCATTER_THREADS, ZEN_SCATTER_WAVES)
 scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
                const uint32_t *tlist_base, uint64_t tlist_stride, BitmapTables bt)
