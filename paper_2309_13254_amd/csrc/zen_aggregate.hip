@@ -408,25 +408,41 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
 }
 
 // A3, large tables, step 1: compact the occupied slots (any order) into uniq[server][0..U).
+// A block first counts the occupied slots of all its iterations and moves the server's counter once
+// (the counter is one address for the whole chip: one atomic per wave made this kernel atomic-bound),
+// then reads its slots again (they are in the L2) and hands out positions through an LDS counter.
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_compact_kernel(const uint32_t *keys_base, uint64_t table_cap, uint32_t *uniq_base, uint64_t uniq_stride,
                    uint32_t *counters_base)
 {
+    __shared__ uint32_t s_total, s_base, s_cur;
     const uint32_t server = blockIdx.y;
     const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
     uint32_t *uniq = uniq_base + (uint64_t)server * uniq_stride;
     uint32_t *counters = counters_base + server * 16;
     if (counters[CNT_SKIP]) return;
+    if (threadIdx.x == 0) { s_total = 0; s_cur = 0; }
+    __syncthreads();
     // table_cap is a multiple of the block size: every wave runs the same number of iterations
+    uint32_t mine = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < table_cap;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        mine += (uint32_t)__popcll(ballot(keys[i] != ZEN_EMPTY_KEY));   // the same in every lane of the wave
+    if (lane_id() == 0 && mine) atomicAdd(&s_total, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) s_base = s_total ? atomicAdd(&counters[CNT_UNIQUE], s_total) : 0u;
+    __syncthreads();
+    if (s_total == 0) return;
+    const uint32_t block_base = s_base;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < table_cap;
          i += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t k = keys[i];
         const bool occ = k != ZEN_EMPTY_KEY;
         const uint64_t m = ballot(occ);
         uint32_t base = 0;
-        if (lane_id() == 0 && m) base = atomicAdd(&counters[CNT_UNIQUE], (uint32_t)__popcll(m));
+        if (lane_id() == 0 && m) base = atomicAdd(&s_cur, (uint32_t)__popcll(m));
         base = __shfl(base, 0, ZEN_WAVE);
-        if (occ) uniq[base + mbcnt(m)] = k;
+        if (occ) uniq[block_base + base + mbcnt(m)] = k;
     }
 }
 
@@ -778,7 +794,8 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         uint32_t *uniq = (uint32_t *)(ws + L.uniq_off);
         uint32_t *hist = (uint32_t *)(ws + L.sorthist_off);
         const uint64_t ustride = 2 * L.uniq_cap, hstride = L.sort_blocks * 256;
-        uint64_t cblocks = cap / AGG_THREADS;
+        uint64_t cblocks = cap / AGG_THREADS / 8;   // eight iterations per block, one global atomic per block
+        if (cblocks < 1) cblocks = 1;
         if (cblocks > 2048) cblocks = 2048;
         {
             ProfScope prof(ctx, K_AGG_COMPACT, s);
