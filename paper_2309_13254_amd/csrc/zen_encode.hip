@@ -272,9 +272,19 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
     const uint32_t t0 = active ? min(grp * per, g.n_tiles) : 0;
     const uint32_t t1 = active ? min(t0 + per, g.n_tiles) : 0;
 
+    // Batches of 8 tiles: the loads of a batch are independent and issued together (one at a time,
+    // this walk is a chain of memory round trips and the kernel runs one block per worker).
     uint32_t sum = 0;
-    for (uint32_t t = t0; t < t1; ++t)
-        if (!g.sparse_mask || tflag[t]) sum += hist[(uint64_t)t * n + p];
+    for (uint32_t tb = t0; tb < t1; tb += 8) {
+        uint32_t h[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t t = tb + u;
+            h[u] = (t < t1 && (!g.sparse_mask || tflag[t])) ? hist[(uint64_t)t * n + p] : 0u;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) sum += h[u];
+    }
     if (active) s_part[grp * n + p] = sum;
     __syncthreads();
     // exclusive scan over groups for each p (Hillis-Steele along the group axis, all p at once)
@@ -306,12 +316,20 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
     for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) outs.offsets[worker][i] = s_off[i];
     if (active) {
         uint32_t run = s_off[p] + my_prefix;
-        for (uint32_t t = t0; t < t1; ++t) {
-            if (g.sparse_mask && !tflag[t]) continue;
-            const uint64_t a = (uint64_t)t * n + p;
-            const uint32_t h = hist[a];
-            hist[a] = run;
-            run += h;
+        for (uint32_t tb = t0; tb < t1; tb += 8) {
+            uint32_t h[8];
+            bool on[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t t = tb + u;
+                on[u] = t < t1 && (!g.sparse_mask || tflag[t]);
+                h[u] = on[u] ? hist[(uint64_t)t * n + p] : 0u;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                if (on[u]) hist[(uint64_t)(tb + u) * n + p] = run;
+                run += h[u];
+            }
         }
     }
     // For the scatter of element-level inputs: ascending list of the worker's non-empty tiles (all
