@@ -227,34 +227,12 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
     if (!hist_base) return;   // the one-block-per-worker partition path hashes the rows itself
     // owner histogram of the tile's non-zero rows: walk the mask words, most of them are zero
     if (g.tile_words >= blockDim.x) {
-        // A wave takes 64 consecutive mask words.  Non-zeros in runs (a few full words, the rest empty):
-        // the non-zero words are worked through two at a time, lane b of each half testing bit b.
-        // Sparse words (none half full): one word per lane, a loop over its bits.
-        const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-        for (uint32_t w0 = wave * ZEN_WAVE; w0 < g.tile_words; w0 += nw * ZEN_WAVE) {
-            const uint32_t word = w0 + lane < g.tile_words ? s_mask[w0 + lane] : 0u;
-            uint64_t todo = ballot(word != 0);
-            if (todo == 0) continue;
-            if (ballot(__popc(word) >= 16) == 0) {   // no word is half full: fewer than 16 trips with a lane per word
-                uint32_t wd = word;
-                while (wd) {
-                    const uint32_t b = __ffs(wd) - 1;
-                    wd &= wd - 1;
-                    atomicAdd(&s_hist[owner_of((uint32_t)(row0 + (uint64_t)(w0 + lane) * 32 + b), g.seed, g.n_parts,
-                                               g.pow2_mask)], 1u);
-                }
-                continue;
-            }
-            while (todo) {   // uniform
-                const uint32_t a = (uint32_t)__ffsll((unsigned long long)todo) - 1;
-                todo &= todo - 1;
-                uint32_t b = ZEN_WAVE;
-                if (todo) { b = (uint32_t)__ffsll((unsigned long long)todo) - 1; todo &= todo - 1; }
-                const uint32_t src = lane < 32 ? a : b;
-                const uint32_t w = __shfl(word, (int)(src & (ZEN_WAVE - 1)), ZEN_WAVE);
-                if (src < ZEN_WAVE && ((w >> (lane & 31u)) & 1u))
-                    atomicAdd(&s_hist[owner_of((uint32_t)(row0 + (uint64_t)(w0 + src) * 32 + (lane & 31u)), g.seed,
-                                               g.n_parts, g.pow2_mask)], 1u);
+        for (uint32_t wi = threadIdx.x; wi < g.tile_words; wi += blockDim.x) {
+            uint32_t word = s_mask[wi];
+            while (word) {
+                const uint32_t b = __ffs(word) - 1;
+                word &= word - 1;
+                atomicAdd(&s_hist[owner_of((uint32_t)(row0 + wi * 32 + b), g.seed, g.n_parts, g.pow2_mask)], 1u);
             }
         }
     } else {
