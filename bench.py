@@ -270,6 +270,9 @@ def main():
     ap.add_argument("--hashmem", action="store_true",
                     help="extra leg: the paper's parameter study of Algorithm 1's hash memory (r1, k) on a synthetic "
                          "214 M-element tensor, next to the histogram/scan/scatter encode of the same tensor")
+    ap.add_argument("--input-sets", type=int, default=0,
+                    help="copies of the input buffers the steps rotate through, so that no step finds its inputs in "
+                         "the last-level cache (default: enough for 2 GiB of distinct inputs, at most 16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain 1 GiB copy kernel three times (reference for hardware "
                          "byte counters under rocprofv3 --pmc)")
@@ -308,8 +311,17 @@ def main():
     aggs = [zen.alloc_aggregated(ctx, max_in) for _ in range(n)]
     ws_agg = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, n, max_in))
 
+    # Rotating input copies: a small workload's inputs would otherwise stay in the 256 MB last-level cache
+    # between steps.  The copies hold the same values at other addresses, so every step's result is the same.
+    total_in = wl.n_workers * wl.dense_bytes
+    n_sets = args.input_sets if args.input_sets > 0 else max(1, min(16, -(-(2 << 30) // total_in)))
+    grad_sets = [grads] + [[g.clone() for g in grads] for _ in range(n_sets - 1)]
+    step_no = [0]
+
     def step():
-        zen.zen_encode_batch(ctx, grads, encs, ws_enc)
+        gs = grad_sets[step_no[0] % n_sets]
+        step_no[0] += 1
+        zen.zen_encode_batch(ctx, gs, encs, ws_enc)
         zen.zen_aggregate_batch(ctx, encs, aggs, max_in, ws_agg)
 
     for _ in range(args.warmup):
@@ -331,9 +343,9 @@ def main():
 
     # per-step and per-stage times from events on the launch stream, in a pass of its own
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for e0, e1, e2 in evs:
+    for i, (e0, e1, e2) in enumerate(evs):
         e0.record()
-        zen.zen_encode_batch(ctx, grads, encs, ws_enc)
+        zen.zen_encode_batch(ctx, grad_sets[i % n_sets], encs, ws_enc)
         e1.record()
         zen.zen_aggregate_batch(ctx, encs, aggs, max_in, ws_agg)
         e2.record()
@@ -359,6 +371,9 @@ def main():
         torch.cuda.synchronize()
         kernel_ms = {k: round(v[0] / 5, 4) for k, v in zen.zen_profile_collect(ctx).items()}
         zen.zen_profile_enable(ctx, 0, 0)
+
+    grad_sets = None      # the extra legs below use the first set only
+    torch.cuda.empty_cache()
 
     pull = None
     if args.pull:
@@ -404,7 +419,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "config_id": wl.config_id, "n_rows": wl.n_rows, "row_dim": D,
                    "n_workers": wl.n_workers, "n_parts": n, "index_format": "bitmap" if wl.bitmap else "coo",
-                   "nnz_total": int(sum(nnz)), "unique_total": int(sum(U)), "max_in_rows": max_in},
+                   "nnz_total": int(sum(nnz)), "unique_total": int(sum(U)), "max_in_rows": max_in,
+                   "input_sets": n_sets},
         "ms_per_step_events": {"median": round(med(step_ms), 4), "min": round(step_ms[0], 4),
                                "encode_median": round(med(enc_ms), 4), "aggregate_median": round(med(agg_ms), 4)},
         "nnz_per_s": round(sum(nnz) / t, 1),
