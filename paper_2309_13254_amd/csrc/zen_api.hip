@@ -171,6 +171,7 @@ zen_status zen_ctx_destroy(zen_ctx *ctx)
     if (ctx->d_dom_tile_base) (void)hipFree(ctx->d_dom_tile_base);
     if (ctx->d_bm_word_off) (void)hipFree(ctx->d_bm_word_off);
     if (ctx->d_pull_base) (void)hipFree(ctx->d_pull_base);
+    if (ctx->d_group_base) (void)hipFree(ctx->d_group_base);
     free(ctx->h_bm_word_off);
     free(ctx->h_dom_sizes);
     delete ctx;

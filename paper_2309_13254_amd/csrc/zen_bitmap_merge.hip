@@ -84,7 +84,8 @@ bm_scan_kernel(BmArgs a, uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_ba
         uint32_t sum = 0;
         for (uint32_t c = c0; c < c1; ++c) sum += r[c];
         const uint32_t inc = wave_inclusive_scan(sum);
-        uint32_t run = inc - sum;
+        // a part's prefixes start at the first value of partition p inside the part's value array
+        uint32_t run = inc - sum + ((row < a.n_in && !a.single) ? a.bounds[row][p] : 0u);
         for (uint32_t c = c0; c < c1; ++c) { const uint32_t t = r[c]; r[c] = run; run += t; }
         const uint32_t total = __shfl(inc, ZEN_WAVE - 1, ZEN_WAVE);
         if (lane == 0) {
@@ -130,7 +131,7 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
     }
     const uint32_t d0 = dom_offsets[p], n_dom = dom_offsets[p + 1] - d0, n_words = (n_dom + 31) >> 5;
     if (chunk * BM_CHUNK_WORDS >= n_words) return;
-    const uint32_t *pre = cnt + ((uint64_t)server * (ZEN_MAX_BATCH + 1)) * n_chunks;   // exclusive prefixes
+    const uint32_t *pre = cnt + ((uint64_t)server * (ZEN_MAX_BATCH + 1)) * n_chunks;   // exclusive prefixes (+ value base)
     const uint64_t cap_rows = outs.cap_rows[server];
     uint32_t *__restrict__ out_idx = outs.indices[server];
     float *__restrict__ out_val = out_values.v[server];
@@ -191,7 +192,7 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
             const uint32_t t_wave = __shfl(inc, ZEN_WAVE - 1, ZEN_WAVE);
             s_word[lane] = word;
             s_ex[lane] = inc - c;
-            uint32_t vbase = pre[(uint64_t)w * n_chunks + chunk] + (a.single ? 0u : a.bounds[w][p]);
+            uint32_t vbase = pre[(uint64_t)w * n_chunks + chunk];
             for (uint32_t v = 0; v < wave; ++v) vbase += s_wtot[w * 4 + v];
             const float *vals = src_values.v[w] + vbase;
             __builtin_amdgcn_wave_barrier();
@@ -215,6 +216,29 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
         }
         // write out the wave's output range: indices from the sorted domain, values from LDS
         const uint32_t k0 = chunk * BM_CHUNK_WORDS + wave * ZEN_WAVE;
+        const uint64_t nzu = ballot(uni != 0);
+        if ((uint32_t)__popcll(nzu) < 8 * ((u_wave + ZEN_WAVE - 1) / ZEN_WAVE)) {
+            uint64_t todo = nzu;
+            while (todo) {   // uniform; as above: two union words per trip, a lane per bit
+                const uint32_t wa = (uint32_t)__ffsll((unsigned long long)todo) - 1;
+                todo &= todo - 1;
+                uint32_t wb = ZEN_WAVE;
+                if (todo) { wb = (uint32_t)__ffsll((unsigned long long)todo) - 1; todo &= todo - 1; }
+                const uint32_t src = lane < 32 ? wa : wb, bit = lane & 31u;
+                if (src < ZEN_WAVE) {
+                    const uint32_t ww = s_uni[src];
+                    if ((ww >> bit) & 1u) {
+                        const uint32_t i = s_uex[src] + __popc(ww & ((1u << bit) - 1u));
+                        const uint64_t orow = (uint64_t)ubase_chunk + ubase_wave + i;
+                        if (orow < cap_rows) {
+                            out_idx[orow] = domain[d0 + (k0 + src) * 32 + bit];
+                            out_val[orow] = acc[i];
+                        }
+                    }
+                }
+            }
+            return;
+        }
         for (uint32_t i = lane; i < u_wave; i += ZEN_WAVE) {
             uint32_t lo = 0;
 #pragma unroll
@@ -258,7 +282,6 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
                 myword = part_words(a, lane, p, word_off)[kw];
                 mypos = pre[(uint64_t)lane * n_chunks + chunk] + s_pre[lane * BM_CHUNK_WORDS + wi];
                 for (uint32_t v = 0; v < src_wave; ++v) mypos += s_wtot[lane * 4 + v];
-                mypos += a.single ? 0u : a.bounds[lane][p];
             }
             uint32_t uni = myword;
 #pragma unroll

@@ -24,6 +24,7 @@ static constexpr int SCATTER_THREADS = 256;
 static constexpr int SCAN_THREADS = 1024;
 static constexpr int SEG_WORDS = 64;              // mask words expanded per scatter segment
 static constexpr int SEG_ROWS = SEG_WORDS * 32;   // 2048
+static constexpr int GROUP_WORDS = ZEN_GROUP_ROWS / 32;   // 16 mask words: the unit the element-level scatter counts rows in
 
 __device__ __forceinline__ u32x4 load_stream(const u32x4 *p)
 {
@@ -364,6 +365,8 @@ struct BitmapTables {
     const uint32_t *rank;       // [n_rows]
     const uint32_t *tile_base;  // [n_tiles+1][n_parts]
     const uint32_t *word_off;   // [n_parts+1]
+    const uint32_t *group_base; // [n_tiles * tile_rows / ZEN_GROUP_ROWS + 1][n_parts] rows of II_p below each group of
+                                // ZEN_GROUP_ROWS rows, or NULL
 };
 
 // ELEM = (row_dim == 1): values are single floats fetched ahead of the ranking loop; otherwise rows
@@ -371,8 +374,11 @@ struct BitmapTables {
 #ifndef ZEN_SCATTER_WAVES
 #define ZEN_SCATTER_WAVES 6   // waves per SIMD the register allocation must allow: 6 measured best (8 spills)
 #endif
+#ifndef ZEN_SCATTER_WAVES_ELEM
+#define ZEN_SCATTER_WAVES_ELEM 5   // element-level: the staged output keeps more values in registers
+#endif
 template <bool ELEM>
-__global__ void __launch_bounds__(SCATTER_THREADS, ZEN_SCATTER_WAVES)
+__global__ void __launch_bounds__(SCATTER_THREADS, ELEM ? ZEN_SCATTER_WAVES_ELEM : ZEN_SCATTER_WAVES)
 scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
                const uint32_t *tlist_base, uint64_t tlist_stride, BitmapTables bt)
@@ -383,11 +389,14 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     const uint32_t n_waves = blockDim.x >> 6;
     uint32_t *s_cnt = s_run + n;                     // [n_waves][n]
     uint32_t *s_list = s_cnt + n_waves * n;                // [SEG_ROWS] row ids of the segment, ascending
-    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row (row copies only)
-    uint32_t *s_tmp = s_pos + (ELEM ? 0 : SEG_ROWS); // [32]
+    uint32_t *s_pos = s_list + SEG_ROWS;             // [SEG_ROWS] output position of each listed row (row copies), or the
+                                                     //            values of a fully non-zero stretch in output order
+    uint32_t *s_tmp = s_pos + SEG_ROWS;              // [32]
     uint32_t *s_mask = s_tmp + 32;                   // [tile_words] the tile's mask
-    uint32_t *s_seg = s_mask + g.tile_words;         // [ceil(tile_words / SEG_WORDS)] rows of each 64-word segment
-    uint32_t *s_b0 = s_seg + (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;   // bitmap only: [n] first bit of (tile, p)
+    uint32_t *s_seg = s_mask + g.tile_words;         // [ceil(tile_words / GROUP_WORDS)] rows of each 16-word group
+    uint32_t *s_delta = s_seg + (g.tile_words + GROUP_WORDS - 1) / GROUP_WORDS;   // [n] \ element-level: per-partition terms
+    uint32_t *s_goff = s_delta + n;                  // [n] / that turn a rank into an LDS slot and an output position
+    uint32_t *s_b0 = s_goff + n;                     // bitmap only: [n] first bit of (tile, p)
     uint32_t *s_b1 = s_b0 + n;                       //              [n] end bit of (tile, p)
     uint32_t *s_boff = s_b1 + n;                     //              [n+1] LDS word offset of p's range
     uint32_t *s_bm = s_boff + n + 1;                 //              [tile_words + 2n] assembled words
@@ -398,6 +407,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     uint32_t *__restrict__ out_bm = outs.bitmap[worker];
     const uint64_t cap = outs.cap_rows[worker];
     const bool bitmap = g.bitmap && out_bm != nullptr;
+    const bool fast_ok = ELEM && bt.group_base != nullptr && bt.rank != nullptr;
 
     for (uint32_t i = threadIdx.x; i < n_waves * n; i += blockDim.x) s_cnt[i] = 0;
 
@@ -440,13 +450,13 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 #pragma unroll
                 for (uint32_t q = 0; q < 8; ++q) {
                     const uint32_t i = (q0 + q) * SCATTER_THREADS + threadIdx.x;
-                    const uint32_t first = i - lane_id();      // the wave's 64 words are one segment
+                    const uint32_t first = i - lane_id();      // the wave's 64 words are four groups
                     if (first >= g.tile_words) continue;       // uniform per wave
                     if (i < g.tile_words) s_mask[i] = mw[q];
-                    uint32_t seg_cnt = __popc(mw[q]);   // rows of the segment
+                    uint32_t grp_cnt = __popc(mw[q]);   // rows of the 16-word group
 #pragma unroll
-                    for (int d = 32; d > 0; d >>= 1) seg_cnt += __shfl_xor(seg_cnt, d, ZEN_WAVE);
-                    if (lane_id() == 0) s_seg[first / SEG_WORDS] = seg_cnt;
+                    for (int d = GROUP_WORDS / 2; d > 0; d >>= 1) grp_cnt += __shfl_xor(grp_cnt, d, ZEN_WAVE);
+                    if ((lane_id() & (GROUP_WORDS - 1)) == 0 && i < g.tile_words) s_seg[i / GROUP_WORDS] = grp_cnt;
                 }
             }
             nxt_tile = nxt2_tile;
@@ -494,17 +504,94 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             for (uint32_t i = threadIdx.x; i < bm_words; i += blockDim.x) s_bm[i] = 0;
         }
 
-        const uint32_t n_seg = (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;
+        const uint32_t seg_words = ELEM ? GROUP_WORDS : SEG_WORDS;
+        const uint32_t n_seg = (g.tile_words + seg_words - 1) / seg_words;
         for (uint32_t sg = 0; sg < n_seg;) {
             // (a) expand mask words into the ascending row list: 64 words at a time, or -- element-level
-            // inputs -- as many consecutive 64-word segments as together hold at most SEG_ROWS rows (a
+            // inputs -- as many consecutive 16-word groups as together hold at most SEG_ROWS rows (a
             // uniformly sparse tile is then one pass instead of sixteen)
-            uint32_t w0 = sg * SEG_WORDS, w1 = min(w0 + SEG_WORDS, g.tile_words), total;
+            uint32_t w0 = sg * seg_words, w1 = min(w0 + seg_words, g.tile_words), total;
             if (ELEM) {
                 uint32_t merged = s_seg[sg];   // uniform: LDS
+                if (fast_ok && merged == ZEN_GROUP_ROWS) {
+                    // (a') A stretch of fully non-zero groups: every row of [ra, rb) is listed, so the rows of
+                    // partition p among them are a contiguous piece of its sorted domain II_p.  Output position
+                    // = running position + (rank in II_p - rank of the stretch's first row of p); the bits
+                    // of p are one contiguous range.  No list, no ranking.
+                    // Values are first placed in LDS in output order (partition-major), then written out:
+                    // consecutive lanes then store to consecutive addresses instead of one cache line each.
+                    const uint32_t g0 = sg;
+                    do ++sg; while (sg < n_seg && s_seg[sg] == ZEN_GROUP_ROWS && sg - g0 < SEG_ROWS / ZEN_GROUP_ROWS);
+                    const uint64_t ga = (uint64_t)tile * (g.tile_rows / ZEN_GROUP_ROWS) + g0, gb = ga + (sg - g0);
+                    const uint32_t ra = (uint32_t)(row0 + (uint64_t)g0 * ZEN_GROUP_ROWS);
+                    const uint32_t cnt = (sg - g0) * ZEN_GROUP_ROWS;   // <= SEG_ROWS
+                    constexpr uint32_t FB = SEG_ROWS / SCATTER_THREADS;   // 8 rows per thread
+                    float fv[FB];
+                    uint32_t fr[FB];
+#pragma unroll
+                    for (uint32_t q = 0; q < FB; ++q) {
+                        const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                        fv[q] = 0.f;
+                        fr[q] = 0;
+                        if (i < cnt) {
+                            fr[q] = bt.rank[ra + i];
+                            if (out_val) fv[q] = grad[ra + i];
+                        }
+                    }
+                    // n <= ZEN_GROUP_MAX_PARTS <= blockDim.x: one thread per partition
+                    uint32_t fa = 0, fb = 0;
+                    if (threadIdx.x < n) {
+                        fa = bt.group_base[ga * n + threadIdx.x];
+                        fb = bt.group_base[gb * n + threadIdx.x];
+                    }
+                    uint32_t stretch_rows;
+                    const uint32_t loff = block_exclusive_scan(fb - fa, s_tmp, &stretch_rows);   // (barriers inside)
+                    if (threadIdx.x < n) {
+                        const uint32_t p = threadIdx.x, run = s_run[p];
+                        s_delta[p] = loff - fa;          // LDS slot   = s_delta[p] + rank
+                        s_goff[p] = run - loff;          // output pos = s_goff[p] + slot
+                        s_run[p] = run + (fb - fa);
+                        if (bitmap && fb > fa) {
+                            const uint32_t lw0 = s_boff[p], tw0 = s_b0[p] >> 5;   // LDS word of the tile's first word of p
+                            const uint32_t wa = fa >> 5, wb = (fb - 1) >> 5;
+                            for (uint32_t w = wa; w <= wb; ++w) {
+                                uint32_t m = 0xFFFFFFFFu;
+                                if (w == wa) m &= 0xFFFFFFFFu << (fa & 31u);
+                                if (w == wb) m &= 0xFFFFFFFFu >> (31u - ((fb - 1) & 31u));
+                                s_bm[lw0 + (w - tw0)] |= m;
+                            }
+                        }
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (uint32_t q = 0; q < FB; ++q) {
+                        const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                        if (i < cnt) {
+                            const uint32_t row = ra + i;
+                            const uint32_t p = owner_of(row, g.seed, n, g.pow2_mask);
+                            const uint32_t slot = s_delta[p] + fr[q];
+                            const uint32_t pos = s_goff[p] + slot;
+                            if (slot < SEG_ROWS) {       // always, for consistent tables
+                                s_list[slot] = pos;
+                                s_pos[slot] = __float_as_uint(fv[q]);
+                            }
+                            if (out_idx && pos < cap) out_idx[pos] = row;
+                        }
+                    }
+                    __syncthreads();
+                    if (out_val) {
+                        for (uint32_t i = threadIdx.x; i < cnt; i += SCATTER_THREADS) {
+                            const uint32_t pos = s_list[i];
+                            if (pos < cap) out_val[pos] = __uint_as_float(s_pos[i]);
+                        }
+                    }
+                    __syncthreads();   // s_list, s_pos, s_delta, s_goff, s_run are rewritten by what follows
+                    continue;
+                }
                 ++sg;
-                while (sg < n_seg && merged + s_seg[sg] <= SEG_ROWS) merged += s_seg[sg++];
-                w1 = min(sg * SEG_WORDS, g.tile_words);
+                while (sg < n_seg && !(fast_ok && s_seg[sg] == ZEN_GROUP_ROWS) && merged + s_seg[sg] <= SEG_ROWS)
+                    merged += s_seg[sg++];
+                w1 = min(sg * seg_words, g.tile_words);
                 if (merged == 0) continue;
                 const uint32_t wpt = (w1 - w0 + SCATTER_THREADS - 1) / SCATTER_THREADS;   // consecutive words per thread
                 const uint32_t wa = min(w0 + threadIdx.x * wpt, w1), wb = min(wa + wpt, w1);
@@ -536,13 +623,17 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     }
                 }
             }
+            if (ELEM)
+                for (uint32_t p = threadIdx.x; p < n; p += blockDim.x) s_delta[p] = s_run[p];   // positions at the segment's start
             __syncthreads();
             // (b) rank, write indices, set bitmap bits.  row_dim == 1: the value and the bitmap rank of
             // up to PF chunks are fetched first so the barrier-paced ranking loop does not wait on them.
             constexpr uint32_t PF = SEG_ROWS / SCATTER_THREADS;   // 8
             const bool prefetch = ELEM;
             float pf_val[PF];
-            uint32_t pf_bit[PF];
+            uint32_t pf_bit[PF], pf_pk[PF];
+#pragma unroll
+            for (uint32_t q = 0; q < PF; ++q) pf_pk[q] = 0;
             if (ELEM) {
 #pragma unroll
                 for (uint32_t q = 0; q < PF; ++q) {
@@ -567,16 +658,67 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 const uint32_t p = valid ? owner_of(row, g.seed, n, g.pow2_mask) : 0u;
                 const uint32_t pos = block_stable_rank(valid, p, g.part_bits, n, s_run, s_cnt);
                 if (valid) {
-                    if (pos < cap) {
+                    if (ELEM) {
+                        // partition and position inside the segment's share of it (< SEG_ROWS = 2^11)
+                        pf_pk[q] = (p << 11) | (pos - s_delta[p]);
+                    } else if (pos < cap) {
                         if (out_idx) out_idx[pos] = row;
-                        if (ELEM && out_val) out_val[pos] = pf_val[q];
-                        if (!ELEM) s_pos[i] = pos;
-                    } else if (!ELEM) {
+                        s_pos[i] = pos;
+                    } else {
                         s_pos[i] = 0xFFFFFFFFu;
                     }
                     if (bitmap) {
                         const uint32_t bit = prefetch ? pf_bit[q] : bt.rank[row];
                         atomicOr(&s_bm[s_boff[p] + (bit >> 5) - (s_b0[p] >> 5)], 1u << (bit & 31));
+                    }
+                }
+            }
+            if (ELEM) {
+                // (b') Indices and values go out in output order: they are first placed in LDS partition-major
+                // (slot = start of the partition's share + position inside it), then consecutive lanes store
+                // to consecutive addresses -- not one cache line per lane, which is what bounds this kernel.
+                __syncthreads();                              // the last chunk's update of s_run
+                const uint32_t per = (n + blockDim.x - 1) / blockDim.x;   // consecutive partitions per thread
+                const uint32_t p0 = min(threadIdx.x * per, n), p1 = min(p0 + per, n);
+                uint32_t mine = 0, seg_total;
+                for (uint32_t p = p0; p < p1; ++p) mine += s_run[p] - s_delta[p];
+                uint32_t off = block_exclusive_scan(mine, s_tmp, &seg_total);
+                for (uint32_t p = p0; p < p1; ++p) { s_goff[p] = off; off += s_run[p] - s_delta[p]; }
+                __syncthreads();
+                if (out_idx) {
+#pragma unroll
+                    for (uint32_t q = 0; q < PF; ++q) {
+                        const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                        if (i < total) s_pos[s_goff[pf_pk[q] >> 11] + (pf_pk[q] & 2047u)] = s_list[i];
+                    }
+                    __syncthreads();
+                }
+#pragma unroll
+                for (uint32_t q = 0; q < PF; ++q) {           // the row list is no longer needed: positions replace it
+                    const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                    if (i < total) {
+                        const uint32_t p = pf_pk[q] >> 11, l = pf_pk[q] & 2047u;
+                        s_list[s_goff[p] + l] = s_delta[p] + l;
+                    }
+                }
+                __syncthreads();
+                if (out_idx) {
+                    for (uint32_t i = threadIdx.x; i < total; i += SCATTER_THREADS) {
+                        const uint32_t pos = s_list[i];
+                        if (pos < cap) out_idx[pos] = s_pos[i];
+                    }
+                    __syncthreads();
+                }
+                if (out_val) {
+#pragma unroll
+                    for (uint32_t q = 0; q < PF; ++q) {
+                        const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
+                        if (i < total) s_pos[s_goff[pf_pk[q] >> 11] + (pf_pk[q] & 2047u)] = __float_as_uint(pf_val[q]);
+                    }
+                    __syncthreads();
+                    for (uint32_t i = threadIdx.x; i < total; i += SCATTER_THREADS) {
+                        const uint32_t pos = s_list[i];
+                        if (pos < cap) out_val[pos] = __uint_as_float(s_pos[i]);
                     }
                 }
             }
@@ -827,7 +969,7 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
                           hipStream_t s)
 {
     const Geometry &g = ctx->geo;
-    BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off};
+    BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off, ctx->d_group_base};
     if (g.bitmap) {
         // the bitmap is assembled with OR: clear it first (a fill kernel, not a memset node)
         for (uint32_t w = 0; w < batch; ++w) {
@@ -838,8 +980,8 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
     }
     ProfScope prof(ctx, K_SCATTER, s);
     const uint32_t threads = scatter_threads(g);
-    size_t words = (1 + threads / 64) * (size_t)g.n_parts + (g.row_dim == 1 ? 1 : 2) * SEG_ROWS + 32 + g.tile_words +
-                   (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;
+    size_t words = (3 + threads / 64) * (size_t)g.n_parts + 2 * SEG_ROWS + 32 + g.tile_words +
+                   (g.tile_words + GROUP_WORDS - 1) / GROUP_WORDS;
     if (g.bitmap) words += 3 * (size_t)g.n_parts + 1 + g.tile_words + 2 * (size_t)g.n_parts;
     if (words * 4 > 160 * 1024) return hipErrorInvalidValue;
     if (words * 4 > 48 * 1024) {   // beyond the default dynamic LDS limit
@@ -1027,7 +1169,7 @@ hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const Encode
                                char *ws, const EncodeLayout &L, hipStream_t s)
 {
     const Geometry &g = ctx->geo;
-    BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off};
+    BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off, ctx->d_group_base};
     uint64_t max_cap = 1;
     for (uint32_t w = 0; w < batch; ++w) {
         if (outs.cap_rows[w] > max_cap) max_cap = outs.cap_rows[w];
@@ -1164,8 +1306,8 @@ hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info
     if ((e = hipGetLastError()) != hipSuccess) return e;
     GradPtrs grads;
     memset(&grads, 0, sizeof(grads));
-    BitmapTables bt{nullptr, nullptr, nullptr};
-    const size_t words = 5 * (size_t)g.n_parts + SEG_ROWS + 32 + g.tile_words + (g.tile_words + SEG_WORDS - 1) / SEG_WORDS;
+    BitmapTables bt{nullptr, nullptr, nullptr, nullptr};
+    const size_t words = 7 * (size_t)g.n_parts + 2 * SEG_ROWS + 32 + g.tile_words + (g.tile_words + GROUP_WORDS - 1) / GROUP_WORDS;
     if (words * 4 > 160 * 1024) return hipErrorInvalidValue;
     if (words * 4 > 48 * 1024) {
         (void)hipFuncSetAttribute((const void *)scatter_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

@@ -5,6 +5,11 @@
 #include <stdint.h>
 #include "../../include/zen.h"
 
+// Element-level hash-bitmap encodes: rows per group in which a fully non-zero stretch is recognised, and the
+// most partitions the per-group rank table is kept for.
+#define ZEN_GROUP_ROWS 512u
+#define ZEN_GROUP_MAX_PARTS 128u
+
 namespace zen {
 
 enum DetectMode : uint32_t {
@@ -124,6 +129,8 @@ struct zen_ctx {
     uint64_t max_dom_words;    // largest per-partition bitmap, in words
     uint32_t small_encode;     // 1: few-row encodes take the one-block-per-worker partition path
     uint32_t *d_pull_base;     // element-level BITMAP contexts: [ceil(n_rows/8192)+1][n_parts] rows of II_p below each tile
+    uint32_t *d_group_base;    // same at ZEN_GROUP_ROWS granularity: [n_tiles * tile_rows / ZEN_GROUP_ROWS + 1][n_parts]
+                               // (element-level BITMAP contexts with few partitions; NULL otherwise)
 };
 
 namespace zen {

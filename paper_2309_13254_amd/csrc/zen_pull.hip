@@ -340,15 +340,15 @@ pull_place_rows_kernel(PullSrc a, uint64_t decoded_mask, const uint32_t *cnt, ui
 // so no zero fill and no scattered 4-byte stores to HBM.
 // ------------------------------------------------------------------------------------------------
 
-// base[t][p] = number of rows of II_p below row t * PULL_TILE_ROWS (built once per context).
+// base[t][p] = number of rows of II_p below row t * step_rows (built once per context).
 __global__ void pull_base_kernel(const uint32_t *domain, const uint32_t *dom_offsets, uint32_t n_parts,
-                                 uint32_t n_tiles, uint64_t n_rows, uint32_t *base)
+                                 uint32_t n_tiles, uint64_t n_rows, uint32_t *base, uint32_t step_rows)
 {
     const uint64_t total = ((uint64_t)n_tiles + 1) * n_parts;
     for (uint64_t id = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total;
          id += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t p = (uint32_t)(id % n_parts), t = (uint32_t)(id / n_parts);
-        const uint64_t key = min((uint64_t)t * PULL_TILE_ROWS, n_rows);
+        const uint64_t key = min((uint64_t)t * step_rows, n_rows);
         const uint32_t *dom = domain + dom_offsets[p];
         uint32_t lo = 0, hi = dom_offsets[p + 1] - dom_offsets[p];
         while (lo < hi) {
@@ -555,9 +555,23 @@ hipError_t build_pull_tables(zen_ctx *ctx, hipStream_t s)
     uint64_t blocks = (entries + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     pull_base_kernel<<<(uint32_t)blocks, 256, 0, s>>>(ctx->d_domain, ctx->d_dom_offsets, g.n_parts, (uint32_t)n_tiles,
-                                                      g.n_rows, ctx->d_pull_base);
+                                                      g.n_rows, ctx->d_pull_base, PULL_TILE_ROWS);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    // The same table at the granularity the encode's scatter recognises fully non-zero stretches at
+    // (n_parts * 4 bytes per ZEN_GROUP_ROWS rows: kept to at most one byte per row).
+    if (g.n_parts <= ZEN_GROUP_MAX_PARTS && g.tile_rows % ZEN_GROUP_ROWS == 0) {
+        const uint64_t n_groups = (uint64_t)g.n_tiles * (g.tile_rows / ZEN_GROUP_ROWS);
+        const uint64_t gentries = (n_groups + 1) * g.n_parts;
+        e = hipMalloc(&ctx->d_group_base, gentries * 4);
+        if (e != hipSuccess) return e;
+        blocks = (gentries + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        pull_base_kernel<<<(uint32_t)blocks, 256, 0, s>>>(ctx->d_domain, ctx->d_dom_offsets, g.n_parts,
+                                                          (uint32_t)n_groups, g.n_rows, ctx->d_group_base, ZEN_GROUP_ROWS);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     return hipStreamSynchronize(s);
 }
 
