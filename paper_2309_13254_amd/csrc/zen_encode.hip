@@ -506,14 +506,30 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 
         const uint32_t seg_words = ELEM ? GROUP_WORDS : SEG_WORDS;
         const uint32_t n_seg = (g.tile_words + seg_words - 1) / seg_words;
+        // element-level: the groups' row counts are held 64 at a time, lane j that of group cur_blk + j, with
+        // the non-empty and the fully non-zero ones as wave-uniform bit masks (empty groups cost nothing)
+        uint32_t cur_blk = 0xFFFFFFFFu, cnt_l = 0;
+        uint64_t nz_m = 0, full_m = 0;
         for (uint32_t sg = 0; sg < n_seg;) {
             // (a) expand mask words into the ascending row list: 64 words at a time, or -- element-level
             // inputs -- as many consecutive 16-word groups as together hold at most SEG_ROWS rows (a
             // uniformly sparse tile is then one pass instead of sixteen)
             uint32_t w0 = sg * seg_words, w1 = min(w0 + seg_words, g.tile_words), total;
             if (ELEM) {
-                uint32_t merged = s_seg[sg];   // uniform: LDS
-                if (fast_ok && merged == ZEN_GROUP_ROWS) {
+                const uint32_t gblk = sg & ~63u;
+                if (gblk != cur_blk) {
+                    cur_blk = gblk;
+                    cnt_l = gblk + lane_id() < n_seg ? s_seg[gblk + lane_id()] : 0u;
+                    nz_m = ballot(cnt_l != 0);
+                    full_m = fast_ok ? ballot(cnt_l == ZEN_GROUP_ROWS) : 0ull;
+                }
+                uint64_t rest = nz_m & (~0ull << (sg & 63u));   // non-empty groups from sg on
+                if (rest == 0) { sg = gblk + 64; continue; }
+                const uint32_t j = (uint32_t)__ffsll((unsigned long long)rest) - 1;
+                sg = gblk + j;
+                w0 = sg * seg_words;
+                uint32_t merged = (uint32_t)__builtin_amdgcn_readlane((int)cnt_l, (int)j);
+                if ((full_m >> j) & 1ull) {
                     // (a') A stretch of fully non-zero groups: every row of [ra, rb) is listed, so the rows of
                     // partition p among them are a contiguous piece of its sorted domain II_p.  Output position
                     // = running position + (rank in II_p - rank of the stretch's first row of p); the bits
@@ -521,7 +537,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     // Values are first placed in LDS in output order (partition-major), then written out:
                     // consecutive lanes then store to consecutive addresses instead of one cache line each.
                     const uint32_t g0 = sg;
-                    do ++sg; while (sg < n_seg && s_seg[sg] == ZEN_GROUP_ROWS && sg - g0 < SEG_ROWS / ZEN_GROUP_ROWS);
+                    do ++sg; while ((sg & 63u) && ((full_m >> (sg & 63u)) & 1ull) && sg - g0 < SEG_ROWS / ZEN_GROUP_ROWS);
                     const uint64_t ga = (uint64_t)tile * (g.tile_rows / ZEN_GROUP_ROWS) + g0, gb = ga + (sg - g0);
                     const uint32_t ra = (uint32_t)(row0 + (uint64_t)g0 * ZEN_GROUP_ROWS);
                     const uint32_t cnt = (sg - g0) * ZEN_GROUP_ROWS;   // <= SEG_ROWS
@@ -588,11 +604,19 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     __syncthreads();   // s_list, s_pos, s_delta, s_goff, s_run are rewritten by what follows
                     continue;
                 }
-                ++sg;
-                while (sg < n_seg && !(fast_ok && s_seg[sg] == ZEN_GROUP_ROWS) && merged + s_seg[sg] <= SEG_ROWS)
-                    merged += s_seg[sg++];
+                uint32_t e = j + 1;
+                rest &= rest - 1;
+                while (rest) {   // following non-empty groups, as long as none is fully non-zero and the rows fit
+                    const uint32_t j2 = (uint32_t)__ffsll((unsigned long long)rest) - 1;
+                    if ((full_m >> j2) & 1ull) break;
+                    const uint32_t c2 = (uint32_t)__builtin_amdgcn_readlane((int)cnt_l, (int)j2);
+                    if (merged + c2 > SEG_ROWS) break;
+                    merged += c2;
+                    e = j2 + 1;
+                    rest &= rest - 1;
+                }
+                sg = gblk + e;
                 w1 = min(sg * seg_words, g.tile_words);
-                if (merged == 0) continue;
                 const uint32_t wpt = (w1 - w0 + SCATTER_THREADS - 1) / SCATTER_THREADS;   // consecutive words per thread
                 const uint32_t wa = min(w0 + threadIdx.x * wpt, w1), wb = min(wa + wpt, w1);
                 uint32_t mine = 0;
