@@ -25,6 +25,7 @@ static constexpr int SCAN_THREADS = 1024;
 static constexpr int SEG_WORDS = 64;              // mask words expanded per scatter segment
 static constexpr int SEG_ROWS = SEG_WORDS * 32;   // 2048
 static constexpr int GROUP_WORDS = ZEN_GROUP_ROWS / 32;   // 16 mask words: the unit the element-level scatter counts rows in
+static constexpr uint32_t MIN_STRETCH_ROWS = 128;  // shortest stretch of consecutive listed rows placed from the rank tables
 
 __device__ __forceinline__ u32x4 load_stream(const u32x4 *p)
 {
@@ -375,7 +376,7 @@ struct BitmapTables {
 #define ZEN_SCATTER_WAVES 6   // waves per SIMD the register allocation must allow: 6 measured best (8 spills)
 #endif
 #ifndef ZEN_SCATTER_WAVES_ELEM
-#define ZEN_SCATTER_WAVES_ELEM 5   // element-level: the staged output keeps more values in registers
+#define ZEN_SCATTER_WAVES_ELEM 4   // element-level: the staged output keeps more values in registers (5 spills, and measures slower)
 #endif
 template <bool ELEM>
 __global__ void __launch_bounds__(SCATTER_THREADS, ELEM ? ZEN_SCATTER_WAVES_ELEM : ZEN_SCATTER_WAVES)
@@ -510,37 +511,62 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
         // the non-empty and the fully non-zero ones as wave-uniform bit masks (empty groups cost nothing)
         uint32_t cur_blk = 0xFFFFFFFFu, cnt_l = 0;
         uint64_t nz_m = 0, full_m = 0;
+        uint32_t cur = 0;   // element-level: row offset inside the tile below which everything is done
         for (uint32_t sg = 0; sg < n_seg;) {
             // (a) expand mask words into the ascending row list: 64 words at a time, or -- element-level
             // inputs -- as many consecutive 16-word groups as together hold at most SEG_ROWS rows (a
             // uniformly sparse tile is then one pass instead of sixteen)
             uint32_t w0 = sg * seg_words, w1 = min(w0 + seg_words, g.tile_words), total;
+            uint32_t first_mask = 0xFFFFFFFFu;   // element-level: bits of word w0 that belong to this piece
             if (ELEM) {
-                const uint32_t gblk = sg & ~63u;
+                sg = cur / ZEN_GROUP_ROWS;
+                if (sg >= n_seg) break;
+                const uint32_t gblk = sg & ~63u, j = sg & 63u, lane = lane_id();
                 if (gblk != cur_blk) {
                     cur_blk = gblk;
-                    cnt_l = gblk + lane_id() < n_seg ? s_seg[gblk + lane_id()] : 0u;
+                    cnt_l = gblk + lane < n_seg ? s_seg[gblk + lane] : 0u;
                     nz_m = ballot(cnt_l != 0);
                     full_m = fast_ok ? ballot(cnt_l == ZEN_GROUP_ROWS) : 0ull;
                 }
-                uint64_t rest = nz_m & (~0ull << (sg & 63u));   // non-empty groups from sg on
-                if (rest == 0) { sg = gblk + 64; continue; }
-                const uint32_t j = (uint32_t)__ffsll((unsigned long long)rest) - 1;
-                sg = gblk + j;
-                w0 = sg * seg_words;
-                uint32_t merged = (uint32_t)__builtin_amdgcn_readlane((int)cnt_l, (int)j);
-                if ((full_m >> j) & 1ull) {
-                    // (a') A stretch of fully non-zero groups: every row of [ra, rb) is listed, so the rows of
-                    // partition p among them are a contiguous piece of its sorted domain II_p.  Output position
-                    // = running position + (rank in II_p - rank of the stretch's first row of p); the bits
-                    // of p are one contiguous range.  No list, no ranking.
-                    // Values are first placed in LDS in output order (partition-major), then written out:
-                    // consecutive lanes then store to consecutive addresses instead of one cache line each.
-                    const uint32_t g0 = sg;
-                    do ++sg; while ((sg & 63u) && ((full_m >> (sg & 63u)) & 1ull) && sg - g0 < SEG_ROWS / ZEN_GROUP_ROWS);
-                    const uint64_t ga = (uint64_t)tile * (g.tile_rows / ZEN_GROUP_ROWS) + g0, gb = ga + (sg - g0);
-                    const uint32_t ra = (uint32_t)(row0 + (uint64_t)g0 * ZEN_GROUP_ROWS);
-                    const uint32_t cnt = (sg - g0) * ZEN_GROUP_ROWS;   // <= SEG_ROWS
+                // first listed row at or after cur: in cur's group, else in the next non-empty group
+                const uint64_t later = j == 63u ? 0ull : nz_m & (~0ull << (j + 1));
+                const uint32_t next_grp_row = (later ? gblk + (uint32_t)__ffsll((unsigned long long)later) - 1 : gblk + 64) * ZEN_GROUP_ROWS;
+                if (!((nz_m >> j) & 1ull)) { cur = next_grp_row; continue; }
+                uint32_t a;
+                {
+                    const uint32_t wi = sg * GROUP_WORDS + (lane & (GROUP_WORDS - 1)), cw = cur >> 5;
+                    uint32_t wd = (lane < GROUP_WORDS && wi < g.tile_words && wi >= cw) ? s_mask[wi] : 0u;
+                    if (wi == cw) wd &= 0xFFFFFFFFu << (cur & 31u);
+                    const uint64_t m = ballot(wd != 0);
+                    if (m == 0) { cur = next_grp_row; continue; }
+                    const uint32_t z = (uint32_t)__ffsll((unsigned long long)m) - 1;
+                    a = (sg * GROUP_WORDS + z) * 32 + (uint32_t)__ffs((int)__builtin_amdgcn_readlane((int)wd, (int)z)) - 1;
+                }
+                // end of the stretch of listed rows that starts at a (looked for in the next 64 words)
+                uint32_t b = a;
+                if (fast_ok) {
+                    const uint32_t aw = a >> 5;
+                    uint32_t inv = aw + lane < g.tile_words ? ~s_mask[aw + lane] : 0xFFFFFFFFu;
+                    if (lane == 0) inv &= 0xFFFFFFFFu << (a & 31u);
+                    const uint64_t zm = ballot(inv != 0);
+                    if (zm == 0) {
+                        b = (aw + ZEN_WAVE) * 32;
+                    } else {
+                        const uint32_t z = (uint32_t)__ffsll((unsigned long long)zm) - 1;
+                        b = (aw + z) * 32 + (uint32_t)__ffs((int)__builtin_amdgcn_readlane((int)inv, (int)z)) - 1;
+                    }
+                    if (b - a > SEG_ROWS) b = a + SEG_ROWS;
+                }
+                if (b - a >= MIN_STRETCH_ROWS) {
+                    // (a') A stretch [A, B) of rows that are all listed: the rows of partition p among them are a
+                    // contiguous piece of its sorted domain II_p, from the rank of p's first row at or after A to
+                    // that at or after B -- the table's value at the 512-row boundary below plus the owners of the
+                    // rows from that boundary on, which only have to be hashed.  Output position = running
+                    // position + (rank in II_p - first rank); the bits of p are one contiguous range.  No list,
+                    // no ranking.  Values are first placed in LDS in output order (partition-major), then
+                    // written out: consecutive lanes store to consecutive addresses, not one cache line each.
+                    const uint32_t ra = (uint32_t)(row0 + a), rb = (uint32_t)(row0 + b), cnt = b - a;   // cnt <= SEG_ROWS
+                    cur = b;
                     constexpr uint32_t FB = SEG_ROWS / SCATTER_THREADS;   // 8 rows per thread
                     float fv[FB];
                     uint32_t fr[FB];
@@ -554,11 +580,18 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                             if (out_val) fv[q] = grad[ra + i];
                         }
                     }
+                    for (uint32_t r = (ra & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < ra; r += SCATTER_THREADS)
+                        atomicAdd(&s_cnt[owner_of(r, g.seed, n, g.pow2_mask)], 1u);
+                    for (uint32_t r = (rb & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < rb; r += SCATTER_THREADS)
+                        atomicAdd(&s_cnt[n + owner_of(r, g.seed, n, g.pow2_mask)], 1u);
+                    __syncthreads();
                     // n <= ZEN_GROUP_MAX_PARTS <= blockDim.x: one thread per partition
                     uint32_t fa = 0, fb = 0;
                     if (threadIdx.x < n) {
-                        fa = bt.group_base[ga * n + threadIdx.x];
-                        fb = bt.group_base[gb * n + threadIdx.x];
+                        fa = bt.group_base[(uint64_t)(ra / ZEN_GROUP_ROWS) * n + threadIdx.x] + s_cnt[threadIdx.x];
+                        fb = bt.group_base[(uint64_t)(rb / ZEN_GROUP_ROWS) * n + threadIdx.x] + s_cnt[n + threadIdx.x];
+                        s_cnt[threadIdx.x] = 0;          // the ranking scratch is all zero between its uses
+                        s_cnt[n + threadIdx.x] = 0;
                     }
                     uint32_t stretch_rows;
                     const uint32_t loff = block_exclusive_scan(fb - fa, s_tmp, &stretch_rows);   // (barriers inside)
@@ -604,9 +637,12 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     __syncthreads();   // s_list, s_pos, s_delta, s_goff, s_run are rewritten by what follows
                     continue;
                 }
+                // scattered rows: the rest of this group and the following non-empty groups, as long as none is
+                // fully non-zero and the rows fit (counts of a group partly done already only over-estimate)
+                uint32_t merged = (uint32_t)__builtin_amdgcn_readlane((int)cnt_l, (int)j);
                 uint32_t e = j + 1;
-                rest &= rest - 1;
-                while (rest) {   // following non-empty groups, as long as none is fully non-zero and the rows fit
+                uint64_t rest = later;
+                while (rest) {
                     const uint32_t j2 = (uint32_t)__ffsll((unsigned long long)rest) - 1;
                     if ((full_m >> j2) & 1ull) break;
                     const uint32_t c2 = (uint32_t)__builtin_amdgcn_readlane((int)cnt_l, (int)j2);
@@ -615,15 +651,17 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     e = j2 + 1;
                     rest &= rest - 1;
                 }
-                sg = gblk + e;
-                w1 = min(sg * seg_words, g.tile_words);
+                cur = (gblk + e) * ZEN_GROUP_ROWS;
+                w0 = a >> 5;
+                first_mask = 0xFFFFFFFFu << (a & 31u);
+                w1 = min((gblk + e) * seg_words, g.tile_words);
                 const uint32_t wpt = (w1 - w0 + SCATTER_THREADS - 1) / SCATTER_THREADS;   // consecutive words per thread
                 const uint32_t wa = min(w0 + threadIdx.x * wpt, w1), wb = min(wa + wpt, w1);
                 uint32_t mine = 0;
-                for (uint32_t wi = wa; wi < wb; ++wi) mine += __popc(s_mask[wi]);
+                for (uint32_t wi = wa; wi < wb; ++wi) mine += __popc(s_mask[wi] & (wi == w0 ? first_mask : 0xFFFFFFFFu));
                 uint32_t k = block_exclusive_scan(mine, s_tmp, &total);
                 for (uint32_t wi = wa; wi < wb; ++wi) {
-                    uint32_t word = s_mask[wi];
+                    uint32_t word = s_mask[wi] & (wi == w0 ? first_mask : 0xFFFFFFFFu);
                     const uint32_t rbase = (uint32_t)(row0 + (uint64_t)wi * 32);
                     while (word) {
                         const uint32_t b = __ffs(word) - 1;
