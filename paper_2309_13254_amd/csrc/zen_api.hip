@@ -47,7 +47,8 @@ static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32
         if (g.tile_rows > 2048) g.tile_rows = 2048;
     }
     g.tile_words = g.tile_rows / 32;
-    g.sparse_mask = g.mode == MODE_ELEM ? 1u : 0u;
+    // wave-per-row tiles have one or a few mask words: always written; sub-row tiles keep their (short) histogram rows
+    g.sparse_mask = g.mode == MODE_ELEM ? 3u : (g.mode == MODE_SUB ? 1u : 0u);
     g.n_tiles = (uint32_t)((n_rows + g.tile_rows - 1) / g.tile_rows);
 }
 

@@ -22,6 +22,7 @@ namespace zen {
 static constexpr int DETECT_THREADS = ZEN_DETECT_THREADS;
 static constexpr int SCATTER_THREADS = 256;
 static constexpr int SCAN_THREADS = 1024;
+static constexpr uint32_t SCAN_FLAG_WORDS = 4096; // partition scan: tile flags kept as bits in LDS up to 131,072 tiles
 static constexpr int SEG_WORDS = 64;              // mask words expanded per scatter segment
 static constexpr int SEG_ROWS = SEG_WORDS * 32;   // 2048
 static constexpr int GROUP_WORDS = ZEN_GROUP_ROWS / 32;   // 16 mask words: the unit the element-level scatter counts rows in
@@ -222,7 +223,13 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
         for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= s_mask[i];
         const int flag = __syncthreads_or((int)(any != 0));
         if (threadIdx.x == 0) tflag_base[worker * tflag_stride + tile] = flag ? 1u : 0u;
-        if (!flag) return;
+        if (!flag) {
+            if (!(g.sparse_mask & 2u) && hist_base) {   // histogram rows are kept valid for every tile: a zero row
+                uint32_t *gh = hist_base + worker * hist_stride_words + (uint64_t)tile * g.n_parts;
+                for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) gh[i] = 0u;
+            }
+            return;
+        }
     }
     uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
     for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) gmask[i] = s_mask[i];
@@ -274,6 +281,34 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
     const uint32_t t0 = active ? min(grp * per, g.n_tiles) : 0;
     const uint32_t t1 = active ? min(t0 + per, g.n_tiles) : 0;
 
+    // The tile flags as a bit set in LDS (when there are few enough tiles): the walks below would otherwise wait
+    // for a flag before they can ask for the histogram row it gates.  No flags: every tile counts.
+    __shared__ uint32_t s_fbits[SCAN_FLAG_WORDS];
+    const bool fbits = g.n_tiles <= SCAN_FLAG_WORDS * 32;
+    if (fbits) {
+        const uint32_t lane = lane_id();
+        for (uint32_t tb = 0; tb < g.n_tiles; tb += 8 * SCAN_THREADS) {
+            uint32_t f[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t t = tb + u * SCAN_THREADS + threadIdx.x;
+                f[u] = t < g.n_tiles ? (g.sparse_mask ? tflag[t] : 1u) : 0u;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t first = tb + u * SCAN_THREADS + threadIdx.x - lane;   // the wave's first tile
+                const uint64_t m = ballot(f[u] != 0);
+                if (first < g.n_tiles && lane < 2) s_fbits[(first >> 5) + lane] = (uint32_t)(m >> (32 * lane));
+            }
+        }
+        __syncthreads();
+    }
+    auto tile_on = [&](uint32_t t) -> bool {      // does tile t have a histogram row?
+        if (!(g.sparse_mask & 2u)) return true;
+        if (fbits) return (s_fbits[t >> 5] >> (t & 31u)) & 1u;
+        return tflag[t] != 0;
+    };
+
     // Batches of 8 tiles: the loads of a batch are independent and issued together (one at a time,
     // this walk is a chain of memory round trips and the kernel runs one block per worker).
     uint32_t sum = 0;
@@ -282,7 +317,7 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
 #pragma unroll
         for (uint32_t u = 0; u < 8; ++u) {
             const uint32_t t = tb + u;
-            h[u] = (t < t1 && (!g.sparse_mask || tflag[t])) ? hist[(uint64_t)t * n + p] : 0u;
+            h[u] = (t < t1 && tile_on(t)) ? hist[(uint64_t)t * n + p] : 0u;
         }
 #pragma unroll
         for (uint32_t u = 0; u < 8; ++u) sum += h[u];
@@ -324,7 +359,7 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
 #pragma unroll
             for (uint32_t u = 0; u < 8; ++u) {
                 const uint32_t t = tb + u;
-                on[u] = t < t1 && (!g.sparse_mask || tflag[t]);
+                on[u] = t < t1 && tile_on(t);
                 h[u] = on[u] ? hist[(uint64_t)t * n + p] : 0u;
             }
 #pragma unroll
@@ -334,11 +369,24 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
             }
         }
     }
-    // For the scatter of element-level inputs: ascending list of the worker's non-empty tiles (all
-    // tiles when the input carries no tile flags), its length behind it.
+    // For the scatter: ascending list of the worker's non-empty tiles (all tiles when the geometry
+    // carries no tile flags), its length behind it.
     if (tlist_base) {
         uint32_t *tlist = tlist_base + worker * tlist_stride;
         uint32_t listed = 0;
+        if (fbits) {
+            const uint32_t n_fw = (g.n_tiles + 31) >> 5;      // a thread lists the tiles of one flag word
+            for (uint32_t w0 = 0; w0 < n_fw; w0 += blockDim.x) {
+                const uint32_t w = w0 + threadIdx.x;
+                uint32_t word = w < n_fw ? s_fbits[w] : 0u, total;
+                uint32_t at = listed + block_exclusive_scan(__popc(word), s_tmp, &total);
+                while (word) {
+                    tlist[at++] = w * 32 + (uint32_t)__ffs((int)word) - 1;
+                    word &= word - 1;
+                }
+                listed += total;
+            }
+        } else
         for (uint32_t t0b = 0; t0b < g.n_tiles; t0b += blockDim.x) {
             const uint32_t t = t0b + threadIdx.x;
             const uint32_t f = (t < g.n_tiles && (!g.sparse_mask || tflag[t])) ? 1u : 0u;
@@ -412,20 +460,19 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 
     for (uint32_t i = threadIdx.x; i < n_waves * n; i += blockDim.x) s_cnt[i] = 0;
 
-    // Tiles to visit: element-level inputs come with the ascending list of their non-empty tiles (empty
-    // ones have no mask words at all); the mask of the next tile is fetched into registers while the
-    // current one is processed, its id one visit earlier still.  Otherwise every tile is visited and
-    // tested (tiles of wide rows have a handful of mask words).
-    const uint32_t *tlist = ELEM ? tlist_base + worker * tlist_stride : nullptr;
-    const uint32_t n_visit = ELEM ? min(tlist[g.n_tiles], g.n_tiles) : g.n_tiles;
+    // Tiles to visit: the ascending list of the worker's non-empty tiles (every tile, each tested here, for the
+    // wave-per-row geometry, which carries no tile flags).  Element-level inputs: the mask of the next tile is
+    // fetched into registers while the current one is processed, its id one visit earlier still.
+    const uint32_t *tlist = tlist_base + worker * tlist_stride;
+    const uint32_t n_visit = min(tlist[g.n_tiles], g.n_tiles);
     const uint32_t *wmask = mask_base + worker * mask_stride_words;
     const bool pf_ok = g.tile_words <= 8 * SCATTER_THREADS;   // 8 registers per thread hold a tile's mask
     uint32_t mw[8];
 #pragma unroll
     for (uint32_t q = 0; q < 8; ++q) mw[q] = 0;
     uint32_t k = blockIdx.x;
-    uint32_t nxt_tile = k < n_visit ? (ELEM ? min(tlist[k], g.n_tiles - 1) : k) : 0u;
-    uint32_t nxt2_tile = (ELEM && k + gridDim.x < n_visit) ? min(tlist[k + gridDim.x], g.n_tiles - 1) : 0u;
+    uint32_t nxt_tile = k < n_visit ? min(tlist[k], g.n_tiles - 1) : 0u;
+    uint32_t nxt2_tile = k + gridDim.x < n_visit ? min(tlist[k + gridDim.x], g.n_tiles - 1) : 0u;
     if (ELEM && pf_ok && k < n_visit) {
 #pragma unroll
         for (uint32_t q = 0; q < 8; ++q) {
@@ -472,10 +519,16 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             }
             __syncthreads();
         } else {
-            nxt_tile = k + gridDim.x;
-            uint32_t any = 0;
-            for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= gmask[i];
-            if (!__syncthreads_or((int)(any != 0))) continue;  // empty tile (also the barrier between tiles)
+            nxt_tile = nxt2_tile;
+            const uint32_t k2 = k + 2 * gridDim.x;
+            nxt2_tile = k2 < n_visit ? min(tlist[k2], g.n_tiles - 1) : 0u;
+            if (g.sparse_mask) {
+                __syncthreads();                               // listed tiles hold rows: only the barrier between tiles
+            } else {
+                uint32_t any = 0;
+                for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= gmask[i];
+                if (!__syncthreads_or((int)(any != 0))) continue;  // empty tile (also the barrier between tiles)
+            }
         }
 
         const uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * n;
@@ -1009,7 +1062,7 @@ hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t
     partition_scan_kernel<<<batch, SCAN_THREADS, 0, s>>>(g, outs, (uint32_t *)(ws + L.hist_off),
                                                          L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
                                                          L.flag_stride / 4,
-                                                         g.row_dim == 1 ? (uint32_t *)(ws + L.list_off) : nullptr,
+                                                         (uint32_t *)(ws + L.list_off),
                                                          L.list_stride / 4, (zen_status_info *)(ws + L.status_off));
     return hipGetLastError();
 }
@@ -1059,8 +1112,8 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
     else
         scatter_kernel<false><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
             g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
-            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
-            L.flag_stride / 4, bt);
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.list_off),
+            L.list_stride / 4, bt);
     return hipGetLastError();
 }
 

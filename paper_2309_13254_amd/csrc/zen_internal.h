@@ -31,7 +31,8 @@ struct Geometry {
     uint32_t tile_words;     // tile_rows / 32
     uint32_t n_tiles;        // ceil(n_rows / tile_rows)
     uint32_t bitmap;         // 1 = hash-bitmap index format
-    uint32_t sparse_mask;    // 1 = per-tile flags gate the mask words / histogram rows (element-level inputs)
+    uint32_t sparse_mask;    // per-tile flags exist and gate: bit 0 the tile's mask words, bit 1 its histogram row
+                             // (empty tiles write neither); 0 = no flags, everything is always written
 };
 
 // Per-call encode workspace layout (bytes from the workspace base).

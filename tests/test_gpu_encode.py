@@ -82,6 +82,26 @@ def test_encode_batch_mini_workloads(oracle, zen, cid):
     assert torch.equal(one.values.view(torch.int32), outs[0].values.view(torch.int32))
 
 
+@pytest.mark.parametrize("cid", [1, 3, 5])
+@pytest.mark.parametrize("fill", [-1, 7, 0x01010101])
+def test_encode_ignores_stale_workspace(oracle, zen, cid, fill):
+    """The workspace carries over nothing: whatever it held (masks, histogram rows and flags of tiles that
+    are empty this time are not rewritten) must not reach the result."""
+    import gpu_util as G
+
+    wl = MINI_WORKLOADS[cid]
+    sparse, grads = G.workload_inputs(wl, n_workers=min(wl.n_workers, 4))
+    fmt = zen.ZEN_INDEX_BITMAP if wl.bitmap else zen.ZEN_INDEX_COO
+    ctx = zen.ZenContext(wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed, fmt)
+    outs = [zen.alloc_encoded(ctx, r.size) for r, _ in sparse]
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, len(grads)))
+    ws.view(torch.int32).fill_(fill)
+    zen.zen_encode_batch(ctx, grads, outs, ws)
+    assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+    for (rows, vals), enc in zip(sparse, outs):
+        _check_encoded(oracle, zen, ctx, wl, dense_from_sparse(wl, rows, vals), enc)
+
+
 SHAPES = [
     # R, D, n
     (1, 1, 1), (5, 1, 3), (255, 1, 2), (256, 1, 4), (257, 1, 5), (70001, 1, 64), (300000, 1, 100),
