@@ -37,7 +37,8 @@ static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32
         g.tile_rows = (uint32_t)t;
     } else if ((row_dim & 3u) == 0 && row_dim <= 128 && is_pow2(row_dim / 4)) {
         g.mode = MODE_SUB;
-        uint64_t t = target_bytes / (4ull * row_dim);
+        uint64_t t = 4 * target_bytes / (4ull * row_dim);   // 512 KB: rows are sparse here, and every tile with a row
+                                                            // costs the partition scan and the scatter a fixed amount
         while (t > 64 && n_rows / t < 1024) t >>= 1;
         g.tile_rows = (uint32_t)align_up(t < 64 ? 64 : t, 64);
     } else {
