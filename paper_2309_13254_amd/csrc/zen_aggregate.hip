@@ -11,6 +11,7 @@
 namespace zen {
 
 static constexpr int AGG_THREADS = 256;
+static constexpr uint32_t GATHER_GROUP_ROWS = 4;   // output rows a lane group of the narrow-row gather keeps in flight
 static constexpr int SMALL_THREADS = 1024;
 static constexpr uint32_t SMALL_MAX_IN = 6500;     // rows into one server that the one-block LDS path takes:
                                                    // table of 8192 slots (load <= 0.8) x 2 arrays + 8192 sorted
@@ -101,24 +102,25 @@ __device__ __forceinline__ uint32_t probe_find(const uint32_t *__restrict__ keys
     return 0xFFFFFFFFu;
 }
 
-// A1: keys = EMPTY for every server, counters and status zeroed.
-__global__ void agg_clear_kernel(uint32_t *keys, uint64_t n_keys, uint32_t *counters, uint32_t n_counters,
+// A1: keys = EMPTY and repeat counts = 0 for every server, counters and status zeroed.
+__global__ void agg_clear_kernel(uint32_t *keys, uint32_t *occ, uint64_t n_keys, uint32_t *counters, uint32_t n_counters,
                                  zen_status_info *status)
 {
     const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, nt = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t i = tid; i < n_keys; i += nt) keys[i] = ZEN_EMPTY_KEY;
+    for (uint64_t i = tid; i < n_keys; i += nt) { keys[i] = ZEN_EMPTY_KEY; occ[i] = 0u; }
     for (uint64_t i = tid; i < n_counters; i += nt) counters[i] = 0;
     if (tid == 0) { status->flags = 0; status->reserved = 0; status->needed_rows = 0; }
 }
 
 // A2 (keys): claim a slot for every distinct incoming index.
 __global__ void __launch_bounds__(AGG_THREADS)
-agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base, uint64_t table_cap,
+agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base, uint32_t *occ_base, uint64_t table_cap,
                   uint32_t *counters_base, uint64_t max_in_rows, zen_status_info *status)
 {
     __shared__ uint32_t s_tmp[32];
     const uint32_t server = blockIdx.z, w = blockIdx.y;
     uint32_t *keys = keys_base + (uint64_t)server * table_cap;
+    uint32_t *occ = occ_base + (uint64_t)server * table_cap;   // repeats of the slot's key (the rank table, until finalize)
     uint32_t *counters = counters_base + server * 16;
     const uint32_t cap_mask = (uint32_t)(table_cap - 1);
 
@@ -144,7 +146,8 @@ agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base
         uint32_t slot = table_hash(key, seed) & cap_mask;
         for (uint32_t t = 0; t <= cap_mask; ++t) {
             const uint32_t prev = atomicCAS(&keys[slot], ZEN_EMPTY_KEY, key);
-            if (prev == ZEN_EMPTY_KEY || prev == key) break;
+            if (prev == ZEN_EMPTY_KEY) break;                      // claimed: the first occurrence
+            if (prev == key) { atomicAdd(&occ[slot], 1u); break; }  // a repeat
             slot = (slot + 1) & cap_mask;
         }
     }
@@ -170,8 +173,9 @@ __device__ __forceinline__ uint32_t lds_probe(const uint32_t *tkeys, uint32_t ca
 __global__ void __launch_bounds__(SMALL_THREADS)
 agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32_t max_in_rows,
                  uint32_t *counters_base, AggOut outs, uint32_t *rowstart_base, uint32_t *contrib_base,
-                 uint64_t ws_stride, const uint32_t *dec_flags)
+                 uint64_t ws_stride, const uint32_t *dec_flags, Arr64<const float *> src_values, const float **src_tab)
 {
+    if (blockIdx.x == 0 && threadIdx.x < ZEN_MAX_BATCH) src_tab[threadIdx.x] = src_values.v[threadIdx.x];   // for the gather
     extern __shared__ uint32_t smem[];
     uint32_t *tkeys = smem;                 // [cap]
     uint32_t *tval = tkeys + cap;           // [cap] occurrences, later the fill cursor
@@ -314,15 +318,17 @@ __device__ __forceinline__ uint64_t next_contrib(const uint64_t *list, uint32_t 
 }
 
 // A2 (values), small tables: out_values[u] = sum of the rows listed for u, in ascending (part, row)
-// order.  Wide rows: one wave per output row; narrow rows: one thread per output element.
+// order.  Wide rows: one wave per output row; otherwise one thread per output element.
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_servers,
-                  uint32_t *counters_base, const uint32_t *rowstart_base, const uint32_t *contrib_base,
-                  uint64_t ws_stride, Arr64<float *> out_values, AggOut outs, zen_status_info *status)
+                  uint32_t *counters_base, const uint32_t *rowstart_base, uint64_t rowstart_stride,
+                  const uint32_t *contrib_base, uint64_t contrib_stride, Arr64<float *> out_values, AggOut outs,
+                  zen_status_info *status)
 {
+    // strides in u32 words; status: non-NULL when the servers' results are still to be folded into the call's
     const uint32_t server = blockIdx.y;
     const uint32_t D = row_dim;
-    if (blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
+    if (status && blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
         // status of the whole call = OR / max over the servers' own results
         uint32_t fl = 0, need = 0;
         for (uint32_t j = 0; j < n_servers; ++j) {
@@ -338,8 +344,8 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
     const uint32_t U = counters[CNT_UNIQUE];
     const uint64_t cap_rows = outs.cap_rows[server];
     const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
-    const uint32_t *rowstart = rowstart_base + (uint64_t)server * ws_stride;
-    const uint64_t *contrib = (const uint64_t *)(contrib_base + (uint64_t)server * ws_stride);
+    const uint32_t *rowstart = rowstart_base + (uint64_t)server * rowstart_stride;
+    const uint64_t *contrib = (const uint64_t *)(contrib_base + (uint64_t)server * contrib_stride);
     float *__restrict__ out = out_values.v[server];
 
     if ((D & 3u) == 0 && D >= 256) {
@@ -403,6 +409,130 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
                 acc += src_values.v[(uint32_t)(e >> 32)][(e & 0xFFFFFFFFull) * D + c];
             }
             out[f] = acc;
+        }
+    }
+}
+
+// The same for rows of 4..252 floats (a multiple of four): a power-of-two group of lanes per output row, 16 bytes
+// per lane.  (A kernel of its own: it keeps four rows per group in registers.)
+__global__ void __launch_bounds__(AGG_THREADS)
+agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_dim, uint32_t n_servers,
+                        uint32_t *counters_base, const uint32_t *rowstart_base, uint64_t rowstart_stride,
+                        const uint32_t *contrib_base, uint64_t contrib_stride, Arr64<float *> out_values, AggOut outs,
+                        zen_status_info *status)
+{
+    const uint32_t server = blockIdx.y;
+    const uint32_t D = row_dim;
+    if (status && blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
+        uint32_t fl = 0, need = 0;
+        for (uint32_t j = 0; j < n_servers; ++j) {
+            fl |= counters_base[j * 16 + CNT_FLAGS];
+            need = max(need, counters_base[j * 16 + CNT_NEEDED]);
+        }
+        status->flags = fl;
+        status->reserved = 0;
+        status->needed_rows = need;
+    }
+    const uint32_t *counters = counters_base + server * 16;
+    if (counters[CNT_SKIP]) return;
+    const uint32_t U = counters[CNT_UNIQUE];
+    const uint64_t cap_rows = outs.cap_rows[server];
+    const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
+    const uint32_t *rowstart = rowstart_base + (uint64_t)server * rowstart_stride;
+    const uint64_t *contrib = (const uint64_t *)(contrib_base + (uint64_t)server * contrib_stride);
+    float *__restrict__ out = out_values.v[server];
+    {
+        // rows of 4..252 floats: a power-of-two group of lanes per output row, 16 bytes per lane
+        const uint32_t V = D >> 2, lane = lane_id();
+        uint32_t lanes = 1;
+        while (lanes < V) lanes <<= 1;
+        const uint32_t per_wave = ZEN_WAVE / lanes, sub = lane / lanes, vl = lane % lanes;
+        const uint32_t wave_id = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), n_wave = gridDim.x * (blockDim.x >> 6);
+        const uint32_t g0 = sub * lanes;                 // first lane of my group
+        // Four output rows per group at a time: their row bounds, then their lists, then the rows of their first
+        // two contributors are fetched together -- a row is a chain of three dependent accesses, and one row at
+        // a time leaves the kernel waiting on them.
+        constexpr uint32_t R = GATHER_GROUP_ROWS;
+        auto rank_holder = [&](uint32_t my_rank, uint32_t k, uint64_t mine) -> uint64_t {
+            // the list entry of rank k, from the lane of my group that holds it (every lane of the group calls)
+            const uint64_t holders = ballot(my_rank == k) >> g0;
+            const uint32_t srcl = g0 + (uint32_t)__ffsll((unsigned long long)holders) - 1u;
+            return ((uint64_t)__shfl((uint32_t)(mine >> 32), (int)srcl, ZEN_WAVE) << 32) |
+                   __shfl((uint32_t)mine, (int)srcl, ZEN_WAVE);
+        };
+        auto src_vec = [&](uint64_t e) -> f32x4 {
+            // the parts' value arrays come from a table in memory: lanes differ in the part they read
+            return ((const f32x4 *)(src_tab[(uint32_t)(e >> 32)] + (e & 0xFFFFFFFFull) * D))[vl];
+        };
+        for (uint64_t ub = (uint64_t)wave_id * per_wave * R; ub < rows; ub += (uint64_t)n_wave * per_wave * R) {
+            uint64_t u[R], mine[R];
+            uint32_t r0[R], len[R], my_rank[R];
+            bool on[R], held[R];
+            f32x4 acc[R], x[R][2];
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r) {
+                u[r] = ub + (uint64_t)r * per_wave + sub;
+                on[r] = u[r] < rows;
+                r0[r] = on[r] ? rowstart[u[r]] : 0u;
+                len[r] = on[r] ? rowstart[u[r] + 1] - r0[r] : 0u;
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r) {
+                held[r] = on[r] && len[r] <= lanes;           // the list fits across the group's lanes
+                mine[r] = (held[r] && vl < len[r]) ? contrib[r0[r] + vl] : ~0ull;
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r) {
+                my_rank[r] = 0;
+                if (held[r]) {
+                    for (uint32_t j = 0; j < len[r]; ++j) {
+                        const uint64_t cj = ((uint64_t)__shfl((uint32_t)(mine[r] >> 32), (int)(g0 + j), ZEN_WAVE) << 32) |
+                                            __shfl((uint32_t)mine[r], (int)(g0 + j), ZEN_WAVE);
+                        my_rank[r] += cj < mine[r] ? 1u : 0u;
+                    }
+                    if (vl >= len[r]) my_rank[r] = 0xFFFFFFFFu;
+                }
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r)
+#pragma unroll
+                for (uint32_t q = 0; q < 2; ++q) {
+                    x[r][q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    if (held[r] && q < len[r]) {
+                        const uint64_t e = rank_holder(my_rank[r], q, mine[r]);
+                        if (vl < V) x[r][q] = src_vec(e);
+                    }
+                }
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r) {
+                acc[r] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (held[r]) {
+                    if (len[r] > 0) acc[r] += x[r][0];
+                    if (len[r] > 1) acc[r] += x[r][1];
+                    for (uint32_t k0 = 2; k0 < len[r]; k0 += 4) {   // longer lists: four rows in flight, added in order
+                        f32x4 y[4];
+#pragma unroll
+                        for (uint32_t q = 0; q < 4; ++q) {
+                            y[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                            if (k0 + q < len[r]) {
+                                const uint64_t e = rank_holder(my_rank[r], k0 + q, mine[r]);
+                                if (vl < V) y[q] = src_vec(e);
+                            }
+                        }
+#pragma unroll
+                        for (uint32_t q = 0; q < 4; ++q)
+                            if (k0 + q < len[r]) acc[r] += y[q];
+                    }
+                } else if (on[r]) {
+                    uint64_t prev = 0;
+                    for (uint32_t k = 0; k < len[r]; ++k) {
+                        const uint64_t e = next_contrib(contrib + r0[r], len[r], prev, k == 0);
+                        prev = e;
+                        if (vl < V) acc[r] += src_vec(e);
+                    }
+                }
+                if (on[r] && vl < V) ((f32x4 *)(out + u[r] * D))[vl] = acc[r];
+            }
         }
     }
 }
@@ -542,7 +672,7 @@ rs_scatter_kernel(const uint32_t *in_base, uint32_t *out_base, uint64_t uniq_str
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_stride, const uint32_t *keys_base,
                     uint32_t *rank_base, uint64_t table_cap, const uint32_t *counters_base, AggOut outs,
-                    zen_status_info *status)
+                    uint32_t *rowcnt_base, uint64_t rowcnt_stride, zen_status_info *status)
 {
     const uint32_t server = blockIdx.y;
     const uint32_t *counters = counters_base + server * 16;
@@ -550,6 +680,7 @@ agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_st
     const uint32_t *sorted = sorted_base + (uint64_t)server * uniq_stride;
     const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
     uint32_t *rank = rank_base + (uint64_t)server * table_cap;
+    uint32_t *rowcnt = rowcnt_base + (uint64_t)server * rowcnt_stride;
     const uint32_t cap_mask = (uint32_t)(table_cap - 1);
     const uint64_t cap_rows = outs.cap_rows[server];
     uint32_t *out_idx = outs.indices[server];
@@ -557,7 +688,9 @@ agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_st
         const uint32_t key = sorted[u];
         if (u < cap_rows) out_idx[u] = key;
         const uint32_t slot = probe_find(keys, cap_mask, key, seed);
-        if (slot != 0xFFFFFFFFu) rank[slot] = u;
+        uint32_t c = 0;
+        if (slot != 0xFFFFFFFFu) { c = rank[slot] + 1u; rank[slot] = u; }   // the slot counted the key's repeats so far
+        rowcnt[u] = c;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *outs.count[server] = U;
@@ -568,86 +701,58 @@ agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_st
     }
 }
 
-// Zero the output rows that will receive atomic adds.
-__global__ void __launch_bounds__(AGG_THREADS)
-agg_zero_kernel(Arr64<float *> out_values, AggOut outs, uint32_t row_dim, const uint32_t *counters_base)
+// Large tables: row_start[] = exclusive scan of the keys' occurrence counts (CSR over the output rows), and a
+// fill cursor per output row that starts there.  One block per server.
+__global__ void __launch_bounds__(1024)
+agg_rowstart_kernel(const uint32_t *counters_base, uint32_t *rowstart_base, uint32_t *cursor_base, uint64_t stride,
+                    Arr64<const float *> src_values, const float **src_tab)
 {
-    const uint32_t server = blockIdx.y;
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t server = blockIdx.x;
+    if (server == 0 && threadIdx.x < ZEN_MAX_BATCH) src_tab[threadIdx.x] = src_values.v[threadIdx.x];   // for the gather
     const uint32_t *counters = counters_base + server * 16;
-    const uint64_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
-    const uint64_t rows = U < outs.cap_rows[server] ? U : outs.cap_rows[server];
-    const uint64_t n = rows * row_dim;
-    float *out = out_values.v[server];
-    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, nt = (uint64_t)gridDim.x * blockDim.x;
-    if ((row_dim & 3u) == 0) {
-        f32x4 *o4 = (f32x4 *)out;
-        for (uint64_t i = tid; i < (n >> 2); i += nt) o4[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    } else {
-        for (uint64_t i = tid; i < n; i += nt) out[i] = 0.f;
+    const uint32_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
+    uint32_t *rowstart = rowstart_base + (uint64_t)server * stride, *cursor = cursor_base + (uint64_t)server * stride;
+    uint32_t carried = 0;                                        // rows listed before this chunk
+    for (uint32_t base = 0; base < U; base += 8 * blockDim.x) {  // 8 consecutive rows per thread: 32-byte accesses
+        const uint32_t ub = base + threadIdx.x * 8;
+        uint32_t c[8], sum = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) { c[q] = ub + q < U ? rowstart[ub + q] : 0u; sum += c[q]; }
+        uint32_t chunk_total;
+        uint32_t run = carried + block_exclusive_scan(sum, s_tmp, &chunk_total);
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q)
+            if (ub + q < U) { rowstart[ub + q] = run; cursor[ub + q] = run; run += c[q]; }
+        carried += chunk_total;
     }
+    const uint32_t total = carried;
+    if (threadIdx.x == 0) rowstart[U] = total;
 }
 
-__device__ __forceinline__ void add_f32(float *p, float v) { unsafeAtomicAdd(p, v); }
-
-// A2 (values): every incoming row finds its key's rank and adds itself into out_values[rank].
+// A2 (values), large tables: every incoming row appends its id (part << 32 | row in the part's values) to the
+// contributor list of its key's output row.  agg_gather_kernel then sums every output row from its list in
+// ascending (part, row) order: no value atomics, no zero fill, reproducible bit for bit.
 __global__ void __launch_bounds__(AGG_THREADS)
-agg_accum_kernel(PartIdx src, Arr64<const float *> src_values, uint32_t seed, uint32_t row_dim,
-                 const uint32_t *keys_base, const uint32_t *rank_base, uint64_t table_cap,
-                 const uint32_t *counters_base, Arr64<float *> out_values, AggOut outs)
+agg_fill_kernel(PartIdx src, uint32_t seed, const uint32_t *keys_base, const uint32_t *rank_base, uint64_t table_cap,
+                const uint32_t *counters_base, uint32_t *cursor_base, uint64_t cursor_stride, uint64_t *contrib_base,
+                uint64_t contrib_stride)
 {
     const uint32_t server = blockIdx.z, w = blockIdx.y;
     const uint32_t *counters = counters_base + server * 16;
     if (counters[CNT_SKIP]) return;
     const uint32_t *__restrict__ keys = keys_base + (uint64_t)server * table_cap;
     const uint32_t *__restrict__ rank = rank_base + (uint64_t)server * table_cap;
+    uint32_t *cursor = cursor_base + (uint64_t)server * cursor_stride;
+    uint64_t *contrib = contrib_base + (uint64_t)server * contrib_stride;
     const uint32_t cap_mask = (uint32_t)(table_cap - 1);
-    const uint64_t cap_rows = outs.cap_rows[server];
-    float *__restrict__ out = out_values.v[server];
     const PartRange r = part_range(src, w, server);
-    const float *__restrict__ vals = src_values.v[w] + (uint64_t)r.vbegin * row_dim;
-    const uint32_t D = row_dim;
-
-    if (D == 1) {
-        for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < r.count; i += gridDim.x * blockDim.x) {
-            const uint32_t key = r.idx[r.begin + i];
-            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
-            if (slot == 0xFFFFFFFFu) continue;
-            const uint32_t u = rank[slot];
-            if (u < cap_rows) add_f32(out + u, vals[i]);
-        }
-    } else if (D >= 64) {
-        // one wave per incoming row; lanes cover consecutive elements so that every atomic
-        // instruction touches 256 contiguous bytes
-        const uint32_t lane = lane_id(), nw = blockDim.x >> 6;
-        for (uint32_t i = blockIdx.x * nw + (threadIdx.x >> 6); i < r.count; i += gridDim.x * nw) {
-            const uint32_t key = r.idx[r.begin + i];
-            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
-            if (slot == 0xFFFFFFFFu) continue;
-            const uint32_t u = rank[slot];
-            if (u >= cap_rows) continue;
-            const float *__restrict__ src_row = vals + (uint64_t)i * D;
-            float *o = out + (uint64_t)u * D;
-            for (uint32_t e = lane; e < D; e += 64 * 4) {
-                float x[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) x[k] = (e + 64 * k < D) ? src_row[e + 64 * k] : 0.f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (e + 64 * k < D) add_f32(o + e + 64 * k, x[k]);
-            }
-        }
-    } else {
-        // flat (row, element) space; consecutive threads share a row, so the probes coalesce
-        const uint64_t n_el = (uint64_t)r.count * D;
-        for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_el;
-             f += (uint64_t)gridDim.x * blockDim.x) {
-            const uint32_t i = (uint32_t)(f / D), c = (uint32_t)(f - (uint64_t)i * D);
-            const uint32_t key = r.idx[r.begin + i];
-            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
-            if (slot == 0xFFFFFFFFu) continue;
-            const uint32_t u = rank[slot];
-            if (u < cap_rows) add_f32(out + (uint64_t)u * D + c, vals[f]);
-        }
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < r.count; i += gridDim.x * blockDim.x) {
+        const uint32_t key = r.idx[r.begin + i];
+        const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+        if (slot == 0xFFFFFFFFu) continue;                      // the reserved key: flagged by the insert
+        const uint32_t at = atomicAdd(&cursor[rank[slot]], 1u);
+        contrib[at] = ((uint64_t)w << 32) | (uint64_t)(r.vbegin + i);
     }
 }
 
@@ -667,6 +772,7 @@ AggLayout aggregate_layout(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_r
     uint64_t off = 0;
     L.status_off = off; off += 256;
     L.counters_off = off; off += align_up((uint64_t)batch * 16 * 4, 256);
+    L.srctab_off = off; off += ZEN_MAX_BATCH * 8;   // the parts' value arrays, for kernels whose lanes differ in the part they read
     L.keys_off = off; off += align_up((uint64_t)batch * cap * 4, 256);
     L.rank_off = off; off += align_up((uint64_t)batch * cap * 4, 256);
     L.uniq_cap = align_up(max_in_rows > 0 ? max_in_rows : 1, 64);
@@ -674,6 +780,8 @@ AggLayout aggregate_layout(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_r
     if (!L.small_path) {
         L.uniq_off = off; off += align_up((uint64_t)batch * 2 * L.uniq_cap * 4, 256);
         L.sorthist_off = off; off += align_up((uint64_t)batch * L.sort_blocks * 256 * 4, 256);
+        L.rowstart_stride = L.uniq_cap + 64;
+        L.rowstart_off = off; off += align_up((uint64_t)batch * 2 * L.rowstart_stride * 4, 256);   // row starts + fill cursors
     }
     L.decode_off = off;
     L.decode_stride = 0;
@@ -686,6 +794,26 @@ AggLayout aggregate_layout(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_r
     }
     L.total = off;
     return L;
+}
+
+// Blocks per server for the gather kernels: enough for max_in_rows output rows in one sweep, no more (a block
+// without a row still waits for the server's counters before it can leave).
+static uint32_t gather_grid_x(uint32_t row_dim, uint64_t max_in_rows)
+{
+    uint64_t gx;
+    if ((row_dim & 3u) == 0 && row_dim >= 256) {
+        gx = (max_in_rows + 3) / 4;                                   // a wave per row
+    } else if ((row_dim & 3u) == 0) {
+        uint32_t lanes = 1;
+        while (lanes < (row_dim >> 2)) lanes <<= 1;
+        const uint64_t rows_per_block = (uint64_t)(AGG_THREADS / lanes) * GATHER_GROUP_ROWS;   // groups x rows per group
+        gx = (max_in_rows + rows_per_block - 1) / rows_per_block;
+    } else {
+        gx = (max_in_rows * row_dim + AGG_THREADS - 1) / AGG_THREADS;
+    }
+    if (gx < 1) gx = 1;
+    if (gx > 8192) gx = 8192;
+    return (uint32_t)gx;
 }
 
 #define ZEN_LAUNCH_CHECK()                         \
@@ -744,18 +872,19 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         {
             ProfScope prof(ctx, K_AGG_SORT_SMALL, s);
             agg_small_kernel<<<n_servers, SMALL_THREADS, lds, s>>>(src, n_in, g.seed, lcap, (uint32_t)max_in_rows,
-                                                                   counters, outs, keys, rank, cap, dec_flags);
+                                                                   counters, outs, keys, rank, cap, dec_flags, src_values,
+                                                                   (const float **)(ws + L.srctab_off));
             ZEN_LAUNCH_CHECK();
         }
         {
-            uint64_t gx;
-            if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) gx = (max_in_rows + 3) / 4;
-            else gx = (max_in_rows * g.row_dim + AGG_THREADS - 1) / AGG_THREADS;
-            if (gx < 1) gx = 1;
-            if (gx > 8192) gx = 8192;
+            const uint32_t gx = gather_grid_x(g.row_dim, max_in_rows);
             ProfScope prof(ctx, K_AGG_GATHER, s);
-            agg_gather_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
-                src_values, g.row_dim, n_servers, counters, keys, rank, cap, out_values, outs, status);
+            if ((g.row_dim & 3u) == 0 && g.row_dim < 256)
+                agg_gather_group_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
+                    (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, keys, cap, rank, cap, out_values, outs, status);
+            else
+                agg_gather_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
+                    src_values, g.row_dim, n_servers, counters, keys, cap, rank, cap, out_values, outs, status);
             ZEN_LAUNCH_CHECK();
         }
         return hipSuccess;
@@ -766,7 +895,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         if (blocks > 16384) blocks = 16384;
         {
             ProfScope prof(ctx, K_AGG_CLEAR, s);
-            agg_clear_kernel<<<(uint32_t)blocks, 256, 0, s>>>(keys, n_keys, counters, n_servers * 16, status);
+            agg_clear_kernel<<<(uint32_t)blocks, 256, 0, s>>>(keys, rank, n_keys, counters, n_servers * 16, status);
             ZEN_LAUNCH_CHECK();
         }
     }
@@ -785,7 +914,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
     if (gx > 4096) gx = 4096;
     {
         ProfScope prof(ctx, K_AGG_INSERT, s);
-        agg_insert_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, n_in, g.seed, keys, cap, counters,
+        agg_insert_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, n_in, g.seed, keys, rank, cap, counters,
                                                                             max_in_rows, status);
         ZEN_LAUNCH_CHECK();
     }
@@ -831,38 +960,40 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         {
             ProfScope prof(ctx, K_AGG_FINALIZE, s);
             agg_finalize_kernel<<<dim3((uint32_t)fblocks, n_servers), AGG_THREADS, 0, s>>>(
-                g.seed, a, ustride, keys, rank, cap, counters, outs, status);
+                g.seed, a, ustride, keys, rank, cap, counters, outs, (uint32_t *)(ws + L.rowstart_off), L.rowstart_stride,
+                status);
             ZEN_LAUNCH_CHECK();
         }
     }
-
     {
-        // zero: rows <= min(max_in_rows, cap_rows) per server
-        uint64_t n_el = max_in_rows * (uint64_t)g.row_dim;
-        uint64_t zb = (n_el / 4 + AGG_THREADS - 1) / AGG_THREADS;
-        if (zb < 1) zb = 1;
-        if (zb > 2048) zb = 2048;
+        // CSR over the output rows, contributor lists (in the sort's ping-pong buffers, free by now), gather
+        uint32_t *rowstart = (uint32_t *)(ws + L.rowstart_off), *cursor = rowstart + (uint64_t)n_servers * L.rowstart_stride;
+        uint64_t *contrib = (uint64_t *)(ws + L.uniq_off);
         {
             ProfScope prof(ctx, K_AGG_ZERO, s);
-            agg_zero_kernel<<<dim3((uint32_t)zb, n_servers), AGG_THREADS, 0, s>>>(out_values, outs, g.row_dim, counters);
+            agg_rowstart_kernel<<<n_servers, 1024, 0, s>>>(counters, rowstart, cursor, L.rowstart_stride, src_values,
+                                                           (const float **)(ws + L.srctab_off));
             ZEN_LAUNCH_CHECK();
         }
-    }
-    {
-        uint64_t units;   // work units per part: rows (wave per row), rows (D==1), or elements
-        if (g.row_dim == 1) units = (per_part + AGG_THREADS - 1) / AGG_THREADS;
-        else if (g.row_dim >= 64) units = (per_part + 3) / 4;
-        else units = (per_part * g.row_dim + AGG_THREADS - 1) / AGG_THREADS;
-        if (units < 1) units = 1;
-        if (units > 8192) units = 8192;
         {
             ProfScope prof(ctx, K_AGG_ACCUM, s);
-            agg_accum_kernel<<<dim3((uint32_t)units, n_in, n_servers), AGG_THREADS, 0, s>>>(
-                src, src_values, g.seed, g.row_dim, keys, rank, cap, counters, out_values, outs);
+            agg_fill_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, g.seed, keys, rank, cap, counters, cursor,
+                                                                              L.rowstart_stride, contrib, L.uniq_cap);
             ZEN_LAUNCH_CHECK();
         }
+        const uint32_t ggx = gather_grid_x(g.row_dim, max_in_rows);
+        ProfScope prof(ctx, K_AGG_GATHER, s);
+        if ((g.row_dim & 3u) == 0 && g.row_dim < 256)
+            agg_gather_group_kernel<<<dim3((uint32_t)ggx, n_servers), AGG_THREADS, 0, s>>>(
+                (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, rowstart, L.rowstart_stride, (const uint32_t *)contrib,
+                2 * L.uniq_cap, out_values, outs, nullptr);
+        else
+            agg_gather_kernel<<<dim3((uint32_t)ggx, n_servers), AGG_THREADS, 0, s>>>(
+                src_values, g.row_dim, n_servers, counters, rowstart, L.rowstart_stride, (const uint32_t *)contrib,
+                2 * L.uniq_cap, out_values, outs, nullptr);
+        return hipGetLastError();
     }
-    return hipSuccess;
+
 }
 
 } // namespace zen

@@ -80,12 +80,15 @@ struct AggOut {
 struct AggLayout {
     uint64_t status_off;     // zen_status_info
     uint64_t counters_off;   // per server: 16 u32 (0: unique count, 1: total rows in)
+    uint64_t srctab_off;     // ZEN_MAX_BATCH device pointers: the parts' value arrays
     uint64_t keys_off;       // per server: table_cap u32 keys
     uint64_t rank_off;       // per server: table_cap u32 output rank of the slot's key
     uint64_t uniq_off;       // large path: per server 2 x uniq_cap u32 (ping-pong)
     uint64_t uniq_cap;       // = max_in_rows rounded up
     uint64_t sorthist_off;   // large path: per server sort_blocks x 256 u32
     uint64_t sort_blocks;    // radix-sort blocks per server
+    uint64_t rowstart_off;   // large path: per server uniq_cap + 64 u32 row starts, then (all servers) as many fill cursors
+    uint64_t rowstart_stride;
     uint64_t decode_off;     // bitmap parts: per (server, part) decoded indices
     uint64_t decode_stride;
     uint64_t decflags_off;   // small path: per (server, part) decode consistency flag

@@ -1,7 +1,8 @@
 """GPU parity: zen_aggregate / zen_aggregate_batch against the CPU oracle.
 
-Indices and counts bit-exact; fp32 sums within 1e-6 * sum|x| of the oracle's fp64 sum (the atomic
-summation order is not fixed), and bit-exact where a row has a single contributor.
+Indices and counts bit-exact; fp32 sums within 1e-6 * sum|x| of the oracle's fp64 sum (the device adds
+in fp32, in ascending (part, row) order), bit-exact where a row has a single contributor, and bit-identical
+between the device's table paths.
 """
 import numpy as np
 import pytest
@@ -88,6 +89,37 @@ def test_single_server_explicit_parts(oracle, zen, D, max_in_scale):
     U, idx, val = G.aggregated_to_host(out)
     assert U == ref.U and np.array_equal(idx, ref.indices)
     G.check_sums(val, ref)
+
+
+@pytest.mark.parametrize("D", [1, 4, 64, 256])
+def test_paths_agree_bit_for_bit(oracle, zen, D):
+    """Both table paths sum every output row from its contributors in ascending (part, row) order: the one-block
+    LDS path and the multi-kernel path give the same bits, run after run, whatever the workspace held."""
+    import gpu_util as G
+
+    rng = np.random.default_rng(100 + D)
+    R, n_in = 30000, 9
+    ctx = zen.ZenContext(R, D, 4, 77)
+    parts_d, total = [], 0
+    for w in range(n_in):
+        c = int(rng.integers(100, 600))
+        idx = rng.integers(0, 2000, size=c).astype(np.uint32)          # heavy overlap, duplicates inside a part
+        val = rng.standard_normal((c, D)).astype(np.float32)
+        parts_d.append((G.to_dev(idx), None, torch.from_numpy(val).cuda(),
+                        torch.tensor([c], dtype=torch.int32, device="cuda")))
+        total += c
+    results = []
+    for max_in, fill in ((total, 0), (total * 40, 0), (total * 40, -1), (total * 40, 0x3F800000)):
+        out = zen.alloc_aggregated(ctx, total)
+        ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, max_in))
+        ws[: ws.numel() // 4 * 4].view(torch.int32).fill_(fill)
+        zen.zen_aggregate(ctx, parts_d, 1, out, max_in, ws)
+        assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+        results.append(G.aggregated_to_host(out))
+    U0, idx0, val0 = results[0]
+    for U, idx, val in results[1:]:
+        assert U == U0 and np.array_equal(idx, idx0)
+        assert np.array_equal(val.view(np.uint32), val0.view(np.uint32))
 
 
 def test_disjoint_and_identical_inputs(oracle, zen):
