@@ -35,12 +35,17 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 
 // cnt[server][row][chunk]: row w < n_in = set bits of part w in the chunk, row n_in = union bits.
 __global__ void __launch_bounds__(BM_THREADS)
-bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off, uint32_t *cnt, uint32_t n_chunks)
+bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off, uint32_t *cnt, uint32_t n_chunks,
+                uint32_t *wave_tot, uint32_t *uni_words)
 {
+    // wave_tot / uni_words (element-level merges, else NULL): the same counts per wave of the block,
+    // [server][chunk][row][4], and the union words, [server][chunk][256] -- the merge starts from them
     __shared__ uint32_t s_c[ZEN_MAX_BATCH + 1];
+    __shared__ uint32_t s_wt[(ZEN_MAX_BATCH + 1) * 4];   // the same per wave of the block
     const uint32_t chunk = blockIdx.x, server = blockIdx.y, p = a.first_part + server;
     const uint32_t n_dom = dom_offsets[p + 1] - dom_offsets[p], n_words = (n_dom + 31) >> 5;
     const uint32_t k = chunk * BM_CHUNK_WORDS + threadIdx.x;
+    uint32_t *wt = wave_tot ? wave_tot + ((uint64_t)server * n_chunks + chunk) * (ZEN_MAX_BATCH + 1) * 4 : nullptr;
     if (threadIdx.x <= a.n_in) s_c[threadIdx.x] = 0;
     __syncthreads();
     uint32_t uni = 0;
@@ -53,14 +58,22 @@ bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off,
         for (uint32_t q = 0; q < 8; ++q) {
             if (w0 + q >= a.n_in) break;
             uni |= wd[q];
-            if (ballot(wd[q] != 0) == 0) continue;
-            const uint32_t s = wave_sum(__popc(wd[q]));
-            if (lane_id() == 0) atomicAdd(&s_c[w0 + q], s);
+            const uint32_t s = ballot(wd[q] != 0) ? wave_sum(__popc(wd[q])) : 0u;   // (uniform)
+            if (lane_id() == 0) {
+                if (s) atomicAdd(&s_c[w0 + q], s);
+                s_wt[(w0 + q) * 4 + (threadIdx.x >> 6)] = s;
+            }
         }
     }
     const uint32_t su = wave_sum(__popc(uni));
-    if (lane_id() == 0 && su) atomicAdd(&s_c[a.n_in], su);
+    if (lane_id() == 0) {
+        if (su) atomicAdd(&s_c[a.n_in], su);
+        s_wt[a.n_in * 4 + (threadIdx.x >> 6)] = su;
+    }
+    if (uni_words) uni_words[((uint64_t)server * n_chunks + chunk) * BM_CHUNK_WORDS + threadIdx.x] = uni;
     __syncthreads();
+    if (wt)
+        for (uint32_t i = threadIdx.x; i < (a.n_in + 1) * 4; i += BM_THREADS) wt[i] = s_wt[i];
     uint32_t *out = cnt + ((uint64_t)server * (ZEN_MAX_BATCH + 1)) * n_chunks;
     if (threadIdx.x <= a.n_in) out[(uint64_t)threadIdx.x * n_chunks + chunk] = s_c[threadIdx.x];
 }
@@ -113,7 +126,8 @@ __global__ void __launch_bounds__(BM_THREADS)
 bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_servers,
                 const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *word_off,
                 const uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_base, AggOut outs,
-                Arr64<float *> out_values, zen_status_info *status)
+                Arr64<float *> out_values, zen_status_info *status, const uint32_t *wave_tot,
+                const uint32_t *uni_words)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t chunk = blockIdx.x, server = blockIdx.y, p = a.first_part + server;
@@ -148,20 +162,11 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
         uint32_t *s_ex = s_word + ZEN_WAVE;      // exclusive count of the part's bits before each word
         uint32_t *s_uni = s_ex + ZEN_WAVE;       // union words
         uint32_t *s_uex = s_uni + ZEN_WAVE;      // exclusive count of union bits before each word
-        // pass A: union word and per-wave totals for every part
-        uint32_t uni = 0;
-        for (uint32_t w0 = 0; w0 < n_in; w0 += 8) {
-            uint32_t wd[8];
-#pragma unroll
-            for (uint32_t q = 0; q < 8; ++q)
-                wd[q] = (w0 + q < n_in && k < n_words) ? part_words(a, w0 + q, p, word_off)[k] : 0u;
-#pragma unroll
-            for (uint32_t q = 0; q < 8; ++q) {
-                if (w0 + q >= n_in) break;
-                uni |= wd[q];
-                const uint32_t s = wave_sum(__popc(wd[q]));
-                if (lane == 0) s_wtot[(w0 + q) * 4 + wave] = s;
-            }
+        // pass A: the union word and every part's per-wave totals, as the count kernel left them
+        const uint32_t uni = uni_words[((uint64_t)server * n_chunks + chunk) * BM_CHUNK_WORDS + threadIdx.x];
+        {
+            const uint32_t *wt = wave_tot + ((uint64_t)server * n_chunks + chunk) * (ZEN_MAX_BATCH + 1) * 4;
+            for (uint32_t i = threadIdx.x; i < n_in * 4; i += BM_THREADS) s_wtot[i] = wt[i];
         }
         const uint32_t uc = __popc(uni);
         const uint32_t uinc = wave_inclusive_scan(uc);
@@ -330,10 +335,12 @@ hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitm
     uint32_t *counters = (uint32_t *)(ws + L.counters_off);
     zen_status_info *status = (zen_status_info *)(ws + L.status_off);
     const uint32_t n_chunks = (uint32_t)L.bm_chunks;
+    uint32_t *wave_tot = ctx->geo.row_dim == 1 ? (uint32_t *)(ws + L.bmwave_off) : nullptr;
+    uint32_t *uni_words = ctx->geo.row_dim == 1 ? (uint32_t *)(ws + L.bmuni_off) : nullptr;
     {
         ProfScope prof(ctx, K_BM_COUNT, s);
         bm_count_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, 0, s>>>(a, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt,
-                                                                         n_chunks);
+                                                                         n_chunks, wave_tot, uni_words);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -350,7 +357,7 @@ hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitm
                                                   : (size_t)(ZEN_MAX_BATCH + 1) * BM_CHUNK_WORDS * 2);
         bm_merge_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, lds, s>>>(
             a, src_values, ctx->geo.row_dim, n_servers, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt,
-            n_chunks, counters, outs, out_values, status);
+            n_chunks, counters, outs, out_values, status, wave_tot, uni_words);
         return hipGetLastError();
     }
 }
