@@ -181,6 +181,13 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
         for (uint32_t i = lane; i < u_wave; i += ZEN_WAVE) acc[i] = 0.f;
         // pass B: every part adds its values, in part order; the wave walks the part's values (a
         // contiguous run) and finds each value's (word, bit) by searching the prefix tables
+        // lane w works out where part w's values for this wave start (one load for all parts, not one per part
+        // on the way)
+        uint32_t my_vbase = 0;
+        if (lane < n_in) {
+            my_vbase = pre[(uint64_t)lane * n_chunks + chunk];
+            for (uint32_t v = 0; v < wave; ++v) my_vbase += s_wtot[lane * 4 + v];
+        }
         for (uint32_t w0 = 0; w0 < n_in; w0 += 8) {
           uint32_t wd[8];
 #pragma unroll
@@ -191,14 +198,13 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
             const uint32_t w = w0 + q;
             if (w >= n_in) break;
             const uint32_t word = wd[q];
+            const uint32_t vbase = (uint32_t)__builtin_amdgcn_readlane((int)my_vbase, (int)w);   // every lane is active here
             if (ballot(word != 0) == 0) continue;     // wave-uniform: the part has no row in these 64 words
             const uint32_t c = __popc(word);
             const uint32_t inc = wave_inclusive_scan(c);
             const uint32_t t_wave = __shfl(inc, ZEN_WAVE - 1, ZEN_WAVE);
             s_word[lane] = word;
             s_ex[lane] = inc - c;
-            uint32_t vbase = pre[(uint64_t)w * n_chunks + chunk];
-            for (uint32_t v = 0; v < wave; ++v) vbase += s_wtot[w * 4 + v];
             const float *vals = src_values.v[w] + vbase;
             __builtin_amdgcn_wave_barrier();
             for (uint32_t i = lane; i < t_wave; i += ZEN_WAVE) {
