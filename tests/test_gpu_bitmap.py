@@ -198,3 +198,63 @@ def test_elementwise_bitmap_encode_without_index_list(oracle, zen, R, n):
         got = small.values.cpu().numpy()
         assert np.array_equal(got[:cap].view(np.uint32), ref.values[:cap].view(np.uint32))
         assert (got[cap:] == -1.0).all()
+
+
+@pytest.mark.parametrize("n,with_indices", [(64, False), (5, True), (128, True), (129, False)])
+def test_elementwise_stretch_boundaries(oracle, zen, n, with_indices):
+    """Stretches of consecutive non-zero rows placed at and around every boundary the element-level scatter
+    knows (mask word 32, group 512, the 2,048-row limit of a stretch, tile 32,768, end of the tensor), of
+    lengths around the shortest stretch it places from the rank tables (128), next to scattered rows."""
+    import gpu_util as G
+
+    R = 3 * 32768 + 1000 + 13                      # three tiles and a ragged tail
+    rng = np.random.default_rng(n)
+    wl = Workload("t", 0, R, 1, n, int(rng.integers(0, 2**32)), "uniform")
+    ctx = zen.ZenContext(R, 1, n, wl.hash_seed, zen.ZEN_INDEX_BITMAP)
+    total, _, _ = zen.zen_bitmap_layout(ctx)
+    owner = oracle.owner_table(R, n, wl.hash_seed)
+    _, word_off = oracle.bitmap_layout(owner, n)
+    masks = []
+    m = np.zeros(R, bool)                          # runs that start / end on, just before and just after boundaries
+    for start, length in [(0, 127), (512 - 1, 128), (1024, 129), (2048 + 31, 2048), (8192 - 5, 2049 + 5),
+                          (16384, 4096), (32768 - 100, 300), (2 * 32768 - 2048, 2048), (2 * 32768 + 1, 511),
+                          (3 * 32768 - 1, 2), (R - 700, 700)]:
+        m[start:start + length] = True
+    masks.append(m)
+    m = np.zeros(R, bool)                          # scattered rows running into a stretch, a stretch into scattered rows
+    m[rng.integers(0, R, size=3000)] = True
+    m[5000:5000 + 1500] = True
+    m[40000:40000 + 129] = True
+    m[70000:70000 + 5000] = True
+    m[70000 + 2500] = False                        # one hole inside a long run
+    masks.append(m)
+    masks.append(np.ones(R, bool))                 # everything
+    m = np.ones(R, bool)
+    m[::97] = False                                # nearly everything: no stretch reaches 128 rows
+    masks.append(m)
+    hosts, rowsets = [], []
+    for m in masks:
+        rows = np.flatnonzero(m).astype(np.uint32)
+        vals = rng.standard_normal((rows.size, 1)).astype(np.float32) + 4.0
+        hosts.append(dense_from_sparse(wl, rows, vals))
+        rowsets.append(rows)
+    grads = [torch.from_numpy(h).cuda() for h in hosts]
+    encs = [zen.alloc_encoded(ctx, r.size, with_indices=with_indices) for r in rowsets]
+    ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, len(grads)))
+    ws.view(torch.int32).fill_(-1)
+    zen.zen_encode_batch(ctx, grads, encs, ws)
+    assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+    for h, rows, enc in zip(hosts, rowsets, encs):
+        ref = oracle.encode(h, R, 1, n, wl.hash_seed)
+        assert np.array_equal(G.u32(enc.offsets), ref.offsets)
+        assert np.array_equal(G.u32(enc.bitmap[:total]), oracle.bitmap_encode(owner, n, oracle.member_mask(rows, R), word_off))
+        assert np.array_equal(enc.values[:ref.nnz].cpu().numpy().view(np.uint32), ref.values.view(np.uint32))
+        if with_indices:
+            assert np.array_equal(G.u32(enc.indices[:ref.nnz]), ref.indices)
+    # capacity short by a few rows in the middle of the output: flag + needed rows, nothing beyond the capacity
+    short = [zen.alloc_encoded(ctx, r.size - 7, with_indices=with_indices) for r in rowsets]
+    for e in short:
+        e.values.fill_(-1.0)
+    zen.zen_encode_batch(ctx, grads, short, ws)
+    st, flags, needed = zen.zen_status_fetch(ctx, ws)
+    assert st == 2 and (flags & 1) and needed == max(r.size for r in rowsets)
