@@ -13,6 +13,7 @@ namespace zen {
 static constexpr int AGG_THREADS = 256;
 static constexpr uint32_t GATHER_GROUP_ROWS = 4;   // output rows a lane group of the narrow-row gather keeps in flight
 static constexpr int SMALL_THREADS = 1024;
+static constexpr uint32_t SMALL_MERGE_MAX_PARTS = 16;   // small tables: parts merged by binary searches when all ascend
 static constexpr uint32_t SMALL_MAX_IN = 6500;     // rows into one server that the one-block LDS path takes:
                                                    // table of 8192 slots (load <= 0.8) x 2 arrays + 8192 sorted
                                                    // keys = 96 KB of the 160 KB LDS
@@ -216,6 +217,83 @@ agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32
             counters[CNT_NEEDED] = total_in;
         }
         return;
+    }
+    // Parts whose indices ascend strictly (what zen_encode and a decoded hash bitmap produce) need no table and
+    // no sort: an element's place in the merged sequence, ordered by (index, part), is its own place in its
+    // part plus, for every other part, the number of that part's elements before it -- a binary search each.
+    // Heads of equal-index stretches are the output rows, the stretches themselves the contributor lists,
+    // already in ascending (part, row) order.  Few parts only (the searches grow with their number).
+    if (n_in <= SMALL_MERGE_MAX_PARTS) {
+        uint32_t *s_key = smem;                    // [total_in] the parts' indices, part after part
+        uint32_t *s_merged = smem + max_in_rows;   // [total_in] the merged sequence
+        constexpr uint32_t EPT = (SMALL_MAX_IN + SMALL_THREADS - 1) / SMALL_THREADS;   // elements per thread: 7
+        uint32_t key[EPT], part[EPT];
+        uint32_t bad = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < EPT; ++q) {
+            const uint32_t e = q * SMALL_THREADS + threadIdx.x;
+            key[q] = ZEN_EMPTY_KEY;
+            part[q] = 0;
+            if (e < total_in) {
+                uint32_t lo = 0, hi = n_in;
+                while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (s_pre[mid] <= e) lo = mid; else hi = mid; }
+                part[q] = lo;
+                key[q] = s_idx[lo][s_begin[lo] + (e - s_pre[lo])];
+                s_key[e] = key[q];
+                bad |= key[q] == ZEN_EMPTY_KEY ? 1u : 0u;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t q = 0; q < EPT; ++q) {
+            const uint32_t e = q * SMALL_THREADS + threadIdx.x;
+            if (e < total_in && e > s_pre[part[q]]) bad |= s_key[e - 1] >= key[q] ? 1u : 0u;
+        }
+        if (!__syncthreads_or((int)bad)) {
+#pragma unroll
+            for (uint32_t q = 0; q < EPT; ++q) {
+                const uint32_t e = q * SMALL_THREADS + threadIdx.x;
+                if (e >= total_in) continue;
+                const uint32_t w = part[q], v = key[q];
+                uint32_t pos = e - s_pre[w];
+                for (uint32_t o = 0; o < n_in; ++o) {
+                    if (o == w) continue;
+                    // elements of part o before (v, w): those < v, and an equal one if o < w
+                    uint32_t lo = s_pre[o], hi = s_pre[o + 1];
+                    const uint32_t limit = o < w ? v + 1u : v;      // count elements < limit (v + 1 wraps only for the reserved key)
+                    while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (s_key[mid] < limit) lo = mid + 1; else hi = mid; }
+                    pos += lo - s_pre[o];
+                }
+                s_merged[pos] = v;
+                contrib[pos] = ((uint64_t)w << 32) | (uint64_t)(s_vbegin[w] + (e - s_pre[w]));
+            }
+            __syncthreads();
+            // heads -> output rows
+            const uint64_t cap_rows = outs.cap_rows[server];
+            uint32_t *out_idx = outs.indices[server];
+            const uint32_t per = (total_in + blockDim.x - 1) / blockDim.x;
+            const uint32_t a0 = min(threadIdx.x * per, total_in), a1 = min(a0 + per, total_in);
+            uint32_t heads = 0;
+            for (uint32_t a = a0; a < a1; ++a) heads += (a == 0 || s_merged[a] != s_merged[a - 1]) ? 1u : 0u;
+            uint32_t U;
+            uint32_t u = block_exclusive_scan(heads, s_tmp, &U);
+            for (uint32_t a = a0; a < a1; ++a) {
+                if (a == 0 || s_merged[a] != s_merged[a - 1]) {
+                    rowstart[u] = a;
+                    if (u < cap_rows) out_idx[u] = s_merged[a];
+                    ++u;
+                }
+            }
+            if (threadIdx.x == 0) {
+                rowstart[U] = total_in;
+                *outs.count[server] = U;
+                counters[CNT_UNIQUE] = U;
+                counters[CNT_SKIP] = 0;
+                counters[CNT_FLAGS] = flags | ((uint64_t)U > cap_rows ? 1u : 0u);
+                counters[CNT_NEEDED] = (uint64_t)U > cap_rows ? U : 0u;
+            }
+            return;
+        }
     }
     for (uint32_t i = threadIdx.x; i < cap; i += blockDim.x) { tkeys[i] = ZEN_EMPTY_KEY; tval[i] = 0; }
     __syncthreads();
