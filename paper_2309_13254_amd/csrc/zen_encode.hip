@@ -485,8 +485,8 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
         const uint32_t *gmask = wmask + (uint64_t)tile * g.tile_words;
         if (ELEM) {
             __syncthreads();                                   // the barrier between tiles
-            // The tile's mask goes to LDS with a row count per 64-word segment: empty segments then cost
-            // neither a memory access nor a barrier, and sparse neighbours are expanded together.
+            // The tile's mask goes to LDS with a row count per 16-word group: empty groups then cost neither a
+            // memory access nor a barrier, and sparse neighbours are expanded together.
             for (uint32_t q0 = 0; q0 * SCATTER_THREADS < g.tile_words; q0 += 8) {
                 if (!pf_ok) {
 #pragma unroll
