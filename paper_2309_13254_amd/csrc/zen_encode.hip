@@ -535,10 +535,22 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
         const uint64_t row0 = (uint64_t)tile * g.tile_rows;
         for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_run[i] = ghist[i];
 
-        uint32_t bm_words = 0;
         if (bitmap) {
-            // per-partition bit ranges of this tile and their LDS placement
+            // per-partition bit ranges of this tile and their LDS placement (what follows meets a barrier
+            // before it uses them)
             const uint32_t *tb0 = bt.tile_base + (uint64_t)tile * n, *tb1 = tb0 + n;
+            if (n <= ZEN_WAVE) {                    // the first wave alone: a scan without block barriers
+                if (threadIdx.x < ZEN_WAVE) {
+                    const uint32_t p = threadIdx.x;
+                    uint32_t b0 = 0, b1 = 0;
+                    if (p < n) { b0 = tb0[p]; b1 = tb1[p]; }
+                    const uint32_t wcnt = b1 > b0 ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0;
+                    const uint32_t inc = wave_inclusive_scan(wcnt);
+                    if (p < n) { s_b0[p] = b0; s_b1[p] = b1; s_boff[p] = inc - wcnt; }
+                    if (p == n - 1) s_boff[n] = inc;
+                }
+            } else {
+            uint32_t bm_words = 0;
             const uint32_t per = (n + blockDim.x - 1) / blockDim.x;   // consecutive partitions per thread
             const uint32_t p0 = min(threadIdx.x * per, n), p1 = min(p0 + per, n);
             uint32_t mine = 0;
@@ -555,7 +567,8 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 off += b1 > b0 ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0;
             }
             if (threadIdx.x == 0) s_boff[n] = bm_words;
-            for (uint32_t i = threadIdx.x; i < bm_words; i += blockDim.x) s_bm[i] = 0;
+            }
+            for (uint32_t i = threadIdx.x; i < g.tile_words + 2 * n; i += blockDim.x) s_bm[i] = 0;
         }
 
         const uint32_t seg_words = ELEM ? GROUP_WORDS : SEG_WORDS;
@@ -633,21 +646,30 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                             if (out_val) fv[q] = grad[ra + i];
                         }
                     }
+                    // n <= ZEN_GROUP_MAX_PARTS <= blockDim.x: one thread per partition
+                    uint32_t fa = 0, fb = 0;
+                    if (threadIdx.x < n) {
+                        fa = bt.group_base[(uint64_t)(ra / ZEN_GROUP_ROWS) * n + threadIdx.x];
+                        fb = bt.group_base[(uint64_t)(rb / ZEN_GROUP_ROWS) * n + threadIdx.x];
+                    }
                     for (uint32_t r = (ra & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < ra; r += SCATTER_THREADS)
                         atomicAdd(&s_cnt[owner_of(r, g.seed, n, g.pow2_mask)], 1u);
                     for (uint32_t r = (rb & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < rb; r += SCATTER_THREADS)
                         atomicAdd(&s_cnt[n + owner_of(r, g.seed, n, g.pow2_mask)], 1u);
                     __syncthreads();
-                    // n <= ZEN_GROUP_MAX_PARTS <= blockDim.x: one thread per partition
-                    uint32_t fa = 0, fb = 0;
                     if (threadIdx.x < n) {
-                        fa = bt.group_base[(uint64_t)(ra / ZEN_GROUP_ROWS) * n + threadIdx.x] + s_cnt[threadIdx.x];
-                        fb = bt.group_base[(uint64_t)(rb / ZEN_GROUP_ROWS) * n + threadIdx.x] + s_cnt[n + threadIdx.x];
+                        fa += s_cnt[threadIdx.x];
+                        fb += s_cnt[n + threadIdx.x];
                         s_cnt[threadIdx.x] = 0;          // the ranking scratch is all zero between its uses
                         s_cnt[n + threadIdx.x] = 0;
                     }
-                    uint32_t stretch_rows;
-                    const uint32_t loff = block_exclusive_scan(fb - fa, s_tmp, &stretch_rows);   // (barriers inside)
+                    uint32_t loff;                       // rows of the partitions before mine in this stretch
+                    if (n <= ZEN_WAVE) {                 // the first wave alone, no block barrier
+                        loff = threadIdx.x < ZEN_WAVE ? wave_inclusive_scan(fb - fa) - (fb - fa) : 0u;
+                    } else {
+                        uint32_t stretch_rows;
+                        loff = block_exclusive_scan(fb - fa, s_tmp, &stretch_rows);
+                    }
                     if (threadIdx.x < n) {
                         const uint32_t p = threadIdx.x, run = s_run[p];
                         s_delta[p] = loff - fa;          // LDS slot   = s_delta[p] + rank
@@ -892,20 +914,19 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 
         if (bitmap) {
             __syncthreads();
-            for (uint32_t lw = threadIdx.x; lw < bm_words; lw += blockDim.x) {
-                const uint32_t v = s_bm[lw];
-                if (!v) continue;
-                // partition whose LDS range holds lw: last p with s_boff[p] <= lw
-                uint32_t lo = 0, hi = n;
-                while (hi - lo > 1) {
-                    const uint32_t mid = (lo + hi) >> 1;
-                    if (s_boff[mid] <= lw) lo = mid; else hi = mid;
+            // a few threads per partition walk its words (no search for the partition a word belongs to)
+            const uint32_t tpp = blockDim.x >= n ? blockDim.x / n : 1u, sub = threadIdx.x % tpp;
+            for (uint32_t p = threadIdx.x / tpp; p < n; p += blockDim.x / tpp) {
+                const uint32_t b0 = s_b0[p], b1 = s_b1[p];
+                if (b1 <= b0) continue;
+                const uint32_t lw0 = s_boff[p], last = ((b1 - 1) >> 5) - (b0 >> 5);
+                uint32_t *dst = out_bm + bt.word_off[p] + (b0 >> 5);
+                for (uint32_t k = sub; k <= last; k += tpp) {
+                    const uint32_t v = s_bm[lw0 + k];
+                    if (!v) continue;
+                    const bool shared = (k == 0 && (b0 & 31u)) || (k == last && (b1 & 31u));
+                    if (shared) atomicOr(dst + k, v); else dst[k] = v;
                 }
-                const uint32_t p = lo, b0 = s_b0[p], b1 = s_b1[p];
-                const uint32_t k = lw - s_boff[p], last = ((b1 - 1) >> 5) - (b0 >> 5);
-                uint32_t *dst = out_bm + bt.word_off[p] + (b0 >> 5) + k;
-                const bool shared = (k == 0 && (b0 & 31u)) || (k == last && (b1 & 31u));
-                if (shared) atomicOr(dst, v); else *dst = v;
             }
         }
     }
