@@ -578,6 +578,8 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
         uint32_t cur_blk = 0xFFFFFFFFu, cnt_l = 0;
         uint64_t nz_m = 0, full_m = 0;
         uint32_t cur = 0;   // element-level: row offset inside the tile below which everything is done
+        uint32_t prev_rb = 0xFFFFFFFFu, prev_fb = 0;   // end of the last stretch placed from the rank tables, and (thread p)
+                                                       // the rank of partition p's first row at or after it
         for (uint32_t sg = 0; sg < n_seg;) {
             // (a) expand mask words into the ascending row list: 64 words at a time, or -- element-level
             // inputs -- as many consecutive 16-word groups as together hold at most SEG_ROWS rows (a
@@ -646,23 +648,31 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                             if (out_val) fv[q] = grad[ra + i];
                         }
                     }
-                    // n <= ZEN_GROUP_MAX_PARTS <= blockDim.x: one thread per partition
-                    uint32_t fa = 0, fb = 0;
+                    // n <= ZEN_GROUP_MAX_PARTS <= blockDim.x: one thread per partition.  A stretch that starts where
+                    // the last one ended (a run longer than SEG_ROWS) takes over its end ranks.
+                    const bool carry = ra == prev_rb;     // uniform
+                    uint32_t fa = prev_fb, fb = 0;
                     if (threadIdx.x < n) {
-                        fa = bt.group_base[(uint64_t)(ra / ZEN_GROUP_ROWS) * n + threadIdx.x];
+                        if (!carry) fa = bt.group_base[(uint64_t)(ra / ZEN_GROUP_ROWS) * n + threadIdx.x];
                         fb = bt.group_base[(uint64_t)(rb / ZEN_GROUP_ROWS) * n + threadIdx.x];
                     }
-                    for (uint32_t r = (ra & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < ra; r += SCATTER_THREADS)
-                        atomicAdd(&s_cnt[owner_of(r, g.seed, n, g.pow2_mask)], 1u);
+                    uint32_t pp[FB];                      // owners, hashed while the loads are under way
+#pragma unroll
+                    for (uint32_t q = 0; q < FB; ++q) pp[q] = owner_of(ra + q * SCATTER_THREADS + threadIdx.x, g.seed, n, g.pow2_mask);
+                    if (!carry)
+                        for (uint32_t r = (ra & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < ra; r += SCATTER_THREADS)
+                            atomicAdd(&s_cnt[owner_of(r, g.seed, n, g.pow2_mask)], 1u);
                     for (uint32_t r = (rb & ~(ZEN_GROUP_ROWS - 1)) + threadIdx.x; r < rb; r += SCATTER_THREADS)
                         atomicAdd(&s_cnt[n + owner_of(r, g.seed, n, g.pow2_mask)], 1u);
                     __syncthreads();
                     if (threadIdx.x < n) {
-                        fa += s_cnt[threadIdx.x];
+                        fa += s_cnt[threadIdx.x];        // (zero when the ranks were taken over)
                         fb += s_cnt[n + threadIdx.x];
                         s_cnt[threadIdx.x] = 0;          // the ranking scratch is all zero between its uses
                         s_cnt[n + threadIdx.x] = 0;
                     }
+                    prev_rb = rb;
+                    prev_fb = fb;
                     uint32_t loff;                       // rows of the partitions before mine in this stretch
                     if (n <= ZEN_WAVE) {                 // the first wave alone, no block barrier
                         loff = threadIdx.x < ZEN_WAVE ? wave_inclusive_scan(fb - fa) - (fb - fa) : 0u;
@@ -692,7 +702,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                         const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
                         if (i < cnt) {
                             const uint32_t row = ra + i;
-                            const uint32_t p = owner_of(row, g.seed, n, g.pow2_mask);
+                            const uint32_t p = pp[q];
                             const uint32_t slot = s_delta[p] + fr[q];
                             const uint32_t pos = s_goff[p] + slot;
                             if (slot < SEG_ROWS) {       // always, for consistent tables
