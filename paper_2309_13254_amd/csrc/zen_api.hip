@@ -64,7 +64,7 @@ EncodeLayout encode_layout(const Geometry &g, uint32_t batch)
     L.hist_off = off; off += L.hist_stride * batch;
     L.flag_stride = align_up((uint64_t)g.n_tiles * 4, 256);
     L.flag_off = off; off += L.flag_stride * batch;
-    L.list_stride = align_up(((uint64_t)g.n_tiles + 1) * 4, 256);
+    L.list_stride = align_up(2 * ((uint64_t)g.n_tiles + 1) * 4, 256);   // ids, their number, the listed tiles' flag words
     L.list_off = off; off += L.list_stride * batch;
     L.total = off;
     return L;
@@ -128,7 +128,7 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
         ok = ok && hipMalloc(&ctx->d_dom_offsets, (n + 1) * 4) == hipSuccess;
         ok = ok && hipMalloc(&ctx->d_bm_word_off, (n + 1) * 4) == hipSuccess;
         ok = ok && hipMalloc(&ctx->d_dom_tile_base, ((uint64_t)g.n_tiles + 1) * n * 4) == hipSuccess;
-        ok = ok && hipMalloc(&tmp_mask, ((uint64_t)g.n_tiles * g.tile_words + 2 * (uint64_t)g.n_tiles + 1) * 4) == hipSuccess;   // mask + tile flags + tile list
+        ok = ok && hipMalloc(&tmp_mask, ((uint64_t)g.n_tiles * g.tile_words + 3 * (uint64_t)g.n_tiles + 2) * 4) == hipSuccess;   // mask + tile flags + tile list (ids, count, flag words)
         ok = ok && hipMalloc(&tmp_status, 256) == hipSuccess;
         zen_status st = ok ? ZEN_OK : ZEN_ERR_NOMEM;
         if (ok) {
@@ -256,7 +256,7 @@ static zen_status encode_batch_impl(zen_ctx *ctx, const float *const *host_grads
             HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, false, s, thr));
             HIP_TRY(launch_encode_small(ctx, grads, outs, nb, ws, L, s));
         } else {
-            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, true, s, thr));
+            HIP_TRY(launch_detect(ctx, grads, nb, ws, L, w0 == 0, true, s, thr, true));   // masks by segment: the scatter reads them through the flag words
             HIP_TRY(launch_partition_scan(ctx, outs, nb, ws, L, s));
             HIP_TRY(launch_scatter(ctx, grads, outs, nb, ws, L, s));
         }

@@ -25,6 +25,7 @@ static constexpr int SCAN_THREADS = 1024;
 static constexpr uint32_t SCAN_FLAG_WORDS = 4096; // partition scan: tile flags kept as bits in LDS up to 131,072 tiles
 static constexpr int SEG_WORDS = 64;              // mask words expanded per scatter segment
 static constexpr int SEG_ROWS = SEG_WORDS * 32;   // 2048
+static constexpr uint32_t SEG_FLAG_WORDS = 32;    // mask words per bit of a tile's flag word (tiles of 1,024 words)
 static constexpr int GROUP_WORDS = ZEN_GROUP_ROWS / 32;   // 16 mask words: the unit the element-level scatter counts rows in
 static constexpr uint32_t MIN_STRETCH_ROWS = 128;  // shortest stretch of consecutive listed rows placed from the rank tables
 
@@ -187,8 +188,11 @@ template <int PATH>
 __global__ void __launch_bounds__(DETECT_THREADS)
 detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
               uint32_t *hist_base, uint64_t hist_stride_words, uint32_t *tflag_base, uint64_t tflag_stride,
-              zen_status_info *reset_status, const uint32_t *min_mag)
+              zen_status_info *reset_status, const uint32_t *min_mag, uint32_t seg_flags)
 {
+    // seg_flags (element-level tiles of SEG_FLAG_WORDS * 32 mask words only): the tile's flag word says which of its
+    // 32 segments hold a non-zero row, and only those segments' mask words are written -- for a consumer that
+    // reads the mask through the flag word (the scatter).  Otherwise a non-empty tile's flag is all ones.
     // min_mag (element-level inputs only, may be NULL): per worker, the magnitude threshold of a top-k
     // sparsifier applied on the fly -- elements below it are treated as zeros
     extern __shared__ uint32_t smem[];
@@ -213,16 +217,30 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
     else detect_row<1>(grad, g.n_rows, g.row_dim, row0, g.tile_rows, s_mask);
     __syncthreads();
 
-    // Tile flag: 1 iff the tile holds a non-zero row.  Mask words and histogram rows of empty tiles
+    // Tile flag: non-zero iff the tile holds a non-zero row.  Mask words and histogram rows of empty tiles
     // are NOT written (every consumer looks at the flag first): for sparse inputs that removes most
     // of the write traffic, which costs the streaming read far more than its byte share.
     // Used where a tile has many mask words (element-level inputs); elsewhere the mask itself is
     // as small as a flag array would be and everything is always written.
+    uint32_t flag_word = 0xFFFFFFFFu;
     if (g.sparse_mask) {
+        __shared__ uint32_t s_segbits;
+        const bool by_segment = PATH == 0 && seg_flags && g.tile_words == SEG_FLAG_WORDS * 32 && (blockDim.x & 63u) == 0;
         uint32_t any = 0;
+        if (threadIdx.x == 0) s_segbits = 0;
         for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) any |= s_mask[i];
         const int flag = __syncthreads_or((int)(any != 0));
-        if (threadIdx.x == 0) tflag_base[worker * tflag_stride + tile] = flag ? 1u : 0u;
+        if (flag && by_segment) {
+            // a wave's 64 consecutive words are two segments
+            for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) {
+                const uint64_t nzb = ballot(s_mask[i] != 0);
+                const uint32_t two = ((uint32_t)nzb ? 1u : 0u) | ((uint32_t)(nzb >> 32) ? 2u : 0u);
+                if (lane_id() == 0 && two) atomicOr(&s_segbits, two << ((i / SEG_FLAG_WORDS) & 31u));
+            }
+            __syncthreads();
+            flag_word = s_segbits;
+        }
+        if (threadIdx.x == 0) tflag_base[worker * tflag_stride + tile] = flag ? flag_word : 0u;
         if (!flag) {
             if (!(g.sparse_mask & 2u) && hist_base) {   // histogram rows are kept valid for every tile: a zero row
                 uint32_t *gh = hist_base + worker * hist_stride_words + (uint64_t)tile * g.n_parts;
@@ -232,7 +250,8 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
         }
     }
     uint32_t *gmask = mask_base + worker * mask_stride_words + (uint64_t)tile * g.tile_words;
-    for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x) gmask[i] = s_mask[i];
+    for (uint32_t i = threadIdx.x; i < g.tile_words; i += blockDim.x)
+        if ((flag_word >> ((i / SEG_FLAG_WORDS) & 31u)) & 1u) gmask[i] = s_mask[i];
     if (!hist_base) return;   // the one-block-per-worker partition path hashes the rows itself
     // owner histogram of the tile's non-zero rows: walk the mask words, most of them are zero
     if (g.tile_words >= blockDim.x) {
@@ -370,7 +389,7 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
         }
     }
     // For the scatter: ascending list of the worker's non-empty tiles (all tiles when the geometry
-    // carries no tile flags), its length behind it.
+    // carries no tile flags), its length behind it, and behind that the listed tiles' flag words.
     if (tlist_base) {
         uint32_t *tlist = tlist_base + worker * tlist_stride;
         uint32_t listed = 0;
@@ -381,7 +400,9 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
                 uint32_t word = w < n_fw ? s_fbits[w] : 0u, total;
                 uint32_t at = listed + block_exclusive_scan(__popc(word), s_tmp, &total);
                 while (word) {
-                    tlist[at++] = w * 32 + (uint32_t)__ffs((int)word) - 1;
+                    const uint32_t t = w * 32 + (uint32_t)__ffs((int)word) - 1;
+                    tlist[(g.n_tiles + 1) + at] = g.sparse_mask ? tflag[t] : 0xFFFFFFFFu;
+                    tlist[at++] = t;
                     word &= word - 1;
                 }
                 listed += total;
@@ -392,7 +413,10 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
             const uint32_t f = (t < g.n_tiles && (!g.sparse_mask || tflag[t])) ? 1u : 0u;
             uint32_t total;
             const uint32_t pre = block_exclusive_scan(f, s_tmp, &total);
-            if (f) tlist[listed + pre] = t;
+            if (f) {
+                tlist[listed + pre] = t;
+                tlist[(g.n_tiles + 1) + listed + pre] = g.sparse_mask ? tflag[t] : 0xFFFFFFFFu;
+            }
             listed += total;
         }
         if (threadIdx.x == 0) tlist[g.n_tiles] = listed;
@@ -473,15 +497,21 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     uint32_t k = blockIdx.x;
     uint32_t nxt_tile = k < n_visit ? min(tlist[k], g.n_tiles - 1) : 0u;
     uint32_t nxt2_tile = k + gridDim.x < n_visit ? min(tlist[k + gridDim.x], g.n_tiles - 1) : 0u;
+    // element-level: the listed tiles' flag words (behind the list) say which 32-word segments of a tile's mask
+    // were written; the others read as zero
+    const uint32_t *tlflag = tlist + (g.n_tiles + 1);
+    uint32_t nxt_flag = (ELEM && k < n_visit) ? tlflag[k] : 0u;
+    uint32_t nxt2_flag = (ELEM && k + gridDim.x < n_visit) ? tlflag[k + gridDim.x] : 0u;
+    auto seg_written = [](uint32_t flag_word, uint32_t i) -> bool { return (flag_word >> ((i / SEG_FLAG_WORDS) & 31u)) & 1u; };
     if (ELEM && pf_ok && k < n_visit) {
 #pragma unroll
         for (uint32_t q = 0; q < 8; ++q) {
             const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
-            if (i < g.tile_words) mw[q] = wmask[(uint64_t)nxt_tile * g.tile_words + i];
+            if (i < g.tile_words && seg_written(nxt_flag, i)) mw[q] = wmask[(uint64_t)nxt_tile * g.tile_words + i];
         }
     }
     for (; k < n_visit; k += gridDim.x) {
-        const uint32_t tile = nxt_tile;
+        const uint32_t tile = nxt_tile, tile_flag = nxt_flag;
         const uint32_t *gmask = wmask + (uint64_t)tile * g.tile_words;
         if (ELEM) {
             __syncthreads();                                   // the barrier between tiles
@@ -492,7 +522,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 #pragma unroll
                     for (uint32_t q = 0; q < 8; ++q) {
                         const uint32_t i = (q0 + q) * SCATTER_THREADS + threadIdx.x;
-                        mw[q] = i < g.tile_words ? gmask[i] : 0u;
+                        mw[q] = (i < g.tile_words && seg_written(tile_flag, i)) ? gmask[i] : 0u;
                     }
                 }
 #pragma unroll
@@ -508,13 +538,15 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 }
             }
             nxt_tile = nxt2_tile;
+            nxt_flag = nxt2_flag;
             const uint32_t k2 = k + 2 * gridDim.x;
             nxt2_tile = k2 < n_visit ? min(tlist[k2], g.n_tiles - 1) : 0u;
+            nxt2_flag = k2 < n_visit ? tlflag[k2] : 0u;
             if (pf_ok && k + gridDim.x < n_visit) {
 #pragma unroll
                 for (uint32_t q = 0; q < 8; ++q) {
                     const uint32_t i = q * SCATTER_THREADS + threadIdx.x;
-                    mw[q] = i < g.tile_words ? wmask[(uint64_t)nxt_tile * g.tile_words + i] : 0u;
+                    mw[q] = (i < g.tile_words && seg_written(nxt_flag, i)) ? wmask[(uint64_t)nxt_tile * g.tile_words + i] : 0u;
                 }
             }
             __syncthreads();
@@ -1057,7 +1089,7 @@ hipError_t launch_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, 
 
 hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
                          const EncodeLayout &L, bool reset_status, bool want_hist, hipStream_t s,
-                         const uint32_t *min_mag)
+                         const uint32_t *min_mag, bool seg_flags)
 {
     if (min_mag && ctx->geo.mode != MODE_ELEM) return hipErrorInvalidValue;
     const Geometry &g = ctx->geo;
@@ -1075,7 +1107,7 @@ hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, ch
     case P:                                                                                                \
         detect_kernel<P><<<grid, DETECT_THREADS, lds, s>>>(g, grads, mask, L.mask_stride / 4, hist,        \
                                                           L.hist_stride / 4, tflag, L.flag_stride / 4, rs, \
-                                                          min_mag);                                        \
+                                                          min_mag, seg_flags ? 1u : 0u);                   \
         break;
     switch (path) {
         ZEN_DETECT_CASE(0) ZEN_DETECT_CASE(1) ZEN_DETECT_CASE(2) ZEN_DETECT_CASE(3) ZEN_DETECT_CASE(4)
@@ -1402,7 +1434,7 @@ hist_from_mask_kernel(Geometry g, const uint32_t *mask, uint32_t *hist, uint32_t
             atomicAdd(&s_hist[owner_of((uint32_t)(row0 + r), g.seed, g.n_parts, g.pow2_mask)], 1u);
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < g.n_parts; i += blockDim.x) hist[(uint64_t)tile * g.n_parts + i] = s_hist[i];
-    if (threadIdx.x == 0) tflag[tile] = 1u;   // every tile of the all-rows mask holds rows
+    if (threadIdx.x == 0) tflag[tile] = 0xFFFFFFFFu;   // every tile of the all-rows mask holds rows, in every segment
 }
 
 // rank[domain[pos]] = pos - dom_offsets[owner]
@@ -1447,7 +1479,7 @@ hipError_t build_domain_tables(zen_ctx *ctx, uint32_t *tmp_mask, zen_status_info
     outs.offsets[0] = ctx->d_dom_offsets;
     outs.indices[0] = ctx->d_domain;
     outs.cap_rows[0] = g.n_rows;
-    uint32_t *tlist = tflag + g.n_tiles;    // ... and n_tiles + 1 list words behind the flags
+    uint32_t *tlist = tflag + g.n_tiles;    // ... and 2 * (n_tiles + 1) list words (ids, count, flag words) behind the flags
     partition_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(g, outs, ctx->d_dom_tile_base, 0, tflag, 0, tlist, 0, tmp_status);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     GradPtrs grads;

@@ -44,7 +44,8 @@ struct EncodeLayout {
     uint64_t hist_stride;
     uint64_t flag_off;       // per worker: n_tiles u32, 1 = the tile has a non-zero row (its mask words and
     uint64_t flag_stride;    //             histogram row exist), 0 = empty tile (nothing else was written)
-    uint64_t list_off;       // per worker: n_tiles + 1 u32, ascending ids of the flagged tiles, then their number
+    uint64_t list_off;       // per worker: 2 * (n_tiles + 1) u32: ascending ids of the flagged tiles, their number (at n_tiles),
+                             //             then the listed tiles' flag words
     uint64_t list_stride;
     uint64_t total;
 };
@@ -166,7 +167,7 @@ struct ProfScope {
 
 hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, char *ws,
                          const EncodeLayout &L, bool reset_status, bool want_hist, hipStream_t s,
-                         const uint32_t *min_mag = nullptr);
+                         const uint32_t *min_mag = nullptr, bool seg_flags = false);
 bool encode_small_applies(const zen_ctx *ctx, const EncodedPtrs &outs, uint32_t batch);
 hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const EncodedPtrs &outs, uint32_t batch,
                                char *ws, const EncodeLayout &L, hipStream_t s);
