@@ -154,6 +154,15 @@ agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base
     }
 }
 
+// The parts' value arrays as a table in memory (kernel arguments can only be indexed uniformly without a loop
+// over the distinct indices: constant indices here, one thread each).
+__device__ __forceinline__ void write_src_table(const Arr64<const float *> &src_values, const float **src_tab)
+{
+#pragma unroll
+    for (uint32_t w = 0; w < ZEN_MAX_BATCH; ++w)
+        if (threadIdx.x == w) src_tab[w] = src_values.v[w];
+}
+
 // ----------------------------------------------------------------------------------------------
 // Small tables (max_in_rows <= SMALL_MAX_IN): the whole merge of one server runs in one block with
 // the open-addressing table in LDS.
@@ -176,7 +185,7 @@ agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32
                  uint32_t *counters_base, AggOut outs, uint32_t *rowstart_base, uint32_t *contrib_base,
                  uint64_t ws_stride, const uint32_t *dec_flags, Arr64<const float *> src_values, const float **src_tab)
 {
-    if (blockIdx.x == 0 && threadIdx.x < ZEN_MAX_BATCH) src_tab[threadIdx.x] = src_values.v[threadIdx.x];   // for the gather
+    if (src_tab && blockIdx.x == 0) write_src_table(src_values, src_tab);   // for the gather of narrow rows
     extern __shared__ uint32_t smem[];
     uint32_t *tkeys = smem;                 // [cap]
     uint32_t *tval = tkeys + cap;           // [cap] occurrences, later the fill cursor
@@ -787,7 +796,7 @@ agg_rowstart_kernel(const uint32_t *counters_base, uint32_t *rowstart_base, uint
 {
     __shared__ uint32_t s_tmp[32];
     const uint32_t server = blockIdx.x;
-    if (server == 0 && threadIdx.x < ZEN_MAX_BATCH) src_tab[threadIdx.x] = src_values.v[threadIdx.x];   // for the gather
+    if (src_tab && server == 0) write_src_table(src_values, src_tab);   // for the gather of narrow rows
     const uint32_t *counters = counters_base + server * 16;
     const uint32_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
     uint32_t *rowstart = rowstart_base + (uint64_t)server * stride, *cursor = cursor_base + (uint64_t)server * stride;
@@ -917,6 +926,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
     uint32_t *rank = (uint32_t *)(ws + L.rank_off);
     const uint64_t cap = L.table_cap;
     const uint64_t n_keys = (uint64_t)n_servers * cap;
+    const bool narrow_rows = (g.row_dim & 3u) == 0 && g.row_dim < 256;   // summed by agg_gather_group_kernel
 
     bool any_bitmap = false;
     for (uint32_t w = 0; w < n_in; ++w) any_bitmap |= (src.indices[w] == nullptr);
@@ -955,13 +965,13 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
             ProfScope prof(ctx, K_AGG_SORT_SMALL, s);
             agg_small_kernel<<<n_servers, SMALL_THREADS, lds, s>>>(src, n_in, g.seed, lcap, (uint32_t)max_in_rows,
                                                                    counters, outs, keys, rank, cap, dec_flags, src_values,
-                                                                   (const float **)(ws + L.srctab_off));
+                                                                   narrow_rows ? (const float **)(ws + L.srctab_off) : nullptr);
             ZEN_LAUNCH_CHECK();
         }
         {
             const uint32_t gx = gather_grid_x(g.row_dim, max_in_rows);
             ProfScope prof(ctx, K_AGG_GATHER, s);
-            if ((g.row_dim & 3u) == 0 && g.row_dim < 256)
+            if (narrow_rows)
                 agg_gather_group_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
                     (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, keys, cap, rank, cap, out_values, outs, status);
             else
@@ -1054,7 +1064,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         {
             ProfScope prof(ctx, K_AGG_ZERO, s);
             agg_rowstart_kernel<<<n_servers, 1024, 0, s>>>(counters, rowstart, cursor, L.rowstart_stride, src_values,
-                                                           (const float **)(ws + L.srctab_off));
+                                                           narrow_rows ? (const float **)(ws + L.srctab_off) : nullptr);
             ZEN_LAUNCH_CHECK();
         }
         {
@@ -1065,7 +1075,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         }
         const uint32_t ggx = gather_grid_x(g.row_dim, max_in_rows);
         ProfScope prof(ctx, K_AGG_GATHER, s);
-        if ((g.row_dim & 3u) == 0 && g.row_dim < 256)
+        if (narrow_rows)
             agg_gather_group_kernel<<<dim3((uint32_t)ggx, n_servers), AGG_THREADS, 0, s>>>(
                 (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, rowstart, L.rowstart_stride, (const uint32_t *)contrib,
                 2 * L.uniq_cap, out_values, outs, nullptr);
