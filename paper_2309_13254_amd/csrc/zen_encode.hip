@@ -1046,6 +1046,34 @@ __global__ void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v)
         p[i] = v;
 }
 
+// The hash bitmaps of all workers of a launch group are assembled with OR: cleared first, in one launch (a fill
+// kernel, not a memset node), 16 bytes per store where the pointer allows.
+__global__ void __launch_bounds__(256) bitmap_clear_kernel(EncodedPtrs outs, uint64_t n_words)
+{
+    uint32_t *p = outs.bitmap[blockIdx.y];
+    if (!p) return;
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, nt = (uint64_t)gridDim.x * blockDim.x;
+    if (((uintptr_t)p & 15u) == 0) {
+        u32x4 *p4 = (u32x4 *)p;
+        for (uint64_t i = tid; i < (n_words >> 2); i += nt) p4[i] = (u32x4){0u, 0u, 0u, 0u};
+        for (uint64_t i = (n_words & ~3ull) + tid; i < n_words; i += nt) p[i] = 0u;
+    } else {
+        for (uint64_t i = tid; i < n_words; i += nt) p[i] = 0u;
+    }
+}
+
+static hipError_t launch_bitmap_clear(const EncodedPtrs &outs, uint32_t batch, uint64_t n_words, hipStream_t s)
+{
+    bool any = false;
+    for (uint32_t w = 0; w < batch; ++w) any |= outs.bitmap[w] != nullptr;
+    if (!any || n_words == 0) return hipSuccess;
+    uint64_t blocks = (n_words / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    bitmap_clear_kernel<<<dim3((uint32_t)blocks, batch), 256, 0, s>>>(outs, n_words);
+    return hipGetLastError();
+}
+
 // Plain streaming copy: the reference kernel against which hardware HBM byte counters are scaled.
 __global__ void __launch_bounds__(256) copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, uint64_t n_vec)
 {
@@ -1149,12 +1177,8 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
     const Geometry &g = ctx->geo;
     BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off, ctx->d_group_base};
     if (g.bitmap) {
-        // the bitmap is assembled with OR: clear it first (a fill kernel, not a memset node)
-        for (uint32_t w = 0; w < batch; ++w) {
-            if (!outs.bitmap[w]) continue;
-            hipError_t e = launch_fill_u32(outs.bitmap[w], ctx->bm_total_words, 0u, s);
-            if (e != hipSuccess) return e;
-        }
+        const hipError_t e = launch_bitmap_clear(outs, batch, ctx->bm_total_words, s);
+        if (e != hipSuccess) return e;
     }
     ProfScope prof(ctx, K_SCATTER, s);
     const uint32_t threads = scatter_threads(g);
@@ -1349,12 +1373,11 @@ hipError_t launch_encode_small(zen_ctx *ctx, const GradPtrs &grads, const Encode
     const Geometry &g = ctx->geo;
     BitmapTables bt{ctx->d_rank, ctx->d_dom_tile_base, ctx->d_bm_word_off, ctx->d_group_base};
     uint64_t max_cap = 1;
-    for (uint32_t w = 0; w < batch; ++w) {
+    for (uint32_t w = 0; w < batch; ++w)
         if (outs.cap_rows[w] > max_cap) max_cap = outs.cap_rows[w];
-        if (g.bitmap && outs.bitmap[w]) {
-            hipError_t e = launch_fill_u32(outs.bitmap[w], ctx->bm_total_words, 0u, s);
-            if (e != hipSuccess) return e;
-        }
+    if (g.bitmap) {
+        const hipError_t e = launch_bitmap_clear(outs, batch, ctx->bm_total_words, s);
+        if (e != hipSuccess) return e;
     }
     uint32_t list_cap = SEG_ROWS;
     while (list_cap < max_cap) list_cap <<= 1;
