@@ -419,7 +419,10 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
             }
             listed += total;
         }
-        if (threadIdx.x == 0) tlist[g.n_tiles] = listed;
+        if (threadIdx.x == 0) {
+            tlist[g.n_tiles] = listed;
+            tlist[2 * g.n_tiles + 1] = 0;   // length of a second list a consumer may build in place of the flag words
+        }
     }
 }
 
@@ -974,6 +977,83 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     }
 }
 
+// E5 + E6 for tiles of at most 64 mask words whose rows are a few 16-byte vectors (4 <= row_dim <= 128, a power of
+// two of vectors), index-list output, n_parts <= 64: ONE WAVE per listed tile, no block barrier anywhere.  Lane w
+// holds mask word w, lane p the running output position of partition p; the tile's rows are listed in the wave's
+// own LDS, ranked 64 at a time with wave ballots, and copied by groups of row_dim / 4 lanes.  Tiles here hold a
+// handful of rows each (sparse embedding rows): a block per tile spent its time at barriers.
+// Same results as scatter_kernel<false>.
+static constexpr uint32_t WAVE_TILE_MAX_ROWS = 2048;
+static constexpr uint32_t WAVE_TILE_DENSE_ROWS = 128;   // tiles with more rows are handed to the block-per-tile kernel
+__global__ void __launch_bounds__(SCATTER_THREADS)
+scatter_wave_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
+                    uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
+                    uint32_t *tlist_base, uint64_t tlist_stride)
+{
+    __shared__ uint32_t s_rows[SCATTER_THREADS / ZEN_WAVE][WAVE_TILE_MAX_ROWS];   // the tile's rows, ascending
+    __shared__ uint32_t s_at[SCATTER_THREADS / ZEN_WAVE][ZEN_WAVE];              // output positions of a chunk
+    __shared__ uint32_t s_add[SCATTER_THREADS / ZEN_WAVE][ZEN_WAVE];             // rows of a chunk per partition
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, n = g.n_parts, D = g.row_dim;
+    const uint32_t worker = blockIdx.y;
+    const float *__restrict__ grad = grads.p[worker];
+    uint32_t *__restrict__ out_idx = outs.indices[worker];
+    float *__restrict__ out_val = outs.values[worker];
+    const uint64_t cap = outs.cap_rows[worker];
+    uint32_t *tlist = tlist_base + worker * tlist_stride;
+    uint32_t *dense = tlist + (g.n_tiles + 1);      // tiles left to the block-per-tile kernel: ids, their number at [n_tiles]
+    const uint32_t n_visit = min(tlist[g.n_tiles], g.n_tiles);
+    const uint32_t *wmask = mask_base + worker * mask_stride_words;
+    const uint32_t *whist = hist_base + worker * hist_stride_words;
+    const uint32_t V = D >> 2;                      // 16-byte vectors per row = lanes per row (power of two <= 32)
+    const uint32_t rows_per_pass = ZEN_WAVE / V, sub = lane / V, vl = lane % V;
+    uint32_t *rows = s_rows[wave], *at = s_at[wave], *add = s_add[wave];
+    add[lane] = 0;
+    const uint32_t n_waves = gridDim.x * (SCATTER_THREADS / ZEN_WAVE);
+    for (uint32_t k = blockIdx.x * (SCATTER_THREADS / ZEN_WAVE) + wave; k < n_visit; k += n_waves) {
+        const uint32_t tile = min(tlist[k], g.n_tiles - 1);
+        uint32_t word = lane < g.tile_words ? wmask[(uint64_t)tile * g.tile_words + lane] : 0u;
+        uint32_t run = lane < n ? whist[(uint64_t)tile * n + lane] : 0u;   // lane p: next output position of partition p
+        const uint32_t c = __popc(word);
+        const uint32_t inc = wave_inclusive_scan(c);
+        const uint32_t total = __shfl(inc, ZEN_WAVE - 1, ZEN_WAVE);
+        if (total > WAVE_TILE_DENSE_ROWS) {          // uniform: a well-filled tile (the head of a skewed table) is a
+            if (lane == 0) dense[atomicAdd(&dense[g.n_tiles], 1u)] = tile;   // block's work, not one wave's
+            continue;
+        }
+        const uint32_t row0 = tile * g.tile_rows;
+        for (uint32_t j = inc - c; word; ++j) {
+            rows[j] = row0 + lane * 32 + (uint32_t)__ffs((int)word) - 1;
+            word &= word - 1;
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (uint32_t c0 = 0; c0 < total; c0 += ZEN_WAVE) {     // uniform
+            const uint32_t i = c0 + lane;
+            const bool valid = i < total;
+            const uint32_t row = valid ? rows[i] : 0u;
+            const uint32_t p = valid ? owner_of(row, g.seed, n, g.pow2_mask) : 0u;
+            const uint64_t peers = wave_peers(valid, p, g.part_bits);
+            const uint32_t rank = mbcnt(peers);
+            const uint32_t pos = __shfl(run, (int)p, ZEN_WAVE) + rank;
+            if (valid && rank == 0) add[p] = (uint32_t)__popcll(peers);
+            at[lane] = (valid && pos < cap) ? pos : 0xFFFFFFFFu;
+            if (valid && pos < cap && out_idx) out_idx[pos] = row;
+            __builtin_amdgcn_wave_barrier();
+            run += add[lane];
+            add[lane] = 0;
+            if (out_val) {
+                const uint32_t here = min(total - c0, (uint32_t)ZEN_WAVE);
+                for (uint32_t j0 = 0; j0 < here; j0 += rows_per_pass) {
+                    const uint32_t j = j0 + sub;
+                    const uint32_t dst = j < here ? at[j] : 0xFFFFFFFFu;
+                    if (dst != 0xFFFFFFFFu)
+                        ((u32x4 *)(out_val + (uint64_t)dst * D))[vl] = ((const u32x4 *)(grad + (uint64_t)rows[c0 + j] * D))[vl];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
 // E2 on its own: ascending list of non-zero rows from the mask (zen_nonzero).  The scan kernel has
 // turned hist into bases, so with n_parts = 1 geometry hist[tile][0] is the tile's output position.
 __global__ void __launch_bounds__(SCATTER_THREADS)
@@ -1190,6 +1270,24 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
         (void)hipFuncSetAttribute((const void *)scatter_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         (void)hipFuncSetAttribute((const void *)scatter_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         (void)hipGetLastError();
+    }
+    if (g.mode == MODE_SUB && !g.bitmap && g.n_parts <= ZEN_WAVE && g.tile_words <= ZEN_WAVE &&
+        g.tile_rows <= WAVE_TILE_MAX_ROWS && g.sparse_mask) {
+        // sparse rows of a few vectors: a wave per listed tile
+        uint32_t gx = (g.n_tiles + 3) / 4;
+        if (gx > 8192) gx = 8192;
+        scatter_wave_kernel<<<dim3(gx, batch), SCATTER_THREADS, 0, s>>>(
+            g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (uint32_t *)(ws + L.list_off),
+            L.list_stride / 4);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        // the well-filled tiles it listed: a block each
+        scatter_kernel<false><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
+            g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+            (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4,
+            (const uint32_t *)(ws + L.list_off) + (g.n_tiles + 1), L.list_stride / 4, bt);
+        return hipGetLastError();
     }
     if (g.row_dim == 1)
         scatter_kernel<true><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
