@@ -984,7 +984,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 // handful of rows each (sparse embedding rows): a block per tile spent its time at barriers.
 // Same results as scatter_kernel<false>.
 static constexpr uint32_t WAVE_TILE_MAX_ROWS = 2048;
-static constexpr uint32_t WAVE_TILE_DENSE_ROWS = 128;   // tiles with more rows are handed to the block-per-tile kernel
+static constexpr uint32_t WAVE_TILE_DENSE_ROWS = 64;   // tiles with more rows are handed to the block-per-tile kernel
 __global__ void __launch_bounds__(SCATTER_THREADS)
 scatter_wave_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                     uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
