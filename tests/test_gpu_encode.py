@@ -157,10 +157,11 @@ def test_special_values_and_signed_zero(oracle, zen):
         assert ref.nnz == 7
 
 
-def test_capacity_overflow_is_reported_and_contained(oracle, zen):
+@pytest.mark.parametrize("cid", [1, 3, 5])
+def test_capacity_overflow_is_reported_and_contained(oracle, zen, cid):
     import gpu_util as G
 
-    wl = MINI_WORKLOADS[1]
+    wl = MINI_WORKLOADS[cid]
     rows, vals = worker_sparse(wl, 0)
     g = G.dense_device(wl, rows, vals)
     ctx = zen.ZenContext(wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed)
@@ -168,13 +169,13 @@ def test_capacity_overflow_is_reported_and_contained(oracle, zen):
     enc = zen.alloc_encoded(ctx, cap)
     # guard region after the capacity must stay untouched
     big_idx = torch.full((rows.size,), -2, dtype=torch.int32, device="cuda")
-    big_val = torch.full((rows.size, 1), 7.0, dtype=torch.float32, device="cuda")
+    big_val = torch.full((rows.size, wl.row_dim), 7.0, dtype=torch.float32, device="cuda")
     enc.indices, enc.values = big_idx, big_val
     ws = zen.alloc_workspace(zen.zen_encode_workspace_bytes(ctx, 1))
     zen.zen_encode_batch(ctx, [g], [enc], ws)
     st, flags, needed = zen.zen_status_fetch(ctx, ws)
     assert st == zen.ZEN_ERR_CAPACITY and (flags & 1) and needed == rows.size
-    ref = oracle.encode(dense_from_sparse(wl, rows, vals), wl.n_rows, 1, wl.n_parts, wl.hash_seed)
+    ref = oracle.encode(dense_from_sparse(wl, rows, vals), wl.n_rows, wl.row_dim, wl.n_parts, wl.hash_seed)
     assert np.array_equal(G.u32(enc.offsets), ref.offsets)            # offsets still complete
     assert np.array_equal(G.u32(big_idx[:cap]), ref.indices[:cap])    # everything below the capacity is right
     assert np.array_equal(big_val[:cap].cpu().numpy().view(np.uint32), ref.values[:cap].view(np.uint32))
