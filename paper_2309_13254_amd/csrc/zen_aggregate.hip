@@ -20,7 +20,7 @@ static constexpr uint32_t SMALL_MAX_IN = 6500;     // rows into one server that 
 static constexpr int RS_ITEMS = 8;                 // radix sort: keys per thread per block
 static constexpr int RS_BLOCK_KEYS = AGG_THREADS * RS_ITEMS;
 
-enum : uint32_t { CNT_UNIQUE = 0, CNT_TOTAL_IN = 1, CNT_SKIP = 2, CNT_FLAGS = 3, CNT_NEEDED = 4 };
+enum : uint32_t { CNT_UNIQUE = 0, CNT_TOTAL_IN = 1, CNT_SKIP = 2, CNT_FLAGS = 3, CNT_NEEDED = 4, CNT_LISTED = 5 };
 
 // rows [begin, begin+count) of idx are the part's indices; its values start at row vbegin
 struct PartRange { const uint32_t *idx; uint32_t begin, count, vbegin; };
@@ -408,11 +408,13 @@ __device__ __forceinline__ uint64_t next_contrib(const uint64_t *list, uint32_t 
 // order.  Wide rows: one wave per output row; otherwise one thread per output element.
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_servers,
-                  uint32_t *counters_base, const uint32_t *rowstart_base, uint64_t rowstart_stride,
-                  const uint32_t *contrib_base, uint64_t contrib_stride, Arr64<float *> out_values, AggOut outs,
-                  zen_status_info *status)
+                  uint32_t *counters_base, const uint32_t *rowstart_base, const uint32_t *rowend_base,
+                  uint64_t rowstart_stride, const uint32_t *contrib_base, uint64_t contrib_stride,
+                  Arr64<float *> out_values, AggOut outs, zen_status_info *status)
 {
-    // strides in u32 words; status: non-NULL when the servers' results are still to be folded into the call's
+    // rowstart / rowend: the contributor list of output row u is contrib[rowstart[u] .. rowend[u]) (a CSR array
+    // serves as both, rowend = rowstart + 1); strides in u32 words; status: non-NULL when the servers' results
+    // are still to be folded into the call's
     const uint32_t server = blockIdx.y;
     const uint32_t D = row_dim;
     if (status && blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
@@ -432,13 +434,14 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
     const uint64_t cap_rows = outs.cap_rows[server];
     const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
     const uint32_t *rowstart = rowstart_base + (uint64_t)server * rowstart_stride;
+    const uint32_t *rowend = rowend_base + (uint64_t)server * rowstart_stride;
     const uint64_t *contrib = (const uint64_t *)(contrib_base + (uint64_t)server * contrib_stride);
     float *__restrict__ out = out_values.v[server];
 
     if ((D & 3u) == 0 && D >= 256) {
         const uint32_t lane = lane_id(), nw = blockDim.x >> 6, V = D >> 2;
         for (uint32_t u = blockIdx.x * nw + (threadIdx.x >> 6); u < rows; u += gridDim.x * nw) {
-            const uint32_t r0 = rowstart[u], len = rowstart[u + 1] - r0;
+            const uint32_t r0 = rowstart[u], len = rowend[u] - r0;
             // the row's contributor list, sorted across the lanes (lists longer than a wave: see below)
             const bool in_wave = len <= ZEN_WAVE;
             uint64_t mine = ~0ull;
@@ -487,7 +490,7 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
         for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_el;
              f += (uint64_t)gridDim.x * blockDim.x) {
             const uint32_t u = (uint32_t)(f / D), c = (uint32_t)(f - (uint64_t)u * D);
-            const uint32_t r0 = rowstart[u], len = rowstart[u + 1] - r0;
+            const uint32_t r0 = rowstart[u], len = rowend[u] - r0;
             float acc = 0.f;
             uint64_t prev = 0;
             for (uint32_t k = 0; k < len; ++k) {
@@ -504,9 +507,9 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
 // per lane.  (A kernel of its own: it keeps four rows per group in registers.)
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_dim, uint32_t n_servers,
-                        uint32_t *counters_base, const uint32_t *rowstart_base, uint64_t rowstart_stride,
-                        const uint32_t *contrib_base, uint64_t contrib_stride, Arr64<float *> out_values, AggOut outs,
-                        zen_status_info *status)
+                        uint32_t *counters_base, const uint32_t *rowstart_base, const uint32_t *rowend_base,
+                        uint64_t rowstart_stride, const uint32_t *contrib_base, uint64_t contrib_stride,
+                        Arr64<float *> out_values, AggOut outs, zen_status_info *status)
 {
     const uint32_t server = blockIdx.y;
     const uint32_t D = row_dim;
@@ -526,6 +529,7 @@ agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_d
     const uint64_t cap_rows = outs.cap_rows[server];
     const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
     const uint32_t *rowstart = rowstart_base + (uint64_t)server * rowstart_stride;
+    const uint32_t *rowend = rowend_base + (uint64_t)server * rowstart_stride;
     const uint64_t *contrib = (const uint64_t *)(contrib_base + (uint64_t)server * contrib_stride);
     float *__restrict__ out = out_values.v[server];
     {
@@ -561,7 +565,7 @@ agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_d
                 u[r] = ub + (uint64_t)r * per_wave + sub;
                 on[r] = u[r] < rows;
                 r0[r] = on[r] ? rowstart[u[r]] : 0u;
-                len[r] = on[r] ? rowstart[u[r] + 1] - r0[r] : 0u;
+                len[r] = on[r] ? rowend[u[r]] - r0[r] : 0u;
             }
 #pragma unroll
             for (uint32_t r = 0; r < R; ++r) {
@@ -759,25 +763,37 @@ rs_scatter_kernel(const uint32_t *in_base, uint32_t *out_base, uint64_t uniq_str
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_stride, const uint32_t *keys_base,
                     uint32_t *rank_base, uint64_t table_cap, const uint32_t *counters_base, AggOut outs,
-                    uint32_t *rowcnt_base, uint64_t rowcnt_stride, zen_status_info *status)
+                    uint32_t *rowstart_base, uint32_t *cursor_base, uint64_t row_stride, uint32_t *counters_rw,
+                    Arr64<const float *> src_values, const float **src_tab, zen_status_info *status)
 {
+    // rowstart / cursor: where the contributor list of every output row starts (the fill kernel moves the cursor
+    // to the list's end).  A wave takes the room for its 64 rows' lists with one atomic; the lists lie in no
+    // particular order, which shows in no result.
+    if (src_tab && blockIdx.x == 0 && blockIdx.y == 0) write_src_table(src_values, src_tab);   // for the gather of narrow rows
     const uint32_t server = blockIdx.y;
     const uint32_t *counters = counters_base + server * 16;
     const uint32_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
     const uint32_t *sorted = sorted_base + (uint64_t)server * uniq_stride;
     const uint32_t *keys = keys_base + (uint64_t)server * table_cap;
     uint32_t *rank = rank_base + (uint64_t)server * table_cap;
-    uint32_t *rowcnt = rowcnt_base + (uint64_t)server * rowcnt_stride;
+    uint32_t *rowstart = rowstart_base + (uint64_t)server * row_stride, *cursor = cursor_base + (uint64_t)server * row_stride;
     const uint32_t cap_mask = (uint32_t)(table_cap - 1);
     const uint64_t cap_rows = outs.cap_rows[server];
     uint32_t *out_idx = outs.indices[server];
-    for (uint32_t u = blockIdx.x * blockDim.x + threadIdx.x; u < U; u += gridDim.x * blockDim.x) {
-        const uint32_t key = sorted[u];
-        if (u < cap_rows) out_idx[u] = key;
-        const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+    for (uint32_t u0 = blockIdx.x * blockDim.x; u0 < U; u0 += gridDim.x * blockDim.x) {   // whole waves together
+        const uint32_t u = u0 + threadIdx.x;
         uint32_t c = 0;
-        if (slot != 0xFFFFFFFFu) { c = rank[slot] + 1u; rank[slot] = u; }   // the slot counted the key's repeats so far
-        rowcnt[u] = c;
+        if (u < U) {
+            const uint32_t key = sorted[u];
+            if (u < cap_rows) out_idx[u] = key;
+            const uint32_t slot = probe_find(keys, cap_mask, key, seed);
+            if (slot != 0xFFFFFFFFu) { c = rank[slot] + 1u; rank[slot] = u; }   // the slot counted the key's repeats so far
+        }
+        const uint32_t inc = wave_inclusive_scan(c);
+        uint32_t base = 0;
+        if (lane_id() == ZEN_WAVE - 1) base = atomicAdd(&counters_rw[server * 16 + CNT_LISTED], inc);
+        base = __shfl(base, ZEN_WAVE - 1, ZEN_WAVE);
+        if (u < U) { rowstart[u] = base + inc - c; cursor[u] = base + inc - c; }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *outs.count[server] = U;
@@ -786,35 +802,6 @@ agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_st
             atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)U);
         }
     }
-}
-
-// Large tables: row_start[] = exclusive scan of the keys' occurrence counts (CSR over the output rows), and a
-// fill cursor per output row that starts there.  One block per server.
-__global__ void __launch_bounds__(1024)
-agg_rowstart_kernel(const uint32_t *counters_base, uint32_t *rowstart_base, uint32_t *cursor_base, uint64_t stride,
-                    Arr64<const float *> src_values, const float **src_tab)
-{
-    __shared__ uint32_t s_tmp[32];
-    const uint32_t server = blockIdx.x;
-    if (src_tab && server == 0) write_src_table(src_values, src_tab);   // for the gather of narrow rows
-    const uint32_t *counters = counters_base + server * 16;
-    const uint32_t U = counters[CNT_SKIP] ? 0u : counters[CNT_UNIQUE];
-    uint32_t *rowstart = rowstart_base + (uint64_t)server * stride, *cursor = cursor_base + (uint64_t)server * stride;
-    uint32_t carried = 0;                                        // rows listed before this chunk
-    for (uint32_t base = 0; base < U; base += 8 * blockDim.x) {  // 8 consecutive rows per thread: 32-byte accesses
-        const uint32_t ub = base + threadIdx.x * 8;
-        uint32_t c[8], sum = 0;
-#pragma unroll
-        for (uint32_t q = 0; q < 8; ++q) { c[q] = ub + q < U ? rowstart[ub + q] : 0u; sum += c[q]; }
-        uint32_t chunk_total;
-        uint32_t run = carried + block_exclusive_scan(sum, s_tmp, &chunk_total);
-#pragma unroll
-        for (uint32_t q = 0; q < 8; ++q)
-            if (ub + q < U) { rowstart[ub + q] = run; cursor[ub + q] = run; run += c[q]; }
-        carried += chunk_total;
-    }
-    const uint32_t total = carried;
-    if (threadIdx.x == 0) rowstart[U] = total;
 }
 
 // A2 (values), large tables: every incoming row appends its id (part << 32 | row in the part's values) to the
@@ -973,10 +960,10 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
             ProfScope prof(ctx, K_AGG_GATHER, s);
             if (narrow_rows)
                 agg_gather_group_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
-                    (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, keys, cap, rank, cap, out_values, outs, status);
+                    (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, keys, keys + 1, cap, rank, cap, out_values, outs, status);
             else
                 agg_gather_kernel<<<dim3((uint32_t)gx, n_servers), AGG_THREADS, 0, s>>>(
-                    src_values, g.row_dim, n_servers, counters, keys, cap, rank, cap, out_values, outs, status);
+                    src_values, g.row_dim, n_servers, counters, keys, keys + 1, cap, rank, cap, out_values, outs, status);
             ZEN_LAUNCH_CHECK();
         }
         return hipSuccess;
@@ -1051,22 +1038,17 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         if (fblocks > 4096) fblocks = 4096;
         {
             ProfScope prof(ctx, K_AGG_FINALIZE, s);
+            uint32_t *rs = (uint32_t *)(ws + L.rowstart_off);
             agg_finalize_kernel<<<dim3((uint32_t)fblocks, n_servers), AGG_THREADS, 0, s>>>(
-                g.seed, a, ustride, keys, rank, cap, counters, outs, (uint32_t *)(ws + L.rowstart_off), L.rowstart_stride,
-                status);
+                g.seed, a, ustride, keys, rank, cap, counters, outs, rs, rs + (uint64_t)n_servers * L.rowstart_stride,
+                L.rowstart_stride, counters, src_values, narrow_rows ? (const float **)(ws + L.srctab_off) : nullptr, status);
             ZEN_LAUNCH_CHECK();
         }
     }
     {
-        // CSR over the output rows, contributor lists (in the sort's ping-pong buffers, free by now), gather
+        // contributor lists (in the sort's ping-pong buffers, free by now; cursor[u] ends at the end of row u's list), gather
         uint32_t *rowstart = (uint32_t *)(ws + L.rowstart_off), *cursor = rowstart + (uint64_t)n_servers * L.rowstart_stride;
         uint64_t *contrib = (uint64_t *)(ws + L.uniq_off);
-        {
-            ProfScope prof(ctx, K_AGG_ZERO, s);
-            agg_rowstart_kernel<<<n_servers, 1024, 0, s>>>(counters, rowstart, cursor, L.rowstart_stride, src_values,
-                                                           narrow_rows ? (const float **)(ws + L.srctab_off) : nullptr);
-            ZEN_LAUNCH_CHECK();
-        }
         {
             ProfScope prof(ctx, K_AGG_ACCUM, s);
             agg_fill_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, g.seed, keys, rank, cap, counters, cursor,
@@ -1077,11 +1059,11 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         ProfScope prof(ctx, K_AGG_GATHER, s);
         if (narrow_rows)
             agg_gather_group_kernel<<<dim3((uint32_t)ggx, n_servers), AGG_THREADS, 0, s>>>(
-                (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, rowstart, L.rowstart_stride, (const uint32_t *)contrib,
-                2 * L.uniq_cap, out_values, outs, nullptr);
+                (const float *const *)(ws + L.srctab_off), g.row_dim, n_servers, counters, rowstart, cursor, L.rowstart_stride,
+                (const uint32_t *)contrib, 2 * L.uniq_cap, out_values, outs, nullptr);
         else
             agg_gather_kernel<<<dim3((uint32_t)ggx, n_servers), AGG_THREADS, 0, s>>>(
-                src_values, g.row_dim, n_servers, counters, rowstart, L.rowstart_stride, (const uint32_t *)contrib,
+                src_values, g.row_dim, n_servers, counters, rowstart, cursor, L.rowstart_stride, (const uint32_t *)contrib,
                 2 * L.uniq_cap, out_values, outs, nullptr);
         return hipGetLastError();
     }

@@ -88,7 +88,8 @@ struct AggLayout {
     uint64_t uniq_cap;       // = max_in_rows rounded up
     uint64_t sorthist_off;   // large path: per server sort_blocks x 256 u32
     uint64_t sort_blocks;    // radix-sort blocks per server
-    uint64_t rowstart_off;   // large path: per server uniq_cap + 64 u32 row starts, then (all servers) as many fill cursors
+    uint64_t rowstart_off;   // large path: per server uniq_cap + 64 u32 contributor-list starts, then (all servers) as many fill
+                             // cursors, which are the lists' ends once filled
     uint64_t rowstart_stride;
     uint64_t decode_off;     // bitmap parts: per (server, part) decoded indices
     uint64_t decode_stride;
