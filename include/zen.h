@@ -141,9 +141,10 @@ zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint6
 
 /*
  * Aggregate n_in incoming parts at server part_id: out_indices = ascending union of the parts'
- * indices (kept even if a sum cancels to 0), out_values = fp32 sums over every occurrence (fp32
- * atomic adds: the summation order is not fixed, results agree with an fp64 sum to ~1e-7 relative
- * to sum|x|).  max_in_rows bounds sum of *count over the parts; it sizes the open-addressing table
+ * indices (kept even if a sum cancels to 0), out_values = fp32 sums over every occurrence, added in
+ * ascending (part, position in the part) order with plain loads and one store per element (no value
+ * atomics): the same inputs give the same bits on every call, and results agree with an fp64 sum to
+ * ~1e-7 relative to sum|x|.  max_in_rows bounds sum of *count over the parts; it sizes the open-addressing table
  * (power of two >= 2*max_in_rows).  A larger actual total raises the table flag and leaves
  * *out_count = 0.  U > out_cap_rows raises the capacity flag, writes the first out_cap_rows rows
  * and sets *out_count = U.

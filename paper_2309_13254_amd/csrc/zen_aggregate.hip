@@ -1050,7 +1050,7 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         uint32_t *rowstart = (uint32_t *)(ws + L.rowstart_off), *cursor = rowstart + (uint64_t)n_servers * L.rowstart_stride;
         uint64_t *contrib = (uint64_t *)(ws + L.uniq_off);
         {
-            ProfScope prof(ctx, K_AGG_ACCUM, s);
+            ProfScope prof(ctx, K_AGG_FILL, s);
             agg_fill_kernel<<<dim3(gx, n_in, n_servers), AGG_THREADS, 0, s>>>(src, g.seed, keys, rank, cap, counters, cursor,
                                                                               L.rowstart_stride, contrib, L.uniq_cap);
             ZEN_LAUNCH_CHECK();

@@ -424,7 +424,7 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
 static const char *const kKernelNames[K_COUNT] = {
     "detect_kernel", "partition_scan_kernel", "scatter_kernel", "agg_clear_kernel", "agg_insert_kernel",
     "agg_small_kernel", "agg_compact_kernel", "rs_hist_kernel", "rs_scan_kernel", "rs_scatter_kernel",
-    "agg_finalize_kernel", "(unused)", "agg_fill_kernel", "nonzero_list_kernels", "bitmap_decode_kernel",
+    "agg_finalize_kernel", "agg_fill_kernel", "nonzero_list_kernels", "bitmap_decode_kernel",
     "agg_gather_kernel", "bm_count_kernel", "bm_scan_kernel", "bm_merge_kernel", "encode_small_kernel", "gather_rows_kernel",
     "pull_encode_kernel", "pull_zero_kernel", "pull_count_kernel", "pull_scan_kernel", "pull_place_kernel",
     "pull_place_coo_kernel", "hm_clear_kernel", "hm_insert_kernel", "hm_extract_kernels",

@@ -108,7 +108,7 @@ struct AggLayout {
 namespace zen {
 enum KernelId : uint32_t {
     K_DETECT = 0, K_PARTITION_SCAN, K_SCATTER, K_AGG_CLEAR, K_AGG_INSERT, K_AGG_SORT_SMALL, K_AGG_COMPACT,
-    K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_ZERO, K_AGG_ACCUM, K_NONZERO_LIST, K_BITMAP_DECODE,
+    K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_AGG_FINALIZE, K_AGG_FILL, K_NONZERO_LIST, K_BITMAP_DECODE,
     K_AGG_GATHER, K_BM_COUNT, K_BM_SCAN, K_BM_MERGE, K_ENCODE_SMALL, K_GATHER_ROWS,
     K_PULL_ENCODE, K_PULL_ZERO, K_PULL_COUNT, K_PULL_SCAN, K_PULL_PLACE, K_PULL_PLACE_COO,
     K_HM_CLEAR, K_HM_INSERT, K_HM_EXTRACT, K_STATS,
