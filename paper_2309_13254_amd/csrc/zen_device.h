@@ -59,14 +59,18 @@ __device__ __forceinline__ uint32_t nonzero_mag(u32x4 v)
     return (v.x | v.y | v.z | v.w) & 0x7fffffffu;
 }
 
-// Inclusive scan over the 64 lanes of a wave.
+// Inclusive scan over the 64 lanes of a wave, in six data-parallel-primitive adds and without the LDS
+// crossbar: shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane shifted in from outside the row
+// adds 0), then lane 15 of rows 0 and 2 added to all of rows 1 and 3, then lane 31 added to rows 2 and
+// 3.  The active lanes must be lanes [0, n) of the wave for some n (lanes that are off add nothing).
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
 {
-#pragma unroll
-    for (int d = 1; d < ZEN_WAVE; d <<= 1) {
-        uint32_t t = __shfl_up(v, d, ZEN_WAVE);
-        if ((int)lane_id() >= d) v += t;
-    }
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast:31 -> rows 2, 3
     return v;
 }
 
