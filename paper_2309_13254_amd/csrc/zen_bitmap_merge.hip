@@ -26,12 +26,6 @@ __device__ __forceinline__ const uint32_t *part_words(const BmArgs &a, uint32_t 
     return a.bitmap[w] + (a.single ? 0u : word_off[p]);
 }
 
-// Sum over the wave, the same in every lane; all 64 lanes must be active.
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(v), ZEN_WAVE - 1);
-}
-
 // cnt[server][row][chunk]: row w < n_in = set bits of part w in the chunk, row n_in = union bits.
 __global__ void __launch_bounds__(BM_THREADS)
 bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off, uint32_t *cnt, uint32_t n_chunks,

@@ -74,6 +74,12 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
     return v;
 }
 
+// Sum over the wave, the same in every lane; all 64 lanes must be active.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(v), ZEN_WAVE - 1);
+}
+
 // Exclusive scan of one value per thread over a block of up to 1024 threads.  `s_tmp` holds at
 // least 17 words.  Returns the exclusive prefix; *total receives the block sum.  Contains barriers:
 // every thread of the block must call it.

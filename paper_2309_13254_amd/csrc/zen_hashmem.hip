@@ -130,7 +130,7 @@ hm_count_kernel(HashParams hp, const uint32_t *x, uint32_t *cnt, uint32_t chunks
         const uint32_t q = c * HM_CHUNK + u * HM_THREADS + threadIdx.x;
         if (q < hp.cells && xp[q] != ZEN_EMPTY_KEY) ++mine;
     }
-    for (int d = 32; d > 0; d >>= 1) mine += __shfl_xor(mine, d, ZEN_WAVE);
+    mine = wave_sum(mine);
     if (lane_id() == 0 && mine) atomicAdd(&s_c, mine);
     __syncthreads();
     if (threadIdx.x == 0) cnt[(uint64_t)p * chunks + c] = s_c;

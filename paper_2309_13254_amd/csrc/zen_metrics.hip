@@ -14,13 +14,6 @@ static constexpr int ST_THREADS = 256;
 
 struct StatsOut { unsigned long long *nnz, *union_prefix, *overlap, *even_split; };
 
-__device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
-{
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, ZEN_WAVE);
-    return v;
-}
-
 // One block per tile of the masks; W <= ZEN_MAX_BATCH workers.
 __global__ void __launch_bounds__(ST_THREADS)
 stats_kernel(Geometry g, uint32_t W, const uint32_t *mask_base, uint64_t mask_stride_words, const uint32_t *tflag_base,
@@ -60,11 +53,11 @@ stats_kernel(Geometry g, uint32_t W, const uint32_t *mask_base, uint64_t mask_st
             acc |= m[w];
             const uint32_t cu = __popc(acc);
             if (w < W && ballot(cu != 0) != 0) {          // uniform
-                const uint32_t su = wave_sum32(cu);
+                const uint32_t su = wave_sum(cu);
                 if (lane == 0) atomicAdd(&s_uni[w], su);
             }
             if (w < W && ballot(c != 0) != 0) {           // uniform
-                const uint32_t sc = wave_sum32(c);
+                const uint32_t sc = wave_sum(c);
                 if (lane == 0) atomicAdd(&s_nnz[w], sc);
                 if (one_part) {
                     if (lane == 0) atomicAdd(&out.even_split[(uint64_t)w * g.n_parts + i0_first], (unsigned long long)sc);
@@ -88,7 +81,7 @@ stats_kernel(Geometry g, uint32_t W, const uint32_t *mask_base, uint64_t mask_st
             for (uint32_t b = a + 1; b < ZEN_MAX_BATCH; ++b) {
                 const uint32_t c = __popc(m[a] & m[b]);
                 if (b < W && ballot(c != 0) != 0) {
-                    const uint32_t sc = wave_sum32(c);
+                    const uint32_t sc = wave_sum(c);
                     if (lane == 0) atomicAdd(&s_ov[a * ZEN_MAX_BATCH + b], sc);
                 }
             }

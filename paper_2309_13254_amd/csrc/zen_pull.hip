@@ -43,13 +43,6 @@ __device__ __forceinline__ uint32_t domain_word(const uint32_t *__restrict__ bm,
     return w;
 }
 
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
-{
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, ZEN_WAVE);
-    return v;
-}
-
 // First position in the ascending list a[0..n) whose element is >= key (n if none).  Called by all
 // 64 lanes of a wave with the same arguments; every step probes 64 evenly spaced elements, so a list
 // of 2^24 entries needs four dependent loads instead of twenty-four.
@@ -169,7 +162,7 @@ pull_encode_kernel(PullSrc a, Arr64<uint64_t> cap_rows, Arr64<uint32_t *> out_wo
         }
     }
     if (word < n_words) out_words.v[server][word] = bits;
-    const uint32_t found = wave_sum_u32(__popc(bits));
+    const uint32_t found = wave_sum(__popc(bits));
     if (lane == 0 && found) atomicAdd(&s_found, found);
     __syncthreads();
     if (threadIdx.x == 0 && (bad || s_found != m_all)) atomicOr(&status->flags, 4u);
@@ -212,7 +205,7 @@ pull_count_kernel(PullSrc a, const uint32_t *dom_offsets, uint32_t *cnt, uint32_
     if (threadIdx.x == 0) s_c = 0;
     __syncthreads();
     const uint32_t w = domain_word(bm, k, n_dom);
-    const uint32_t s = wave_sum_u32(__popc(w));
+    const uint32_t s = wave_sum(__popc(w));
     if (lane_id() == 0 && s) atomicAdd(&s_c, s);
     __syncthreads();
     if (threadIdx.x == 0) cnt[(uint64_t)server * (n_chunks + 1) + chunk] = s_c;
