@@ -447,6 +447,9 @@ struct BitmapTables {
 
 // ELEM = (row_dim == 1): values are single floats fetched ahead of the ranking loop; otherwise rows
 // are copied after it.  Two instantiations so that each keeps its own register budget.
+#ifndef ZEN_COPY_UNROLL
+#define ZEN_COPY_UNROLL 4   // 16-byte vectors a thread of the narrow-row copy keeps in flight (1, 2, 8 measured slower)
+#endif
 #ifndef ZEN_SCATTER_WAVES
 #define ZEN_SCATTER_WAVES 6   // waves per SIMD the register allocation must allow: 6 measured best (8 spills)
 #endif
@@ -937,13 +940,27 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 } else if ((D & 3u) == 0) {
                     const uint32_t V = D >> 2;
                     const uint32_t n_vec = total * V;           // total <= 2048, V < 64
-                    for (uint32_t f = threadIdx.x; f < n_vec; f += blockDim.x) {
-                        const uint32_t i = f / V, v = f - i * V;
-                        const uint32_t pos = s_pos[i];
-                        if (pos != 0xFFFFFFFFu) {
-                            const u32x4 x = ((const u32x4 *)(grad + (uint64_t)s_list[i] * D))[v];
-                            ((u32x4 *)(out_val + (uint64_t)pos * D))[v] = x;
+                    const uint32_t vsh = (V & (V - 1)) == 0 ? (uint32_t)__ffs((int)V) - 1 : 0xFFFFFFFFu;   // V = 2^vsh
+                    // ZEN_COPY_UNROLL vectors per thread in flight; a power-of-two row needs no division to find its row
+                    for (uint32_t f0 = threadIdx.x; f0 < n_vec; f0 += ZEN_COPY_UNROLL * blockDim.x) {
+                        u32x4 x[ZEN_COPY_UNROLL];
+                        u32x4 *dst[ZEN_COPY_UNROLL];
+#pragma unroll
+                        for (uint32_t u = 0; u < ZEN_COPY_UNROLL; ++u) {
+                            const uint32_t f = f0 + u * blockDim.x;
+                            dst[u] = nullptr;
+                            if (f < n_vec) {
+                                const uint32_t i = vsh != 0xFFFFFFFFu ? f >> vsh : f / V, v = f - i * V;
+                                const uint32_t pos = s_pos[i];
+                                if (pos != 0xFFFFFFFFu) {
+                                    x[u] = ((const u32x4 *)(grad + (uint64_t)s_list[i] * D))[v];
+                                    dst[u] = (u32x4 *)(out_val + (uint64_t)pos * D) + v;
+                                }
+                            }
                         }
+#pragma unroll
+                        for (uint32_t u = 0; u < ZEN_COPY_UNROLL; ++u)
+                            if (dst[u]) *dst[u] = x[u];
                     }
                 } else {
                     const uint32_t n_el = total * D;            // total <= 2048, row_dim <= 2^20
