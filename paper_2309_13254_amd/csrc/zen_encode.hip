@@ -1001,13 +1001,16 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
 // handful of rows each (sparse embedding rows): a block per tile spent its time at barriers.
 // Same results as scatter_kernel<false>.
 static constexpr uint32_t WAVE_TILE_MAX_ROWS = 2048;
-static constexpr uint32_t WAVE_TILE_DENSE_ROWS = 64;   // tiles with more rows are handed to the block-per-tile kernel
+#ifndef ZEN_WAVE_TILE_DENSE_ROWS
+#define ZEN_WAVE_TILE_DENSE_ROWS 64
+#endif
+static constexpr uint32_t WAVE_TILE_DENSE_ROWS = ZEN_WAVE_TILE_DENSE_ROWS;   // tiles with more rows are handed to the block-per-tile kernel
 __global__ void __launch_bounds__(SCATTER_THREADS)
 scatter_wave_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
                     uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
                     uint32_t *tlist_base, uint64_t tlist_stride)
 {
-    __shared__ uint32_t s_rows[SCATTER_THREADS / ZEN_WAVE][WAVE_TILE_MAX_ROWS];   // the tile's rows, ascending
+    __shared__ uint32_t s_rows[SCATTER_THREADS / ZEN_WAVE][WAVE_TILE_DENSE_ROWS];   // the tile's rows, ascending (fuller tiles are passed on)
     __shared__ uint32_t s_at[SCATTER_THREADS / ZEN_WAVE][ZEN_WAVE];              // output positions of a chunk
     __shared__ uint32_t s_add[SCATTER_THREADS / ZEN_WAVE][ZEN_WAVE];             // rows of a chunk per partition
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, n = g.n_parts, D = g.row_dim;
