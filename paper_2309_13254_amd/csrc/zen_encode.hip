@@ -994,39 +994,34 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
     }
 }
 
-// E5 + E6 for tiles of at most 64 mask words whose rows are a few 16-byte vectors (4 <= row_dim <= 128, a power of
+// E5 for tiles of at most 64 mask words whose rows are a few 16-byte vectors (4 <= row_dim <= 128, a power of
 // two of vectors), index-list output, n_parts <= 64: ONE WAVE per listed tile, no block barrier anywhere.  Lane w
 // holds mask word w, lane p the running output position of partition p; the tile's rows are listed in the wave's
-// own LDS, ranked 64 at a time with wave ballots, and copied by groups of row_dim / 4 lanes.  Tiles here hold a
-// handful of rows each (sparse embedding rows): a block per tile spent its time at barriers.
-// Same results as scatter_kernel<false>.
+// own LDS and ranked 64 at a time with wave ballots.  Tiles here hold a handful of rows each (sparse embedding
+// rows): a block per tile spent its time at barriers.  Writes the indices only (same as scatter_kernel<false>
+// would); the rows are copied by gather_rows_kernel afterwards.
 static constexpr uint32_t WAVE_TILE_MAX_ROWS = 2048;
 #ifndef ZEN_WAVE_TILE_DENSE_ROWS
 #define ZEN_WAVE_TILE_DENSE_ROWS 64
 #endif
 static constexpr uint32_t WAVE_TILE_DENSE_ROWS = ZEN_WAVE_TILE_DENSE_ROWS;   // tiles with more rows are handed to the block-per-tile kernel
 __global__ void __launch_bounds__(SCATTER_THREADS)
-scatter_wave_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mask_base,
+scatter_wave_kernel(Geometry g, EncodedPtrs outs, const uint32_t *mask_base,
                     uint64_t mask_stride_words, const uint32_t *hist_base, uint64_t hist_stride_words,
                     uint32_t *tlist_base, uint64_t tlist_stride)
 {
     __shared__ uint32_t s_rows[SCATTER_THREADS / ZEN_WAVE][WAVE_TILE_DENSE_ROWS];   // the tile's rows, ascending (fuller tiles are passed on)
-    __shared__ uint32_t s_at[SCATTER_THREADS / ZEN_WAVE][ZEN_WAVE];              // output positions of a chunk
     __shared__ uint32_t s_add[SCATTER_THREADS / ZEN_WAVE][ZEN_WAVE];             // rows of a chunk per partition
-    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, n = g.n_parts, D = g.row_dim;
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, n = g.n_parts;
     const uint32_t worker = blockIdx.y;
-    const float *__restrict__ grad = grads.p[worker];
     uint32_t *__restrict__ out_idx = outs.indices[worker];
-    float *__restrict__ out_val = outs.values[worker];
     const uint64_t cap = outs.cap_rows[worker];
     uint32_t *tlist = tlist_base + worker * tlist_stride;
     uint32_t *dense = tlist + (g.n_tiles + 1);      // tiles left to the block-per-tile kernel: ids, their number at [n_tiles]
     const uint32_t n_visit = min(tlist[g.n_tiles], g.n_tiles);
     const uint32_t *wmask = mask_base + worker * mask_stride_words;
     const uint32_t *whist = hist_base + worker * hist_stride_words;
-    const uint32_t V = D >> 2;                      // 16-byte vectors per row = lanes per row (power of two <= 32)
-    const uint32_t rows_per_pass = ZEN_WAVE / V, sub = lane / V, vl = lane % V;
-    uint32_t *rows = s_rows[wave], *at = s_at[wave], *add = s_add[wave];
+    uint32_t *rows = s_rows[wave], *add = s_add[wave];
     add[lane] = 0;
     const uint32_t n_waves = gridDim.x * (SCATTER_THREADS / ZEN_WAVE);
     for (uint32_t k = blockIdx.x * (SCATTER_THREADS / ZEN_WAVE) + wave; k < n_visit; k += n_waves) {
@@ -1055,20 +1050,10 @@ scatter_wave_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t
             const uint32_t rank = mbcnt(peers);
             const uint32_t pos = __shfl(run, (int)p, ZEN_WAVE) + rank;
             if (valid && rank == 0) add[p] = (uint32_t)__popcll(peers);
-            at[lane] = (valid && pos < cap) ? pos : 0xFFFFFFFFu;
             if (valid && pos < cap && out_idx) out_idx[pos] = row;
             __builtin_amdgcn_wave_barrier();
             run += add[lane];
             add[lane] = 0;
-            if (out_val) {
-                const uint32_t here = min(total - c0, (uint32_t)ZEN_WAVE);
-                for (uint32_t j0 = 0; j0 < here; j0 += rows_per_pass) {
-                    const uint32_t j = j0 + sub;
-                    const uint32_t dst = j < here ? at[j] : 0xFFFFFFFFu;
-                    if (dst != 0xFFFFFFFFu)
-                        ((u32x4 *)(out_val + (uint64_t)dst * D))[vl] = ((const u32x4 *)(grad + (uint64_t)rows[c0 + j] * D))[vl];
-                }
-            }
             __builtin_amdgcn_wave_barrier();
         }
     }
@@ -1296,18 +1281,29 @@ hipError_t launch_scatter(zen_ctx *ctx, const GradPtrs &grads,
         // sparse rows of a few vectors: a wave per listed tile
         uint32_t gx = (g.n_tiles + 3) / 4;
         if (gx > 8192) gx = 8192;
+        // Both kernels write offsets-ordered indices only; the rows are copied afterwards by one gather over all
+        // output positions.  The head tiles of a skewed table hold thousands of rows each: copied by their own
+        // block they set the kernel's length, spread over the chip the copy runs at the rate of a plain copy.
+        EncodedPtrs outs_idx = outs;
+        uint64_t max_cap = 0;
+        for (uint32_t w = 0; w < batch; ++w) {
+            outs_idx.values[w] = nullptr;
+            if (outs.values[w] && outs.cap_rows[w] > max_cap) max_cap = outs.cap_rows[w];
+        }
         scatter_wave_kernel<<<dim3(gx, batch), SCATTER_THREADS, 0, s>>>(
-            g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+            g, outs_idx, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
             (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (uint32_t *)(ws + L.list_off),
             L.list_stride / 4);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         // the well-filled tiles it listed: a block each
         scatter_kernel<false><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
-            g, grads, outs, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
+            g, grads, outs_idx, (const uint32_t *)(ws + L.mask_off), L.mask_stride / 4,
             (const uint32_t *)(ws + L.hist_off), L.hist_stride / 4,
             (const uint32_t *)(ws + L.list_off) + (g.n_tiles + 1), L.list_stride / 4, bt);
-        return hipGetLastError();
+        e = hipGetLastError();
+        if (e != hipSuccess || max_cap == 0) return e;
+        return launch_gather_rows(ctx, grads, outs, batch, max_cap, s);
     }
     if (g.row_dim == 1)
         scatter_kernel<true><<<dim3(scatter_grid_x(g, batch), batch), threads, words * 4, s>>>(
@@ -1441,6 +1437,7 @@ gather_rows_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs)
     const float *__restrict__ grad = grads.p[worker];
     const uint32_t *__restrict__ idx = outs.indices[worker];
     float *__restrict__ out_val = outs.values[worker];
+    if (!out_val || !idx) return;
     const uint32_t nnz = outs.offsets[worker][g.n_parts];
     const uint32_t rows = (uint64_t)nnz < outs.cap_rows[worker] ? nnz : (uint32_t)outs.cap_rows[worker];
     if ((D & 3u) == 0 && D >= 256) {
@@ -1459,12 +1456,30 @@ gather_rows_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs)
             }
         }
     } else if ((D & 3u) == 0) {
+        // four vectors per thread in flight (a vector is a chain of two accesses: the row id, then the row)
         const uint32_t V = D >> 2;
         const uint64_t n_vec = (uint64_t)rows * V;
-        for (uint64_t f = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; f < n_vec;
-             f += (uint64_t)gridDim.x * blockDim.x) {
-            const uint32_t pos = (uint32_t)(f / V), v = (uint32_t)(f - (uint64_t)pos * V);
-            ((u32x4 *)(out_val + (uint64_t)pos * D))[v] = ((const u32x4 *)(grad + (uint64_t)idx[pos] * D))[v];
+        const uint32_t vsh = (V & (V - 1)) == 0 ? (uint32_t)__ffs((int)V) - 1 : 0xFFFFFFFFu;   // V = 2^vsh
+        for (uint64_t f0 = (uint64_t)blockIdx.x * (4 * blockDim.x) + threadIdx.x; f0 < n_vec;
+             f0 += (uint64_t)gridDim.x * (4 * blockDim.x)) {
+            uint32_t pos[4], v[4], row[4];
+            u32x4 x[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint64_t f = f0 + (uint64_t)u * blockDim.x;
+                pos[u] = 0xFFFFFFFFu;
+                if (f < n_vec) {
+                    pos[u] = vsh != 0xFFFFFFFFu ? (uint32_t)(f >> vsh) : (uint32_t)(f / V);
+                    v[u] = (uint32_t)(f - (uint64_t)pos[u] * V);
+                    row[u] = idx[pos[u]];
+                }
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u)
+                if (pos[u] != 0xFFFFFFFFu) x[u] = ((const u32x4 *)(grad + (uint64_t)row[u] * D))[v[u]];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u)
+                if (pos[u] != 0xFFFFFFFFu) ((u32x4 *)(out_val + (uint64_t)pos[u] * D))[v[u]] = x[u];
         }
     } else {
         const uint64_t n_el = (uint64_t)rows * D;
@@ -1536,6 +1551,7 @@ hipError_t launch_gather_rows(zen_ctx *ctx, const GradPtrs &grads, const Encoded
     const Geometry &g = ctx->geo;
     uint64_t gx;
     if ((g.row_dim & 3u) == 0 && g.row_dim >= 256) gx = (max_cap + 3) / 4;
+    else if ((g.row_dim & 3u) == 0) gx = (max_cap * (g.row_dim / 4) + 1023) / 1024;   // four vectors per thread
     else gx = (max_cap * g.row_dim / 4 + 255) / 256;
     if (gx < 1) gx = 1;
     if (gx > 8192) gx = 8192;
