@@ -511,6 +511,11 @@ agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_d
                         uint64_t rowstart_stride, const uint32_t *contrib_base, uint64_t contrib_stride,
                         Arr64<float *> out_values, AggOut outs, zen_status_info *status)
 {
+    // The parts' base pointers go from their table in memory to LDS, fetched next to the first row bounds: they
+    // are then one access less in the chain row bounds -> list entry -> base pointer -> row that every output
+    // row is.  (Staged from the kernel arguments instead, 64 constant-index moves per thread, it measured slower.)
+    __shared__ const float *s_src[ZEN_MAX_BATCH];
+    const float *my_src = threadIdx.x < ZEN_MAX_BATCH ? src_tab[threadIdx.x] : nullptr;
     const uint32_t server = blockIdx.y;
     const uint32_t D = row_dim;
     if (status && blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
@@ -524,8 +529,11 @@ agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_d
         status->needed_rows = need;
     }
     const uint32_t *counters = counters_base + server * 16;
-    if (counters[CNT_SKIP]) return;
+    const uint32_t skip = counters[CNT_SKIP];
     const uint32_t U = counters[CNT_UNIQUE];
+    if (threadIdx.x < ZEN_MAX_BATCH) s_src[threadIdx.x] = my_src;
+    __syncthreads();
+    if (skip) return;
     const uint64_t cap_rows = outs.cap_rows[server];
     const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
     const uint32_t *rowstart = rowstart_base + (uint64_t)server * rowstart_stride;
@@ -553,7 +561,7 @@ agg_gather_group_kernel(const float *const *__restrict__ src_tab, uint32_t row_d
         };
         auto src_vec = [&](uint64_t e) -> f32x4 {
             // the parts' value arrays come from a table in memory: lanes differ in the part they read
-            return ((const f32x4 *)(src_tab[(uint32_t)(e >> 32)] + (e & 0xFFFFFFFFull) * D))[vl];
+            return ((const f32x4 *)(s_src[(uint32_t)(e >> 32) & (ZEN_MAX_BATCH - 1)] + (e & 0xFFFFFFFFull) * D))[vl];
         };
         for (uint64_t ub = (uint64_t)wave_id * per_wave * R; ub < rows; ub += (uint64_t)n_wave * per_wave * R) {
             uint64_t u[R], mine[R];
