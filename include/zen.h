@@ -127,6 +127,27 @@ zen_status zen_encode(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_
                       const zen_encoded *host_out, void *workspace, uint64_t workspace_bytes,
                       void *hip_stream);
 
+/*
+ * zen_encode for callers that cannot allocate device memory or hand in a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same kernels as
+ * zen_encode, with the workspace (row mask, per-tile owner histograms, tile flags and lists, the
+ * status block) held in a file-scope device array of ZEN_STATIC_SCRATCH_BYTES that every GPU the
+ * library runs on keeps until the process ends; its address is looked up once per device
+ * (zen_ctx_create does it for the context's device; otherwise the first call on a device does).
+ * Nothing is allocated or freed, here or in any routine the call uses.
+ *   status (device, 16-byte aligned, may be NULL): receives the call's zen_status_info on the
+ *   stream when the encode has finished (flags bit 0: nnz > cap_rows, needed_rows = nnz).
+ * A context whose one-worker workspace (zen_encode_workspace_bytes(ctx, 1)) exceeds
+ * ZEN_STATIC_SCRATCH_BYTES is refused with ZEN_ERR_NOMEM before anything is launched (element-level
+ * tensors: about n_rows <= 5e7; 16-partition tables of 64-float rows: about 4e7 rows).
+ * All calls on one GPU share that GPU's array: calls that overlap there (two streams, two threads)
+ * race and must be serialised by the caller.  What a call needs cleared it clears itself; nothing is
+ * carried from one call to the next.
+ */
+#define ZEN_STATIC_SCRATCH_BYTES (8u << 20)
+zen_status zen_encode_static(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_t hash_seed,
+                             const zen_encoded *host_out, zen_status_info *status, void *hip_stream);
+
 /* The same for n_workers gradients per launch sequence.  host_grads / host_outs: host arrays. */
 zen_status zen_encode_batch(zen_ctx *ctx, const float *const *host_grads, uint32_t n_workers,
                             const zen_encoded *host_outs, void *workspace, uint64_t workspace_bytes,

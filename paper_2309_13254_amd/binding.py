@@ -14,7 +14,7 @@ __all__ = [
     "ZEN_INDEX_COO", "ZEN_INDEX_BITMAP", "ZEN_MAX_BATCH", "ZEN_MAX_PARTS",
     "ZenError", "ZenContext", "Encoded", "Aggregated", "library_path", "load_library",
     "zen_ctx_create", "zen_ctx_destroy", "zen_bitmap_layout", "zen_encode_workspace_bytes",
-    "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
+    "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_static", "ZEN_STATIC_SCRATCH_BYTES", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
     "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
     "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "zen_pull_workspace_bytes", "zen_pull_encode", "zen_pull_encode_batch", "zen_pull_decode", "zen_pull_apply",
@@ -27,6 +27,7 @@ __all__ = [
 ZEN_OK, ZEN_ERR_INVALID, ZEN_ERR_CAPACITY, ZEN_ERR_NOMEM, ZEN_ERR_DEVICE = 0, 1, 2, 3, 4
 ZEN_INDEX_COO, ZEN_INDEX_BITMAP = 0, 1
 ZEN_MAX_BATCH, ZEN_MAX_PARTS = 64, 1024
+ZEN_STATIC_SCRATCH_BYTES = 8 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libzen_hip.so")
@@ -84,6 +85,7 @@ def load_library():
         "zen_encode_workspace_bytes": [vp, u32, C.POINTER(u64)],
         "zen_aggregate_workspace_bytes": [vp, u32, u64, C.POINTER(u64)],
         "zen_encode": [vp, vp, u32, u32, C.POINTER(_Encoded), vp, u64, vp],
+        "zen_encode_static": [vp, vp, u32, u32, C.POINTER(_Encoded), vp, vp],
         "zen_encode_batch": [vp, C.POINTER(vp), u32, C.POINTER(_Encoded), vp, u64, vp],
         "zen_nonzero": [vp, vp, vp, u64, vp, vp, u64, vp],
         "zen_aggregate": [vp, C.POINTER(_Part), u32, u32, vp, vp, u64, vp, u64, vp, u64, vp],
@@ -249,6 +251,13 @@ def zen_encode(ctx, grad, n_parts, hash_seed, out, workspace, stream=None):
     return _check(load_library().zen_encode(ctx.handle, grad.data_ptr(), int(n_parts), int(hash_seed) & 0xFFFFFFFF,
                                             C.byref(st), workspace.data_ptr(), workspace.numel(), _stream(stream)),
                   "zen_encode")
+
+
+def zen_encode_static(ctx, grad, n_parts, hash_seed, out, status=None, stream=None, allow=()):
+    """status: device tensor of 16 bytes (flags u32, reserved u32, needed_rows u64) or None."""
+    st = out.struct()
+    return _check(load_library().zen_encode_static(ctx.handle, grad.data_ptr(), int(n_parts), int(hash_seed) & 0xFFFFFFFF,
+                                                   C.byref(st), _ptr(status), _stream(stream)), "zen_encode_static", allow)
 
 
 def zen_encode_batch(ctx, grads, outs, workspace, stream=None):

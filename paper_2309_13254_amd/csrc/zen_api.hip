@@ -1,4 +1,5 @@
 // The C ABI (include/zen.h): argument checks, workspace layouts and launch sequences.
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -82,6 +83,42 @@ using namespace zen;
 
 static void prof_release(zen_ctx *ctx);
 
+// ---- zen_encode_static: the encode workspace as a file-scope device array ------------------------
+// Every GPU the library runs on holds its own copy of the array at its own address.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address that kernels and copies take is
+// looked up once per device, with that device current, and kept here.
+static __device__ __align__(256) unsigned char scratch[ZEN_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device d, NULL until looked up
+
+// Address of the calling thread's current device's copy of `scratch` (looked up on first use).
+static zen_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return ZEN_ERR_DEVICE;
+    if (dev < 0 || dev >= kMaxDevices) return ZEN_ERR_INVALID;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return ZEN_ERR_DEVICE;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return ZEN_OK;
+}
+
+// the status block of a workspace, copied to the caller's device buffer on the stream
+__global__ void status_copy_kernel(const zen_status_info *src, zen_status_info *dst)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
+}
+
+
 extern "C" {
 
 const char *zen_status_str(zen_status s)
@@ -112,6 +149,10 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
     ctx->small_encode = 1;   // ZEN_ENCODE_SMALL=0 forces the tiled partition path (testing / tuning)
     if (const char *e = getenv("ZEN_ENCODE_SMALL")) ctx->small_encode = atoi(e) != 0;
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return ZEN_ERR_DEVICE; }
+    {   // zen_encode_static's workspace on this device: found here, so that the call itself has no first-use step
+        void *unused = nullptr;
+        (void)static_scratch(&unused);
+    }
     if (fmt == ZEN_INDEX_BITMAP) {
         // sorted hash domains, per-row ranks and per-tile rank bases, built once on the device
         const Geometry &g = ctx->geo;
@@ -287,6 +328,24 @@ zen_status zen_encode(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_
     if (n_parts != ctx->geo.n_parts || hash_seed != ctx->geo.seed) return ZEN_ERR_INVALID;
     const float *grads[1] = {grad};
     return zen_encode_batch(ctx, grads, 1, host_out, workspace, workspace_bytes, hip_stream);
+}
+
+zen_status zen_encode_static(zen_ctx *ctx, const float *grad, uint32_t n_parts, uint32_t hash_seed,
+                             const zen_encoded *host_out, zen_status_info *status, void *hip_stream)
+{
+    if (!ctx || !host_out) return ZEN_ERR_INVALID;
+    if (n_parts != ctx->geo.n_parts || hash_seed != ctx->geo.seed) return ZEN_ERR_INVALID;
+    if ((uintptr_t)status & 15u) return ZEN_ERR_INVALID;
+    if (encode_layout(ctx->geo, 1).total > (uint64_t)ZEN_STATIC_SCRATCH_BYTES) return ZEN_ERR_NOMEM;   // beyond the array
+    void *ws = nullptr;
+    const zen_status st = static_scratch(&ws);
+    if (st != ZEN_OK) return st;
+    const float *grads[1] = {grad};
+    const zen_status r = encode_batch_impl(ctx, grads, 1, nullptr, host_out, ws, ZEN_STATIC_SCRATCH_BYTES, hip_stream);
+    if (r != ZEN_OK || !status) return r;
+    status_copy_kernel<<<1, 64, 0, (hipStream_t)hip_stream>>>((const zen_status_info *)ws, status);
+    HIP_TRY(hipGetLastError());
+    return ZEN_OK;
 }
 
 zen_status zen_nonzero(zen_ctx *ctx, const float *grad, uint32_t *indices, uint64_t cap_rows,
