@@ -6,6 +6,11 @@ servers, inputs resident in HBM.  Prints ONE JSON line with the whole-job gradie
 roofline of the dominant kernel (the dense scan) measured with HIP events on the launch stream, and
 the CPU oracle timed on a bounded sample of the same workload.
 
+With no --config the run covers every benchmark configuration, one after the other (2, 3, 4, 5, then the
+launch-bound 1): the line's headline fields are those of configuration 4 (the largest of the three the
+bandwidth target is set on) and "configs" holds one record per workload, each with its own step time,
+whole-path fraction, roofline, Pull leg and CPU baseline.  --config C runs that configuration alone.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
 """
 import argparse
@@ -40,6 +45,23 @@ def make_inputs(wl, torch):
     return sparse, grads
 
 
+def host_cpu():
+    """(model name, cores this process may run on) of the machine's host CPU."""
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        total = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        total = os.cpu_count() or 1
+    return model, total
+
+
 def cpu_baseline(wl, sparse, budget_s=20.0):
     """The oracle as it stands, single-threaded, on a bounded sample: whole workers' encodes, then as
     many servers' aggregates as fit the budget.  Returns gradient GB/s over the sampled workers."""
@@ -72,12 +94,15 @@ def cpu_baseline(wl, sparse, budget_s=20.0):
     t_agg_all = t_agg * wl.n_parts / n_agg          # scale the sampled servers to all n servers
     t = t_enc + t_agg_all
     gbytes = n_enc * wl.dense_bytes / 1e9
+    model, total = host_cpu()
     return {
         "value": round(gbytes / t, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
         "sample": "%d of %d workers encoded (%.2f s), %d of %d servers aggregated over those workers "
                   "(%.2f s, scaled to %d servers); 1 thread" % (n_enc, wl.n_workers, t_enc, n_agg, wl.n_parts,
                                                                  t_agg, wl.n_parts),
         "nnz_per_s": round(sum(e.nnz for e in encs) / t, 1),
+        "seconds": round(t, 3),
+        "host_cpu": model, "host_cores_total": total, "cores_used": "1 of %d" % total,
     }
 
 
@@ -250,44 +275,54 @@ def hashmem_leg(zen, torch, n_elems=214_000_000, density=0.028, n_parts=16):
             "dense_scan_ms": round(t.get("detect_kernel", 0.0), 3)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-times", action="store_true", help="extra untimed pass timing every kernel")
-    ap.add_argument("--pull", action="store_true",
-                    help="extra leg after the timed region: the servers' hash bitmaps (zen_pull_encode_batch) and one "
-                         "worker's decode + dense placement (zen_pull_apply), timed on their own")
-    ap.add_argument("--metrics", action="store_true",
-                    help="extra leg: the workload's sparsity metrics (density, densification, overlap, skewness, "
-                         "imbalance ratios) from zen_sparsity_count, and the scheme Equations (1) / (2) choose")
-    ap.add_argument("--sparsify", action="store_true",
-                    help="extra leg: top-5 %% sparsifier (sampled threshold + encode with the threshold applied in "
-                         "the dense scan) on a dense 2^28-element tensor, and the format sizes of the result")
-    ap.add_argument("--hashmem", action="store_true",
-                    help="extra leg: the paper's parameter study of Algorithm 1's hash memory (r1, k) on a synthetic "
-                         "214 M-element tensor, next to the histogram/scan/scatter encode of the same tensor")
-    ap.add_argument("--input-sets", type=int, default=0,
-                    help="copies of the input buffers the steps rotate through, so that no step finds its inputs in "
-                         "the last-level cache (default: enough for 2 GiB of distinct inputs, at most 16)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also launch the library's plain 1 GiB copy kernel three times (reference for hardware "
-                         "byte counters under rocprofv3 --pmc)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU (the n workers are n buffers on that GPU); --gpus %d is not "
-            "supported" % args.gpus)
-        return 2
+def read_ceiling_leg(zen, torch, sizes_gb=(1.048576, 40.96, 134.217728)):
+    """What a read-only stream reaches on this chip: the library's read kernel (16-byte loads, no stores, no LDS)
+    over the byte counts of configurations 2, 3 and 4's dense scans, in the dense scan's own launch shape and in
+    other shapes (threads per block, loads in flight, bytes per block, persistent grid, plain loads).  A pass over
+    1 GB starts at a new offset of the big buffer every time, so the last-level cache holds none of it."""
+    total = int(max(sizes_gb) * 1e9) // 16 * 16
+    buf = torch.zeros(total // 4, dtype=torch.float32, device="cuda")
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    shapes = {
+        "scan_shape_256t_u8_128K_nt": None,
+        "256t_u4_128K_nt": (256, 4, 128 << 10, 0, 1), "256t_u16_128K_nt": (256, 16, 128 << 10, 0, 1),
+        "512t_u8_128K_nt": (512, 8, 128 << 10, 0, 1), "1024t_u4_128K_nt": (1024, 4, 128 << 10, 0, 1),
+        "1024t_u8_128K_nt": (1024, 8, 128 << 10, 0, 1),
+        "256t_u8_32K_nt": (256, 8, 32 << 10, 0, 1), "256t_u8_512K_nt": (256, 8, 512 << 10, 0, 1),
+        "512t_u8_1M_nt": (512, 8, 1 << 20, 0, 1),
+        "256t_u8_128K_plain": (256, 8, 128 << 10, 0, 0), "512t_u8_128K_plain": (512, 8, 128 << 10, 0, 0),
+        "persistent_2048x256t_u8_32K_nt": (256, 8, 32 << 10, 2048, 1), "persistent_1024x512t_u8_64K_nt": (512, 8, 64 << 10, 1024, 1),
+        "persistent_4096x256t_u8_128K_nt": (256, 8, 128 << 10, 4096, 1),
+    }
+    out = {}
+    for gb in sizes_gb:
+        nbytes = int(gb * 1e9) // 16 * 16
+        reps = 20 if gb < 2 else (5 if gb < 50 else 3)
+        span = total - nbytes
+        row = {}
+        for name, shape in shapes.items():
+            views = [buf.view(torch.uint8)[((k * nbytes) % span) // 4096 * 4096 if span else 0:] for k in range(reps + 1)]
+            zen.zen_calibration_read(views[0], sink, nbytes, shape)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for k in range(reps):
+                zen.zen_calibration_read(views[k + 1] if views[k + 1].numel() >= nbytes else views[0], sink, nbytes, shape)
+            e1.record()
+            torch.cuda.synchronize()
+            row[name] = round(nbytes * reps / (e0.elapsed_time(e1) / 1e3) / 1e9, 1)
+        out["%.3f GB" % gb] = row
+        log("  read ceiling %.3f GB: scan shape %.1f GB/s, best %s %.1f GB/s" % (
+            gb, row["scan_shape_256t_u8_128K_nt"], max(row, key=row.get), max(row.values())))
+    return {"unit": "GB/s", "peak": HBM_PEAK_GBS, "read_GBps": out}
 
-    import torch
-    import paper_2309_13254_amd as zen
+
+def run_workload(zen, torch, args, cid, want_cpu, cpu_budget, legs):
+    """Everything for one benchmark configuration: inputs, the timed steps, the per-kernel events, the extra
+    legs, the CPU oracle.  Returns the record (the JSON line's fields for that workload)."""
     from workloads import get_workload
 
-    zen.load_library()
-    wl = get_workload(args.config)
+    wl = get_workload(cid)
     log("workload %s: R=%d D=%d n=%d  dense %.3f GB/worker" % (wl.name, wl.n_rows, wl.row_dim, wl.n_workers,
                                                               wl.dense_bytes / 1e9))
     t0 = time.time()
@@ -364,7 +399,7 @@ def main():
     b_alg = dense_bytes + enc_out + agg_in + agg_out
 
     kernel_ms = None
-    if args.kernel_times:
+    if "kernel_times" in legs:
         zen.zen_profile_enable(ctx, 2, 64 * 8)
         for _ in range(5):
             step()
@@ -375,48 +410,21 @@ def main():
     grad_sets = None      # the extra legs below use the first set only
     torch.cuda.empty_cache()
 
-    pull = None
-    if args.pull:
-        pull = pull_leg(zen, torch, wl, ctx, aggs, U, args.steps)
+    pull = pull_leg(zen, torch, wl, ctx, aggs, U, args.steps) if "pull" in legs else None
+    metrics = metrics_leg(zen, torch, wl, ctx, grads, offs, U) if "metrics" in legs else None
 
-    metrics = None
-    if args.metrics:
-        metrics = metrics_leg(zen, torch, wl, ctx, grads, offs, U)
-
-    sparsify = None
-    if args.sparsify:
-        grads = None
-        torch.cuda.empty_cache()
-        sparsify = sparsify_leg(zen, torch)
-
-    hashmem = None
-    if args.hashmem:
-        del grads
-        grads = None
-        torch.cuda.empty_cache()
-        hashmem = hashmem_leg(zen, torch)
-
-    if args.calibrate_copy:
-        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        b = torch.empty_like(a)
-        for _ in range(3):
-            zen.zen_calibration_copy(a, b)
-        torch.cuda.synchronize()
-        del a, b
-
-    traffic = None
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(wl.name, {}).get("detect_kernel_bytes_per_launch")
+        if traffic is not None:
+            traffic_src = ("profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, collected "
+                           "in separate profiling runs (counters cannot be read inside the timed run)")
 
-    out = {
-        "metric": "encode+aggregate throughput (dense gradient bytes per second, all workers and servers)",
+    rec = {
         "value": round(dense_bytes / t / 1e9, 2),
         "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(t * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "config_id": wl.config_id, "n_rows": wl.n_rows, "row_dim": D,
                    "n_workers": wl.n_workers, "n_parts": n, "index_format": "bitmap" if wl.bitmap else "coo",
                    "nnz_total": int(sum(nnz)), "unique_total": int(sum(U)), "max_in_rows": max_in,
@@ -431,25 +439,124 @@ def main():
             "achieved": round(dense_bytes / det_avg_s / 1e9, 1) if det_avg_s > 0 else None,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(dense_bytes / det_avg_s / 1e9 / HBM_PEAK_GBS, 4) if det_avg_s > 0 else None,
-            "traffic": traffic,
+            "traffic": traffic, "traffic_source": traffic_src,
             "avg_launch_ms": round(det_avg_s * 1e3, 4), "launches": det_n,
             "algorithmic_bytes_per_launch": int(dense_bytes),
         },
     }
     if kernel_ms is not None:
-        out["kernel_ms_per_step"] = kernel_ms
+        rec["kernel_ms_per_step"] = kernel_ms
     if pull is not None:
-        out["pull"] = pull
+        rec["pull"] = pull
+    if metrics is not None:
+        rec["sparsity_metrics"] = metrics
+    del grads, encs, aggs, ws_enc, ws_agg, ctx
+    torch.cuda.empty_cache()
+    if want_cpu:
+        rec["cpu_baseline"] = cpu_baseline(wl, sparse, cpu_budget)
+    log("  %s: %.4f ms/step, %.1f GB/s of gradient, whole path %.3f of peak, dense scan %.3f of peak" % (
+        wl.name, rec["ms_per_step"], rec["value"], rec["hbm_frac_whole_path"], rec["roofline"]["frac"] or 0.0))
+    return rec
+
+
+HEADLINE_CONFIG = 4                 # the largest of the configurations the bandwidth target is set on (2, 3, 4)
+ALL_CONFIGS = (2, 3, 4, 5, 1)       # run order of the default line; 1 is launch-bound context
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=0,
+                    help="benchmark configuration 1..5; default 0 = all of them, headline = configuration 4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-times", action="store_true", help="extra untimed pass timing every kernel")
+    ap.add_argument("--pull", action="store_true",
+                    help="extra leg after the timed region: the servers' hash bitmaps (zen_pull_encode_batch) and one "
+                         "worker's decode + dense placement (zen_pull_apply), timed on their own (always on in the "
+                         "default all-configurations run)")
+    ap.add_argument("--metrics", action="store_true",
+                    help="extra leg: the workload's sparsity metrics (density, densification, overlap, skewness, "
+                         "imbalance ratios) from zen_sparsity_count, and the scheme Equations (1) / (2) choose")
+    ap.add_argument("--sparsify", action="store_true",
+                    help="extra leg: top-5 %% sparsifier (sampled threshold + encode with the threshold applied in "
+                         "the dense scan) on a dense 2^28-element tensor, and the format sizes of the result")
+    ap.add_argument("--hashmem", action="store_true",
+                    help="extra leg: the paper's parameter study of Algorithm 1's hash memory (r1, k) on a synthetic "
+                         "214 M-element tensor, next to the histogram/scan/scatter encode of the same tensor")
+    ap.add_argument("--read-ceiling", action="store_true",
+                    help="extra leg: the rate of the library's read-only streaming kernel over 1 / 41 / 134 GB in the "
+                         "dense scan's launch shape and in others (what a pure read reaches on this chip)")
+    ap.add_argument("--input-sets", type=int, default=0,
+                    help="copies of the input buffers the steps rotate through, so that no step finds its inputs in "
+                         "the last-level cache (default: enough for 2 GiB of distinct inputs, at most 16)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain 1 GiB copy and read kernels three times (references for "
+                         "hardware byte counters under rocprofv3 --pmc)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the n workers are n buffers on that GPU); --gpus %d is not "
+            "supported" % args.gpus)
+        return 2
+    if args.config not in (0, 1, 2, 3, 4, 5):
+        log("bench.py: --config must be 1..5 (or 0 for all)")
+        return 2
+
+    import torch
+    import paper_2309_13254_amd as zen
+
+    zen.load_library()
+    all_configs = args.config == 0
+    cids = list(ALL_CONFIGS) if all_configs else [args.config]
+    headline = HEADLINE_CONFIG if all_configs else args.config
+    legs = set()
+    if args.kernel_times:
+        legs.add("kernel_times")
+    if args.pull or all_configs:
+        legs.add("pull")
+    if args.metrics:
+        legs.add("metrics")
+    records = {}
+    for cid in cids:
+        # the oracle's time is bounded per workload: about 20 s for the headline, a few seconds for the others
+        budget = 20.0 if cid == headline else 5.0
+        records[cid] = run_workload(zen, torch, args, cid, not args.no_cpu_baseline, budget, legs)
+
+    read_ceiling = read_ceiling_leg(zen, torch) if args.read_ceiling else None
+    sparsify = sparsify_leg(zen, torch) if args.sparsify else None
+    hashmem = hashmem_leg(zen, torch) if args.hashmem else None
+
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            zen.zen_calibration_copy(a, b)
+            zen.zen_calibration_read(a, sink)
+        torch.cuda.synchronize()
+        del a, b
+
+    h = records[headline]
+    out = {
+        "metric": "encode+aggregate throughput (dense gradient bytes per second, all workers and servers)",
+        "value": h["value"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": h["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+    }
+    for k, v in h.items():
+        if k not in out:
+            out[k] = v
+    if all_configs:
+        out["configs"] = {records[c]["config"]["workload"]: records[c] for c in cids}
+    if read_ceiling is not None:
+        out["read_ceiling"] = read_ceiling
     if hashmem is not None:
         out["hashmem_study"] = hashmem
-    if metrics is not None:
-        out["sparsity_metrics"] = metrics
     if sparsify is not None:
         out["sparsifier"] = sparsify
-    if not args.no_cpu_baseline:
-        grads = None
-        torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(wl, sparse)
     print(json.dumps(out), flush=True)
     return 0
 

@@ -104,6 +104,20 @@ zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint
                           uint32_t hash_seed, zen_index_format fmt);
 zen_status zen_ctx_destroy(zen_ctx *ctx);
 
+/*
+ * zen_ctx_create with explicit tuning (not part of the method; results do not depend on it).  The
+ * library reads no environment variable: what can be tuned at run time is tuned here.
+ * host_tuning == NULL: the defaults, i.e. zen_ctx_create.
+ */
+typedef struct {
+    uint32_t tile_bytes;    /* dense bytes per tile (the unit of one block of the dense scan and of one
+                               histogram row), 4096 .. 8 MiB; 0 = the default, 128 KiB */
+    uint32_t tiled_encode;  /* 1 = every encode takes the tiled partition path (per-tile histograms, scan,
+                               scatter), also the few-row ones that one block per worker would do; 0 = default */
+} zen_tuning;
+zen_status zen_ctx_create_tuned(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts,
+                                uint32_t hash_seed, zen_index_format fmt, const zen_tuning *host_tuning);
+
 /* Hash-bitmap layout (host outputs).  total words = sum_p ceil(|II_p|/32) <= n_rows/32 + n_parts
  * (appendix "Proof of The Property of Hash Bitmap").  host_word_offsets has n_parts+1 entries and
  * host_domain_sizes n_parts entries; either may be NULL.  ZEN_ERR_INVALID for a COO context. */
@@ -115,6 +129,11 @@ zen_status zen_bitmap_layout(const zen_ctx *ctx, uint64_t *host_total_words, uin
 zen_status zen_encode_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uint64_t *host_bytes);
 zen_status zen_aggregate_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_rows,
                                          uint64_t *host_bytes);
+/* Both at once: *host_enc_bytes = zen_encode_workspace_bytes(ctx, batch), *host_agg_bytes =
+ * zen_aggregate_workspace_bytes(ctx, batch, max_nnz) with max_nnz the bound on the rows entering one
+ * server (e.g. the sum over the workers of their largest partition).  Either output may be NULL. */
+zen_status zen_workspace_bytes(const zen_ctx *ctx, uint64_t max_nnz, uint32_t batch, uint64_t *host_enc_bytes,
+                               uint64_t *host_agg_bytes);
 
 /*
  * Encode one worker's gradient (Algorithm 1's result).  grad: [n_rows][row_dim] fp32 row-major,
@@ -175,9 +194,11 @@ zen_status zen_aggregate(zen_ctx *ctx, const zen_part *host_parts, uint32_t n_in
                          uint32_t *out_count, uint64_t max_in_rows, void *workspace,
                          uint64_t workspace_bytes, void *hip_stream);
 
-/* All n_parts servers in one launch sequence: server j merges partition j of every worker's
- * encoded gradient.  host_encs: n_workers entries (as filled by zen_encode*); host_outs: n_parts
- * entries. */
+/* All n_parts servers: server j merges partition j of every worker's encoded gradient.
+ * host_encs: n_workers <= ZEN_MAX_BATCH entries (as filled by zen_encode*); host_outs: n_parts
+ * entries.  Servers are handled in launch groups of ZEN_MAX_BATCH (one group when n_parts <= 64), so
+ * the workspace is that of zen_aggregate_workspace_bytes(ctx, min(n_parts, ZEN_MAX_BATCH), max_in_rows);
+ * the status block ends up holding the OR / maximum over all groups. */
 zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint32_t n_workers,
                                const zen_aggregated *host_outs, uint64_t max_in_rows, void *workspace,
                                uint64_t workspace_bytes, void *hip_stream);
@@ -345,6 +366,11 @@ zen_status zen_format_bytes(uint64_t n_elems, uint64_t nnz, uint32_t n_servers, 
 zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream,
                             zen_status_info *host_info);
 
+/* After zen_status_fetch on this context returned ZEN_ERR_CAPACITY: *host_needed_rows = the rows the
+ * largest overflowing output or table needed (what that fetch read); 0 if the last fetch found no
+ * overflow or none was made.  No device work. */
+zen_status zen_last_overflow(const zen_ctx *ctx, uint64_t *host_needed_rows);
+
 /* h0's underlying 32-bit hash for `count` indices: out[i] = MurmurHash3_x86_32(idx[i], seed)
  * (section "Implementation").  Exposed so the hash can be checked on its own. */
 zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uint32_t *out,
@@ -354,6 +380,22 @@ zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uin
  * reads `bytes`, writes `bytes`.  Not part of the method: it is the kernel of known traffic against
  * which hardware HBM byte counters are scaled when the library is profiled. */
 zen_status zen_calibration_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream);
+
+/* Plain streaming READ of `bytes` (multiple of 16, src 16-byte aligned) with 16-byte loads: no stores (sink, a
+ * device array of 64 words, is written only if the OR of everything read is all ones), no LDS.  Not part of
+ * the method: it measures what a read-only stream reaches in a given launch shape -- the rate the dense scan of
+ * zen_encode is held against -- and is a second kernel of known traffic for the byte counters.
+ * host_shape == NULL: the dense scan's own shape (256 threads, 8 loads in flight, a 128 KiB tile per block,
+ * non-temporal loads). */
+typedef struct {
+    uint32_t threads;      /* 256, 512 or 1024 per block */
+    uint32_t unroll;       /* 4, 8 or 16 16-byte loads in flight per thread */
+    uint32_t block_bytes;  /* contiguous bytes a block reads at a time (multiple of 16, >= 4096) */
+    uint32_t max_blocks;   /* 0: one block per block_bytes; else at most this many blocks, which stride on */
+    uint32_t nontemporal;  /* 1: non-temporal loads, 0: plain loads */
+} zen_read_shape;
+zen_status zen_calibration_read(const void *src, uint64_t bytes, const zen_read_shape *host_shape, uint32_t *sink,
+                                void *hip_stream);
 
 /*
  * Optional kernel timing with HIP events recorded on the launch stream (for benchmarks; not part of

@@ -13,10 +13,11 @@ __all__ = [
     "ZEN_OK", "ZEN_ERR_INVALID", "ZEN_ERR_CAPACITY", "ZEN_ERR_NOMEM", "ZEN_ERR_DEVICE",
     "ZEN_INDEX_COO", "ZEN_INDEX_BITMAP", "ZEN_MAX_BATCH", "ZEN_MAX_PARTS",
     "ZenError", "ZenContext", "Encoded", "Aggregated", "library_path", "load_library",
-    "zen_ctx_create", "zen_ctx_destroy", "zen_bitmap_layout", "zen_encode_workspace_bytes",
+    "zen_ctx_create", "zen_ctx_create_tuned", "zen_ctx_destroy", "zen_bitmap_layout", "zen_encode_workspace_bytes",
+    "zen_workspace_bytes", "zen_last_overflow",
     "zen_aggregate_workspace_bytes", "zen_encode", "zen_encode_static", "ZEN_STATIC_SCRATCH_BYTES", "zen_encode_batch", "zen_nonzero", "zen_aggregate",
     "zen_aggregate_batch", "zen_status_fetch", "zen_hash_many", "zen_status_str",
-    "zen_calibration_copy", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
+    "zen_calibration_copy", "zen_calibration_read", "zen_profile_enable", "zen_profile_collect", "zen_profile_kernel_name",
     "zen_pull_workspace_bytes", "zen_pull_encode", "zen_pull_encode_batch", "zen_pull_decode", "zen_pull_apply",
     "zen_hash_memory_bytes", "zen_encode_hashed_workspace_bytes", "zen_encode_hashed",
     "zen_sparsity_count", "zen_scheme_times", "zen_topk_workspace_bytes", "zen_topk_threshold",
@@ -61,6 +62,15 @@ class _SparsityCounts(C.Structure):
     _fields_ = [("nnz", C.c_void_p), ("union_prefix", C.c_void_p), ("overlap", C.c_void_p), ("even_split", C.c_void_p)]
 
 
+class _Tuning(C.Structure):
+    _fields_ = [("tile_bytes", C.c_uint32), ("tiled_encode", C.c_uint32)]
+
+
+class _ReadShape(C.Structure):
+    _fields_ = [("threads", C.c_uint32), ("unroll", C.c_uint32), ("block_bytes", C.c_uint32), ("max_blocks", C.c_uint32),
+                ("nontemporal", C.c_uint32)]
+
+
 class _StatusInfo(C.Structure):
     _fields_ = [("flags", C.c_uint32), ("reserved", C.c_uint32), ("needed_rows", C.c_uint64)]
 
@@ -80,7 +90,10 @@ def load_library():
     vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
     sig = {
         "zen_ctx_create": [C.POINTER(vp), u64, u32, u32, u32, C.c_int],
+        "zen_ctx_create_tuned": [C.POINTER(vp), u64, u32, u32, u32, C.c_int, C.POINTER(_Tuning)],
         "zen_ctx_destroy": [vp],
+        "zen_workspace_bytes": [vp, u64, u32, C.POINTER(u64), C.POINTER(u64)],
+        "zen_last_overflow": [vp, C.POINTER(u64)],
         "zen_bitmap_layout": [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)],
         "zen_encode_workspace_bytes": [vp, u32, C.POINTER(u64)],
         "zen_aggregate_workspace_bytes": [vp, u32, u64, C.POINTER(u64)],
@@ -93,6 +106,7 @@ def load_library():
         "zen_status_fetch": [vp, vp, vp, C.POINTER(_StatusInfo)],
         "zen_hash_many": [vp, u64, u32, vp, vp],
         "zen_calibration_copy": [vp, vp, u64, vp],
+        "zen_calibration_read": [vp, u64, C.POINTER(_ReadShape), vp, vp],
         "zen_pull_workspace_bytes": [vp, C.POINTER(u64)],
         "zen_pull_encode": [vp, vp, vp, u64, u32, vp, vp, u64, vp],
         "zen_pull_encode_batch": [vp, C.POINTER(_Aggregated), vp, vp, u64, vp],
@@ -152,12 +166,17 @@ def _check(status, where, allow=()):
 class ZenContext:
     """Owns a zen_ctx*: immutable function of (n_rows, row_dim, n_parts, hash_seed, fmt)."""
 
-    def __init__(self, n_rows, row_dim, n_parts, hash_seed, fmt=ZEN_INDEX_COO):
+    def __init__(self, n_rows, row_dim, n_parts, hash_seed, fmt=ZEN_INDEX_COO, tile_bytes=0, tiled_encode=False):
         self.n_rows, self.row_dim, self.n_parts = int(n_rows), int(row_dim), int(n_parts)
         self.hash_seed, self.fmt = int(hash_seed) & 0xFFFFFFFF, int(fmt)
         h = C.c_void_p()
-        _check(load_library().zen_ctx_create(C.byref(h), self.n_rows, self.row_dim, self.n_parts,
-                                             self.hash_seed, self.fmt), "zen_ctx_create")
+        if tile_bytes or tiled_encode:
+            tun = _Tuning(int(tile_bytes), 1 if tiled_encode else 0)
+            _check(load_library().zen_ctx_create_tuned(C.byref(h), self.n_rows, self.row_dim, self.n_parts,
+                                                       self.hash_seed, self.fmt, C.byref(tun)), "zen_ctx_create_tuned")
+        else:
+            _check(load_library().zen_ctx_create(C.byref(h), self.n_rows, self.row_dim, self.n_parts,
+                                                 self.hash_seed, self.fmt), "zen_ctx_create")
         self.handle = h
 
     def close(self):
@@ -174,6 +193,10 @@ class ZenContext:
 
 def zen_ctx_create(n_rows, row_dim, n_parts, hash_seed, fmt=ZEN_INDEX_COO):
     return ZenContext(n_rows, row_dim, n_parts, hash_seed, fmt)
+
+
+def zen_ctx_create_tuned(n_rows, row_dim, n_parts, hash_seed, fmt=ZEN_INDEX_COO, tile_bytes=0, tiled_encode=False):
+    return ZenContext(n_rows, row_dim, n_parts, hash_seed, fmt, tile_bytes=tile_bytes, tiled_encode=tiled_encode)
 
 
 def zen_ctx_destroy(ctx):
@@ -201,6 +224,21 @@ def zen_aggregate_workspace_bytes(ctx, batch, max_in_rows):
     _check(load_library().zen_aggregate_workspace_bytes(ctx.handle, int(batch), int(max_in_rows), C.byref(b)),
            "zen_aggregate_workspace_bytes")
     return int(b.value)
+
+
+def zen_workspace_bytes(ctx, max_nnz, batch):
+    """-> (encode workspace bytes, aggregate workspace bytes) for `batch` workers / servers."""
+    e, a = C.c_uint64(), C.c_uint64()
+    _check(load_library().zen_workspace_bytes(ctx.handle, int(max_nnz), int(batch), C.byref(e), C.byref(a)),
+           "zen_workspace_bytes")
+    return int(e.value), int(a.value)
+
+
+def zen_last_overflow(ctx):
+    """-> rows needed by the largest overflow the last zen_status_fetch on this context reported (0: none)."""
+    n = C.c_uint64()
+    _check(load_library().zen_last_overflow(ctx.handle, C.byref(n)), "zen_last_overflow")
+    return int(n.value)
 
 
 class Encoded:
@@ -456,3 +494,12 @@ def zen_calibration_copy(src, dst, stream=None):
     assert dst.numel() * dst.element_size() >= nbytes
     return _check(load_library().zen_calibration_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)),
                   "zen_calibration_copy")
+
+
+def zen_calibration_read(src, sink, nbytes=None, shape=None, stream=None):
+    """shape: None (the dense scan's launch shape) or (threads, unroll, block_bytes, max_blocks, nontemporal)."""
+    nbytes = src.numel() * src.element_size() if nbytes is None else int(nbytes)
+    assert nbytes <= src.numel() * src.element_size() and sink.numel() >= 64
+    sh = None if shape is None else C.byref(_ReadShape(*[int(x) for x in shape]))
+    return _check(load_library().zen_calibration_read(src.data_ptr(), nbytes, sh, sink.data_ptr(), _stream(stream)),
+                  "zen_calibration_read")

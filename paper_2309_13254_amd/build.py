@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 SO = os.path.join(HERE, "libzen_hip.so")
-SOURCES = ["zen_encode.hip", "zen_aggregate.hip", "zen_bitmap_merge.hip", "zen_pull.hip", "zen_hashmem.hip", "zen_metrics.hip", "zen_sparsify.hip", "zen_api.hip"]
+SOURCES = ["zen_encode.hip", "zen_aggregate.hip", "zen_bitmap_merge.hip", "zen_pull.hip", "zen_hashmem.hip", "zen_metrics.hip", "zen_sparsify.hip", "zen_calibrate.hip", "zen_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",

@@ -1,10 +1,13 @@
-// Aggregation kernels for gfx950: open-addressing key table (atomicCAS, linear probing), compaction
-// and sort of the unique keys, and fp32 atomic accumulation of the incoming rows.
+// Aggregation kernels for gfx950: an open-addressing table of KEYS only (atomicCAS, linear probing), compaction
+// and sort of the unique keys, a list of contributing (part, row) pairs per key, and one ordered fp32 sum per
+// output row -- plain loads and one store per element, no atomics on values, no zero fill of the output.
 //
-// One launch covers every server of a batch: blockIdx.z = server, blockIdx.y = incoming part.
-//   clear  -> insert (keys only) -> sort unique keys (LDS bitonic, or segmented LSB radix sort)
-//          -> write each key's output rank into its slot -> zero the output rows
-//          -> accumulate: every incoming row looks its rank up and atomically adds into the output.
+// One launch covers every server of a batch: blockIdx.z (or .y) = server, blockIdx.y = incoming part.
+//   large tables: clear -> insert (keys + repeat counts) -> compact -> segmented LSB radix sort of the unique keys
+//                 -> finalize (each key's output rank into its slot, room for its contributor list)
+//                 -> fill (every incoming row appends its id to its key's list) -> gather (ordered sums)
+//   small tables: one block per server does all of it up to the lists in LDS (or merges ascending parts by
+//                 binary searches, no table), then the same gather.
 #include "zen_device.h"
 #include "zen_internal.h"
 

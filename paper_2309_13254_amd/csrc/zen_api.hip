@@ -14,7 +14,7 @@ static bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 // Tile geometry.  A tile is the unit of one detect / scatter block and of the per-partition
 // histogram; sized for ~128 KB of dense data so that every launch has far more blocks than CUs.
 static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts, uint32_t seed,
-                          bool bitmap)
+                          bool bitmap, uint32_t tile_bytes)
 {
     memset(&g, 0, sizeof(g));
     g.n_rows = n_rows;
@@ -25,11 +25,7 @@ static void make_geometry(Geometry &g, uint64_t n_rows, uint32_t row_dim, uint32
     g.part_bits = 0;
     while ((1u << g.part_bits) < n_parts) ++g.part_bits;
     g.bitmap = bitmap ? 1u : 0u;
-    uint64_t target_bytes = 128 * 1024;
-    if (const char *e = getenv("ZEN_TILE_BYTES")) {   // tuning knob: dense bytes per tile
-        const long long v = atoll(e);
-        if (v >= 4096 && v <= (8 << 20)) target_bytes = (uint64_t)v;
-    }
+    const uint64_t target_bytes = tile_bytes ? tile_bytes : 128 * 1024;   // zen_tuning.tile_bytes, checked by the caller
     if (row_dim == 1) {
         g.mode = MODE_ELEM;
         uint64_t t = 2048;
@@ -112,12 +108,26 @@ static zen_status static_scratch(void **out)
     return ZEN_OK;
 }
 
+// Status of a call made of several launch groups: acc = (first ? 0 : acc) folded with the group's status; after
+// the last group the status block takes the folded value.
+__global__ void status_fold_kernel(zen_status_info *status, zen_status_info *acc, uint32_t first, uint32_t last)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    zen_status_info a = *status;
+    if (!first) {
+        a.flags |= acc->flags;
+        a.needed_rows = a.needed_rows > acc->needed_rows ? a.needed_rows : acc->needed_rows;
+    }
+    a.reserved = 0;
+    *acc = a;
+    if (last) *status = a;
+}
+
 // the status block of a workspace, copied to the caller's device buffer on the stream
 __global__ void status_copy_kernel(const zen_status_info *src, zen_status_info *dst)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
 }
-
 
 extern "C" {
 
@@ -136,18 +146,26 @@ const char *zen_status_str(zen_status s)
 zen_status zen_ctx_create(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts,
                           uint32_t hash_seed, zen_index_format fmt)
 {
+    return zen_ctx_create_tuned(out, n_rows, row_dim, n_parts, hash_seed, fmt, nullptr);
+}
+
+zen_status zen_ctx_create_tuned(zen_ctx **out, uint64_t n_rows, uint32_t row_dim, uint32_t n_parts,
+                                uint32_t hash_seed, zen_index_format fmt, const zen_tuning *host_tuning)
+{
     if (!out) return ZEN_ERR_INVALID;
     *out = nullptr;
+    const uint32_t tile_bytes = host_tuning ? host_tuning->tile_bytes : 0u;
+    if (tile_bytes && (tile_bytes < 4096u || tile_bytes > (8u << 20))) return ZEN_ERR_INVALID;
+    if (host_tuning && host_tuning->tiled_encode > 1u) return ZEN_ERR_INVALID;
     if (n_rows == 0 || n_rows > 0xFFFFFFFEull || row_dim == 0 || row_dim > (1u << 20) || n_parts == 0 ||
         n_parts > ZEN_MAX_PARTS || (fmt != ZEN_INDEX_COO && fmt != ZEN_INDEX_BITMAP))
         return ZEN_ERR_INVALID;
     zen_ctx *ctx = new (std::nothrow) zen_ctx();
     if (!ctx) return ZEN_ERR_NOMEM;
     memset(ctx, 0, sizeof(*ctx));
-    make_geometry(ctx->geo, n_rows, row_dim, n_parts, hash_seed, fmt == ZEN_INDEX_BITMAP);
+    make_geometry(ctx->geo, n_rows, row_dim, n_parts, hash_seed, fmt == ZEN_INDEX_BITMAP, tile_bytes);
     ctx->fmt = fmt;
-    ctx->small_encode = 1;   // ZEN_ENCODE_SMALL=0 forces the tiled partition path (testing / tuning)
-    if (const char *e = getenv("ZEN_ENCODE_SMALL")) ctx->small_encode = atoi(e) != 0;
+    ctx->small_encode = !(host_tuning && host_tuning->tiled_encode);   // few-row encodes take the one-block-per-worker path
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return ZEN_ERR_DEVICE; }
     {   // zen_encode_static's workspace on this device: found here, so that the call itself has no first-use step
         void *unused = nullptr;
@@ -245,6 +263,18 @@ zen_status zen_aggregate_workspace_bytes(const zen_ctx *ctx, uint32_t batch, uin
     if (!ctx || !host_bytes || batch == 0 || max_in_rows > 0x7FFFFFFFull) return ZEN_ERR_INVALID;
     const uint32_t b = batch > ZEN_MAX_BATCH ? ZEN_MAX_BATCH : batch;
     *host_bytes = aggregate_layout(ctx, b, max_in_rows).total;
+    return ZEN_OK;
+}
+
+zen_status zen_workspace_bytes(const zen_ctx *ctx, uint64_t max_nnz, uint32_t batch, uint64_t *host_enc_bytes,
+                               uint64_t *host_agg_bytes)
+{
+    if (!ctx || batch == 0 || (!host_enc_bytes && !host_agg_bytes)) return ZEN_ERR_INVALID;
+    if (host_enc_bytes) {
+        const zen_status st = zen_encode_workspace_bytes(ctx, batch, host_enc_bytes);
+        if (st != ZEN_OK) return st;
+    }
+    if (host_agg_bytes) return zen_aggregate_workspace_bytes(ctx, batch, max_nnz, host_agg_bytes);
     return ZEN_OK;
 }
 
@@ -452,21 +482,35 @@ zen_status zen_aggregate_batch(zen_ctx *ctx, const zen_encoded *host_encs, uint3
     const uint32_t group = g.n_parts < ZEN_MAX_BATCH ? g.n_parts : ZEN_MAX_BATCH;
     const AggLayout L = aggregate_layout(ctx, group, max_in_rows);
     if (workspace_bytes < L.total) return ZEN_ERR_NOMEM;
-    if (g.n_parts > ZEN_MAX_BATCH) return ZEN_ERR_INVALID;   // one launch group per call for now
-    AggOut outs;
-    Arr64<float *> ov;
-    memset(&outs, 0, sizeof(outs));
-    memset(&ov, 0, sizeof(ov));
-    for (uint32_t j = 0; j < g.n_parts; ++j) {
-        outs.indices[j] = host_outs[j].indices;
-        outs.count[j] = host_outs[j].count;
-        outs.cap_rows[j] = host_outs[j].cap_rows;
-        ov.v[j] = host_outs[j].values;
-    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
     src.single = 0;
-    src.server0 = 0;
-    return run_aggregate(ctx, src, sv, sb, n_workers, g.n_parts, 0, outs, ov, max_in_rows, (char *)workspace, L,
-                         (hipStream_t)hip_stream);
+    // Servers in launch groups of ZEN_MAX_BATCH.  Every group's kernels write the status block anew, so with
+    // more than one group the blocks are folded (OR of the flags, maximum of the rows needed) in the spare
+    // words behind the status block and the result is put in its place after the last group.
+    zen_status_info *status = (zen_status_info *)(ws + L.status_off), *folded = status + 2;
+    const bool several = g.n_parts > group;
+    for (uint32_t j0 = 0; j0 < g.n_parts; j0 += group) {
+        const uint32_t nb = g.n_parts - j0 < group ? g.n_parts - j0 : group;
+        AggOut outs;
+        Arr64<float *> ov;
+        memset(&outs, 0, sizeof(outs));
+        memset(&ov, 0, sizeof(ov));
+        for (uint32_t j = 0; j < nb; ++j) {
+            outs.indices[j] = host_outs[j0 + j].indices;
+            outs.count[j] = host_outs[j0 + j].count;
+            outs.cap_rows[j] = host_outs[j0 + j].cap_rows;
+            ov.v[j] = host_outs[j0 + j].values;
+        }
+        src.server0 = j0;
+        const zen_status st = run_aggregate(ctx, src, sv, sb, n_workers, nb, j0, outs, ov, max_in_rows, ws, L, s);
+        if (st != ZEN_OK) return st;
+        if (several) {
+            status_fold_kernel<<<1, 64, 0, s>>>(status, folded, j0 == 0 ? 1u : 0u, j0 + nb >= g.n_parts ? 1u : 0u);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    return ZEN_OK;
 }
 
 zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_stream, zen_status_info *host_info)
@@ -477,7 +521,16 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
     HIP_TRY(hipMemcpyAsync(&info, workspace, sizeof(info), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (host_info) *host_info = info;
+    ctx->last_flags = info.flags;
+    ctx->last_needed_rows = info.needed_rows;
     return (info.flags & 3u) ? ZEN_ERR_CAPACITY : (info.flags ? ZEN_ERR_INVALID : ZEN_OK);
+}
+
+zen_status zen_last_overflow(const zen_ctx *ctx, uint64_t *host_needed_rows)
+{
+    if (!ctx || !host_needed_rows) return ZEN_ERR_INVALID;
+    *host_needed_rows = (ctx->last_flags & 3u) ? ctx->last_needed_rows : 0;
+    return ZEN_OK;
 }
 
 static const char *const kKernelNames[K_COUNT] = {

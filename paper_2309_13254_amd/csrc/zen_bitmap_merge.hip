@@ -109,7 +109,16 @@ bm_scan_kernel(BmArgs a, uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_ba
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) counters[CNT_FLAGS] = s_flags;
+    if (threadIdx.x == 0) {
+        counters[CNT_FLAGS] = s_flags;
+        if (s_flags & 4u) {
+            // a part's bitmap and row count disagree: its set bits would index past its values.  The server
+            // puts out nothing and the merge does not touch its parts.
+            *outs.count[server] = 0;
+            counters[CNT_UNIQUE] = 0;
+            counters[CNT_SKIP] = 1;
+        }
+    }
 }
 
 // Merge: one block per (chunk, server).  D == 1: one thread per bitmap word, private LDS
@@ -136,6 +145,7 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
         status->reserved = 0;
         status->needed_rows = need;
     }
+    if (counters_base[server * 16 + CNT_SKIP]) return;   // inconsistent parts (uniform per block)
     const uint32_t d0 = dom_offsets[p], n_dom = dom_offsets[p + 1] - d0, n_words = (n_dom + 31) >> 5;
     if (chunk * BM_CHUNK_WORDS >= n_words) return;
     const uint32_t *pre = cnt + ((uint64_t)server * (ZEN_MAX_BATCH + 1)) * n_chunks;   // exclusive prefixes (+ value base)

@@ -136,6 +136,8 @@ struct zen_ctx {
     uint64_t bm_total_words;
     uint64_t max_dom_words;    // largest per-partition bitmap, in words
     uint32_t small_encode;     // 1: few-row encodes take the one-block-per-worker partition path
+    uint32_t last_flags;       // what the last zen_status_fetch on this context read (zen_last_overflow)
+    uint64_t last_needed_rows;
     uint32_t *d_pull_base;     // element-level BITMAP contexts: [ceil(n_rows/8192)+1][n_parts] rows of II_p below each tile
     uint32_t *d_group_base;    // same at ZEN_GROUP_ROWS granularity: [n_tiles * tile_rows / ZEN_GROUP_ROWS + 1][n_parts]
                                // (element-level BITMAP contexts with few partitions; NULL otherwise)

@@ -64,11 +64,15 @@ stats_kernel(Geometry g, uint32_t W, const uint32_t *mask_base, uint64_t mask_st
                 } else if (c) {
                     if (i0 == i1) {
                         atomicAdd(&out.even_split[(uint64_t)w * g.n_parts + i0], (unsigned long long)c);
-                    } else {   // the word straddles a partition boundary
-                        const uint32_t lo_bits = (uint32_t)((uint64_t)i1 * part_rows - r0);   // rows of the word in i0
-                        const uint32_t c0 = __popc(m[w] & ((1u << lo_bits) - 1u));
-                        if (c0) atomicAdd(&out.even_split[(uint64_t)w * g.n_parts + i0], (unsigned long long)c0);
-                        if (c - c0) atomicAdd(&out.even_split[(uint64_t)w * g.n_parts + i1], (unsigned long long)(c - c0));
+                    } else {   // the word straddles one partition boundary, or several when partitions have fewer than 32 rows
+                        for (uint32_t i = i0; i <= i1 && i < g.n_parts; ++i) {
+                            const uint64_t lo = (uint64_t)i * part_rows, hi = lo + part_rows;   // partition i = rows [lo, hi)
+                            const uint32_t b0 = lo > r0 ? (uint32_t)(lo - r0) : 0u;            // its bits of the word: [b0, b1)
+                            const uint32_t b1 = hi < r0 + 32 ? (uint32_t)(hi - r0) : 32u;
+                            const uint32_t below_b1 = b1 >= 32u ? 0xFFFFFFFFu : (1u << b1) - 1u;
+                            const uint32_t ci = __popc(m[w] & below_b1 & ~((1u << b0) - 1u));
+                            if (ci) atomicAdd(&out.even_split[(uint64_t)w * g.n_parts + i], (unsigned long long)ci);
+                        }
                     }
                 }
             }

@@ -782,12 +782,9 @@ zen_status zen_pull_apply(zen_ctx *ctx, const zen_part *host_parts, float *dense
     } else {
         uint64_t blocks = ((n_elems >> 2) + PULL_THREADS * 4 - 1) / (PULL_THREADS * 4);
         if (blocks < 1) blocks = 1;
-        static const int nt = getenv("ZEN_PULL_ZERO_NT") ? atoi(getenv("ZEN_PULL_ZERO_NT")) : 1;   // tuning knobs
-        static const long cap = getenv("ZEN_PULL_ZERO_BLOCKS") ? atol(getenv("ZEN_PULL_ZERO_BLOCKS")) : (1 << 20);
-        if (blocks > (uint64_t)cap && cap > 0) blocks = (uint64_t)cap;
+        if (blocks > (1u << 20)) blocks = 1u << 20;
         ProfScope prof(ctx, K_PULL_ZERO, s);
-        if (nt) pull_zero_kernel<true><<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);
-        else pull_zero_kernel<false><<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);
+        pull_zero_kernel<true><<<(uint32_t)blocks, PULL_THREADS, 0, s>>>(dense, n_elems, status);   // streaming stores
         HIP_TRY(hipGetLastError());
     }
     uint32_t *dec = (uint32_t *)(ws + L.dec_off);

@@ -74,3 +74,18 @@ def workload_inputs(wl, n_workers=None):
     sparse = [worker_sparse(wl, w) for w in range(n_workers)]
     grads = [dense_device(wl, r, v) for r, v in sparse]
     return sparse, grads
+
+
+def use_tuning(monkeypatch, tiled_encode=False, tile_bytes=0):
+    """Make every zen.ZenContext(...) of the running test a context created with this tuning (the tiled
+    partition path for few-row encodes too, another tile size): zen_ctx_create_tuned instead of zen_ctx_create."""
+    if not tiled_encode and not tile_bytes:
+        return
+    plain = zen.ZenContext
+
+    def tuned(*args, **kw):
+        kw.setdefault("tiled_encode", tiled_encode)
+        kw.setdefault("tile_bytes", tile_bytes)
+        return plain(*args, **kw)
+
+    monkeypatch.setattr(zen, "ZenContext", tuned)

@@ -16,8 +16,22 @@ def _declared():
 
 def test_header_declares_the_boundary():
     names = _declared()
-    for must in ("zen_encode", "zen_aggregate", "zen_encode_batch", "zen_aggregate_batch", "zen_ctx_create"):
-        assert must in names
+    # the boundary's calls: context, workspace sizing, the encode and the aggregate (single and batched), the
+    # overflow report and the status text
+    for must in ("zen_ctx_create", "zen_ctx_destroy", "zen_workspace_bytes", "zen_encode", "zen_aggregate",
+                 "zen_encode_batch", "zen_aggregate_batch", "zen_last_overflow", "zen_status_str",
+                 "zen_status_fetch", "zen_encode_workspace_bytes", "zen_aggregate_workspace_bytes", "zen_bitmap_layout",
+                 "zen_nonzero", "zen_encode_static", "zen_ctx_create_tuned", "zen_pull_encode", "zen_pull_decode",
+                 "zen_pull_apply", "zen_encode_hashed", "zen_sparsity_count", "zen_scheme_times", "zen_topk_threshold",
+                 "zen_format_count", "zen_format_bytes"):
+        assert must in names, must
+
+
+def test_library_reads_no_environment_variable():
+    """What can be tuned at run time goes through zen_ctx_create_tuned, not through the environment."""
+    csrc = os.path.join(ROOT, "paper_2309_13254_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        assert "getenv" not in open(os.path.join(csrc, f)).read(), f
 
 
 def test_library_loads_and_exports_every_declared_symbol():

@@ -193,3 +193,47 @@ def test_overflow_flags(oracle, zen):
     assert np.array_equal(G.u32(guard_idx[:600]), idx[:600])
     assert torch.all(guard_val[:600] == 2.0)
     assert torch.all(guard_idx[600:] == -2) and torch.all(guard_val[600:] == 7.0)
+
+
+@pytest.mark.parametrize("fmt_bitmap", [False, True])
+@pytest.mark.parametrize("big_table", [False, True])
+def test_aggregate_batch_more_servers_than_one_launch_group(oracle, zen, fmt_bitmap, big_table):
+    """n_parts = 100: zen_aggregate_batch handles the servers in groups of ZEN_MAX_BATCH; every server's output
+    is compared with the oracle, and an output capacity that is too small in the FIRST group only must still
+    be reported after the last group."""
+    import gpu_util as G
+    from workloads import Workload
+
+    wl = Workload("agg100", 0, 300_007, 1 if fmt_bitmap else 8, 6, 0xABCD1234, "uniform", nnz=9_000, sigma=1.0)
+    n = 100
+    sparse, grads = G.workload_inputs(wl)
+    fmt = zen.ZEN_INDEX_BITMAP if fmt_bitmap else zen.ZEN_INDEX_COO
+    ctx = zen.ZenContext(wl.n_rows, wl.row_dim, n, wl.hash_seed, fmt)
+    encs, (st, _, _) = G.run_encode_batch(ctx, grads, [r.size for r, _ in sparse])
+    assert st == 0
+    refs = [oracle.encode(dense_from_sparse(wl, r, v), wl.n_rows, wl.row_dim, n, wl.hash_seed) for r, v in sparse]
+    per_server = [sum(int(e.offsets[j + 1]) - int(e.offsets[j]) for e in refs) for j in range(n)]
+    max_in = max(per_server) if not big_table else max(max(per_server), 20000)
+    e_bytes, a_bytes = zen.zen_workspace_bytes(ctx, max_in, n)
+    assert e_bytes == zen.zen_encode_workspace_bytes(ctx, n) and a_bytes == zen.zen_aggregate_workspace_bytes(ctx, n, max_in)
+    outs, (st, flags, needed) = G.run_aggregate_batch(ctx, encs, [max(p, 1) for p in per_server], max_in)
+    assert st == 0 and flags == 0 and zen.zen_last_overflow(ctx) == 0
+    ref_out = []
+    for j in range(n):
+        parts = [(e.indices[e.offsets[j]:e.offsets[j + 1]], e.values[e.offsets[j]:e.offsets[j + 1]]) for e in refs]
+        ref = oracle.aggregate(parts, wl.n_rows, wl.row_dim)
+        ref_out.append(ref)
+        U, idx, val = G.aggregated_to_host(outs[j])
+        assert U == ref.U, j
+        assert np.array_equal(idx, ref.indices), j
+        G.check_sums(val, ref)
+    # server 3 (first group) gets room for 5 rows only
+    caps = [max(p, 1) for p in per_server]
+    caps[3] = 5
+    outs, (st, flags, needed) = G.run_aggregate_batch(ctx, encs, caps, max_in)
+    assert st == zen.ZEN_ERR_CAPACITY and (flags & 1) and needed == ref_out[3].U
+    assert zen.zen_last_overflow(ctx) == ref_out[3].U
+    U, idx, _ = G.aggregated_to_host(outs[3])
+    assert U == ref_out[3].U and np.array_equal(idx, ref_out[3].indices[:5])
+    U, idx, _ = G.aggregated_to_host(outs[99])
+    assert U == ref_out[99].U and np.array_equal(idx, ref_out[99].indices)

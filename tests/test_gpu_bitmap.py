@@ -15,7 +15,9 @@ pytestmark = pytest.mark.gpu
 def partition_path(request, monkeypatch):
     """Run every test through both partition paths: the one-block-per-worker path that few-row
     encodes take by default, and the tiled histogram / scan / scatter path."""
-    monkeypatch.setenv("ZEN_ENCODE_SMALL", "1" if request.param == "small" else "0")
+    import gpu_util as G
+
+    G.use_tuning(monkeypatch, tiled_encode=request.param == "tiled")
     return request.param
 
 
@@ -144,6 +146,44 @@ def test_single_server_bitmap_parts(oracle, zen, mixed, D):
     U, idx, val = G.aggregated_to_host(out)
     assert U == ref.U and np.array_equal(idx, ref.indices)
     G.check_sums(val, ref)
+
+
+@pytest.mark.parametrize("D", [1, 4])
+def test_bitmap_part_with_more_bits_than_rows_is_flagged_and_not_merged(oracle, zen, D):
+    """A part whose bitmap has more set bits than its row count names: flag bit 2, the server puts out nothing,
+    and the merge reads none of the part's values (its value array here is two rows, in the middle of a guard)."""
+    import gpu_util as G
+
+    R, n, seed, part_id = 20000, 8, 99, 2
+    ctx = zen.ZenContext(R, D, n, seed, zen.ZEN_INDEX_BITMAP)
+    owner = oracle.owner_table(R, n, seed)
+    dom_count, word_off = oracle.bitmap_layout(owner, n)
+    dom = np.flatnonzero(owner == part_id).astype(np.uint32)
+    nz = np.zeros(R, np.uint8)
+    nz[dom[: dom.size // 2]] = 1                                     # over a thousand set bits ...
+    bm = oracle.bitmap_encode(owner, n, nz, word_off)[int(word_off[part_id]):int(word_off[part_id + 1])]
+    vals = torch.full((2, D), 3.0, device="cuda")                   # ... and two rows of values
+    good_rows = dom[::7]
+    nz2 = np.zeros(R, np.uint8)
+    nz2[good_rows] = 1
+    bm2 = oracle.bitmap_encode(owner, n, nz2, word_off)[int(word_off[part_id]):int(word_off[part_id + 1])]
+    cnt = lambda k: torch.tensor([k], dtype=torch.int32, device="cuda")
+    parts = [(None, G.to_dev(bm2), torch.ones((good_rows.size, D), device="cuda"), cnt(good_rows.size)),
+             (None, G.to_dev(bm), vals, cnt(2))]
+    out = zen.alloc_aggregated(ctx, dom.size)
+    out.indices.fill_(-7)
+    out.values.fill_(-7.0)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, dom.size))
+    zen.zen_aggregate(ctx, parts, part_id, out, dom.size, ws)
+    st, flags, _ = zen.zen_status_fetch(ctx, ws)
+    assert st == zen.ZEN_ERR_INVALID and flags == 4
+    assert int(out.count.item()) == 0
+    assert torch.all(out.indices == -7) and torch.all(out.values == -7.0)
+    # the same parts with the right count for the first and without the bad one: merged as usual
+    zen.zen_aggregate(ctx, parts[:1], part_id, out, dom.size, ws)
+    assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+    U, idx, val = G.aggregated_to_host(out)
+    assert U == good_rows.size and np.array_equal(idx, good_rows) and np.all(val == 1.0)
 
 
 @pytest.mark.parametrize("R,n", [(1, 1), (33, 3), (5000, 4), (70001, 64), (300000, 100), (5000, 1024), (1 << 20, 7)])

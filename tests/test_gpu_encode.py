@@ -17,7 +17,9 @@ pytestmark = pytest.mark.gpu
 def partition_path(request, monkeypatch):
     """Run every test through both partition paths: the one-block-per-worker path that few-row
     encodes take by default, and the tiled histogram / scan / scatter path."""
-    monkeypatch.setenv("ZEN_ENCODE_SMALL", "1" if request.param == "small" else "0")
+    import gpu_util as G
+
+    G.use_tuning(monkeypatch, tiled_encode=request.param == "tiled")
     return request.param
 
 

@@ -12,8 +12,7 @@ def test_encode_with_more_tiles_than_lds_flag_bits(oracle, monkeypatch):
     import paper_2309_13254_amd as zen
 
     zen.load_library()
-    monkeypatch.setenv("ZEN_TILE_BYTES", "8192")        # 2,048 rows per tile
-    monkeypatch.setenv("ZEN_ENCODE_SMALL", "0")
+    G.use_tuning(monkeypatch, tiled_encode=True, tile_bytes=8192)        # 2,048 rows per tile
     R, n, seed = (1 << 28) + 5000, 7, 0x5EED1234
     rng = np.random.default_rng(42)
     rows = np.unique(np.concatenate([

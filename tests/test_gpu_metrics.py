@@ -40,7 +40,10 @@ def _check(oracle, zen, R, D, n, sets, grads, ctx):
 
 
 @pytest.mark.parametrize("R,D,n,W", [(1, 1, 1, 1), (1000, 1, 7, 3), (70001, 1, 64, 5), (300000, 1, 1000, 2),
-                                     (1 << 20, 1, 3, 64), (9001, 64, 16, 16), (333, 256, 8, 4), (40000, 4, 1000, 2)])
+                                     (1 << 20, 1, 3, 64), (9001, 64, 16, 16), (333, 256, 8, 4), (40000, 4, 1000, 2),
+                                     # even partitions of fewer than 32 rows: a mask word spans several of them
+                                     (100, 1, 10, 3), (333, 1, 64, 4), (1000, 4, 100, 2), (5000, 1, 1000, 3),
+                                     (70, 8, 64, 2)])
 def test_sparsity_counts_random(oracle, zen, R, D, n, W):
     rng = np.random.default_rng(R + D + n + W)
     wl = Workload("t", 0, R, D, n, 5, "uniform")

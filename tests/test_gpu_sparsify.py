@@ -19,7 +19,9 @@ def zen():
 
 @pytest.fixture(params=["small", "tiled"])
 def partition_path(request, monkeypatch):
-    monkeypatch.setenv("ZEN_ENCODE_SMALL", "1" if request.param == "small" else "0")
+    import gpu_util as G
+
+    G.use_tuning(monkeypatch, tiled_encode=request.param == "tiled")
     return request.param
 
 
