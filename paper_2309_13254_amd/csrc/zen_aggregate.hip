@@ -876,9 +876,9 @@ AggLayout aggregate_layout(const zen_ctx *ctx, uint32_t batch, uint64_t max_in_r
         L.decflags_off = off; off += align_up((uint64_t)batch * ZEN_MAX_BATCH * 4, 256);
         L.bm_chunks = bitmap_merge_chunks(ctx->max_dom_words);
         L.bmcnt_off = off; off += align_up((uint64_t)batch * (ZEN_MAX_BATCH + 1) * L.bm_chunks * 4, 256);
-        if (ctx->geo.row_dim == 1) {   // element-level merges: per-wave counts and the union words of every chunk
+        if (ctx->geo.row_dim == 1) {   // element-level merges: per-wave counts of every chunk, the parts' pointer tables
             L.bmwave_off = off; off += align_up((uint64_t)batch * L.bm_chunks * (ZEN_MAX_BATCH + 1) * 4 * 4, 256);
-            L.bmuni_off = off; off += align_up((uint64_t)batch * L.bm_chunks * 256 * 4, 256);
+            L.bmtab_off = off; off += align_up(2 * ZEN_MAX_BATCH * 8, 256);
         }
     }
     L.total = off;

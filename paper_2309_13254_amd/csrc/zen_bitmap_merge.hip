@@ -74,8 +74,20 @@ bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off,
 // Exclusive scan over the chunks of every row; one block per server, one wave per row at a time.
 // Also: *count = U, per-server flags (a part whose bitmap and row count disagree; output capacity).
 __global__ void __launch_bounds__(1024)
-bm_scan_kernel(BmArgs a, uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_base, AggOut outs)
+bm_scan_kernel(BmArgs a, uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_base, AggOut outs,
+               Arr64<const float *> src_values, uint64_t *tabs)
 {
+    // tabs (element-level merges, else NULL): the parts' bitmap pointers [64] and value pointers [64] as tables in
+    // memory for the merge, whose lanes differ in the part they read (kernel arguments can only be indexed
+    // uniformly: constant indices here, one thread each)
+    if (tabs && blockIdx.x == 0) {
+#pragma unroll
+        for (uint32_t w = 0; w < ZEN_MAX_BATCH; ++w)
+            if (threadIdx.x == w) {
+                tabs[w] = (uint64_t)(uintptr_t)a.bitmap[w];
+                tabs[ZEN_MAX_BATCH + w] = (uint64_t)(uintptr_t)src_values.v[w];
+            }
+    }
     __shared__ uint32_t s_flags;
     const uint32_t server = blockIdx.x, p = a.first_part + server;
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -329,6 +341,174 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
     }
 }
 
+// Element-level merge with a LANE PER PART.  Bit j of every part's bitmap is the same row, so a wave that takes
+// a span of 64 consecutive bits can let lane b stand for bit b: for every part that has a bit in the span (the
+// parts are found by one ballot over the lanes, which each hold their own part's 64 bits), the part's mask is
+// broadcast as a scalar, lane b adds that part's value number (values before the span) + (set bits below b),
+// a coalesced load; the union is the OR of the scalars and lane b's output position the number of union bits
+// below it.  No search, no LDS, no atomics; values are added in ascending part order, the first one copied, so
+// every result is the same on every run and a row with one contributor keeps its bits.
+// A block takes a chunk of 256 words as the count kernel does, a wave 64 words = 32 spans.
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef const __attribute__((address_space(1))) float *gfloat_ptr;   // pointers known to be to global memory (they are
+typedef const __attribute__((address_space(1))) uint32_t *gu32_ptr;  // rebuilt from integers, which hides that)
+typedef const __attribute__((address_space(1))) u32x4_a4 *gu32x4_ptr;
+
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, uint32_t src)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, (int)src);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)src);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__global__ void __launch_bounds__(BM_THREADS)
+bm_merge_lanes_kernel(BmArgs a, const uint64_t *tabs, uint32_t n_servers, const uint32_t *domain,
+                      const uint32_t *dom_offsets, const uint32_t *word_off, const uint32_t *cnt, uint32_t n_chunks,
+                      const uint32_t *counters_base, AggOut outs, Arr64<float *> out_values, zen_status_info *status,
+                      const uint32_t *wave_tot)
+{
+    const uint32_t chunk = blockIdx.x, server = blockIdx.y, p = a.first_part + server;
+    const uint32_t n_in = a.n_in, lane = lane_id(), wave = threadIdx.x >> 6;
+    if (chunk == 0 && server == 0 && threadIdx.x == 0) {
+        uint32_t fl = 0, need = 0;
+        for (uint32_t j = 0; j < n_servers; ++j) {
+            fl |= counters_base[j * 16 + CNT_FLAGS];
+            need = max(need, counters_base[j * 16 + CNT_NEEDED]);
+        }
+        status->flags = fl;
+        status->reserved = 0;
+        status->needed_rows = need;
+    }
+    if (counters_base[server * 16 + CNT_SKIP]) return;   // inconsistent parts (uniform per block)
+    const uint32_t d0 = dom_offsets[p], n_dom = dom_offsets[p + 1] - d0, n_words = (n_dom + 31) >> 5;
+    const uint32_t k0 = chunk * BM_CHUNK_WORDS + wave * ZEN_WAVE;   // the wave's first bitmap word
+    if (k0 >= n_words) return;                                       // uniform per wave
+    const uint32_t *pre = cnt + ((uint64_t)server * (ZEN_MAX_BATCH + 1)) * n_chunks;   // exclusive prefixes (+ value base)
+    const uint32_t *wt = wave_tot + ((uint64_t)server * n_chunks + chunk) * (ZEN_MAX_BATCH + 1) * 4;
+    const uint64_t cap_rows = outs.cap_rows[server];
+    uint32_t *__restrict__ out_idx = outs.indices[server];
+    float *__restrict__ out_val = out_values.v[server];
+
+    // lane w: where part w's words and values for this wave start
+    uint64_t bmbase = 0;       // part w's first word of the wave (an address: lanes hand it round as two words)
+    uint64_t vbase = 0;        // part w's value array
+    uint32_t voff = 0;         // index of part w's first value at or after the current span
+    if (lane < n_in) {
+        bmbase = (uint64_t)(uintptr_t)((const uint32_t *)(uintptr_t)tabs[lane] + (a.single ? 0u : word_off[p]) + k0);
+        vbase = tabs[ZEN_MAX_BATCH + lane];
+        voff = pre[(uint64_t)lane * n_chunks + chunk];
+        for (uint32_t v = 0; v < wave; ++v) voff += wt[lane * 4 + v];
+    }
+    uint32_t ubase = pre[(uint64_t)n_in * n_chunks + chunk];         // first output row of this wave (uniform)
+    for (uint32_t v = 0; v < wave; ++v) ubase += wt[n_in * 4 + v];
+
+    // The wave's 64 words of every part, a half (32 words = 16 spans) at a time: read part by part with
+    // consecutive lanes on consecutive words (two parts per load: a load whose lanes sit in 64 parts costs 64
+    // address translations, and the translation misses of such loads were what bounded this kernel), turned
+    // round in LDS so that lane w holds part w's words.
+    extern __shared__ uint32_t smem[];
+    constexpr uint32_t HW = 32, LSTRIDE = HW + 1;                    // odd stride: the turned reads hit 64 banks
+    uint32_t *s_m = smem + wave * (ZEN_WAVE * LSTRIDE);
+    uint64_t *s_ptr = (uint64_t *)(smem + (BM_THREADS / ZEN_WAVE) * (ZEN_WAVE * LSTRIDE)) + wave * ZEN_WAVE;   // [64] the parts' word pointers
+    s_ptr[lane] = lane < n_in ? bmbase : readlane64(bmbase, 0);     // a valid address for every lane
+    __builtin_amdgcn_wave_barrier();
+    constexpr uint32_t GS = 4, SLOTS = 8;
+    for (uint32_t half = 0; half < ZEN_WAVE / HW; ++half) {
+        const uint32_t kw = k0 + half * HW;                          // first word of this half
+        if (kw >= n_words) break;                                    // uniform
+        {
+            const uint32_t q = lane & (HW - 1), hi = lane >> 5;
+            const bool inside = kw + q < n_words;
+            uint32_t t[ZEN_WAVE / 2];
+#pragma unroll
+            for (uint32_t it = 0; it < ZEN_WAVE / 2; ++it) {         // parts 2 it and 2 it + 1
+                t[it] = 0u;
+                if (2 * it < n_in) {                                 // uniform
+                    const gu32_ptr src = (gu32_ptr)(uintptr_t)s_ptr[2 * it + hi];
+                    if (inside) t[it] = src[half * HW + q];          // (a lane beyond the last part reads part 0's word)
+                }
+            }
+            __builtin_amdgcn_wave_barrier();                         // the last half's reads are done
+#pragma unroll
+            for (uint32_t it = 0; it < ZEN_WAVE / 2; ++it) s_m[(2 * it + hi) * LSTRIDE + q] = t[it];
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll 1
+        for (uint32_t qt = 0; qt < 2; ++qt) {
+        constexpr uint32_t QW = HW / 2;                              // a quarter of the wave's words: eight spans
+        uint32_t m[QW];
+#pragma unroll
+        for (uint32_t q = 0; q < QW; ++q) m[q] = lane < n_in ? s_m[lane * LSTRIDE + qt * QW + q] : 0u;
+#pragma unroll
+        for (uint32_t grp = 0; grp < QW / (2 * GS); ++grp) {
+            // groups of four spans: the value loads of all four are under way before any is consumed
+            float v[GS][SLOTS];
+            uint32_t hm[GS], row[GS], voff_at[GS];
+            uint64_t mine[GS], uni[GS], rest[GS];
+#pragma unroll
+            for (uint32_t sp = 0; sp < GS; ++sp) {
+                const uint32_t wq = (grp * GS + sp) * 2;                               // the span's first word of the half
+                mine[sp] = ((uint64_t)m[wq + 1] << 32) | m[wq];                        // part `lane`'s bits of this span
+                uint64_t active = ballot(mine[sp] != 0);                               // parts with a bit in the span
+                const uint32_t bitpos = (kw + qt * QW + wq) * 32 + lane;               // this lane's bit = row II_p[bitpos]
+                row[sp] = 0;
+                if (active != 0 && bitpos < n_dom) row[sp] = domain[d0 + bitpos];
+                hm[sp] = 0;
+                uni[sp] = 0;
+                voff_at[sp] = voff;
+#pragma unroll
+                for (uint32_t j = 0; j < SLOTS; ++j) {                                 // the span's first eight parts
+                    v[sp][j] = 0.f;
+                    if (active) {                                                      // uniform
+                        const uint32_t w = (uint32_t)__ffsll((unsigned long long)active) - 1;
+                        active &= active - 1;
+                        const uint64_t pm = readlane64(mine[sp], w);                  // part w's bits, a scalar
+                        const gfloat_ptr pv = (gfloat_ptr)(uintptr_t)readlane64(vbase, w) +
+                                              (uint32_t)__builtin_amdgcn_readlane((int)voff, (int)w);
+                        uni[sp] |= pm;
+                        if ((pm >> lane) & 1ull) {
+                            hm[sp] |= 1u << j;
+                            v[sp][j] = pv[mbcnt(pm)];                                  // value number = values before + bits below
+                        }
+                    }
+                }
+                rest[sp] = active;
+                voff += (uint32_t)__popcll(mine[sp]);                                  // lanes beyond n_in hold no bits
+            }
+#pragma unroll
+            for (uint32_t sp = 0; sp < GS; ++sp) {
+                if (uni[sp] == 0) continue;                                            // uniform
+                float acc = 0.f;
+#pragma unroll
+                for (uint32_t j = 0; j < SLOTS; ++j)                                   // ascending part order; the first one is copied
+                    if ((hm[sp] >> j) & 1u) acc = (hm[sp] & ((1u << j) - 1u)) ? acc + v[sp][j] : v[sp][j];
+                bool seen = hm[sp] != 0;
+                uint64_t active = rest[sp];
+                while (active) {                                                       // a span with more than eight parts
+                    const uint32_t w = (uint32_t)__ffsll((unsigned long long)active) - 1;
+                    active &= active - 1;
+                    const uint64_t pm = readlane64(mine[sp], w);
+                    const gfloat_ptr pv = (gfloat_ptr)(uintptr_t)readlane64(vbase, w) +
+                                          (uint32_t)__builtin_amdgcn_readlane((int)voff_at[sp], (int)w);
+                    uni[sp] |= pm;
+                    if ((pm >> lane) & 1ull) {
+                        const float x = pv[mbcnt(pm)];
+                        acc = seen ? acc + x : x;
+                        seen = true;
+                    }
+                }
+                const uint32_t o = ubase + mbcnt(uni[sp]);
+                if (((uni[sp] >> lane) & 1ull) && (uint64_t)o < cap_rows) {
+                    out_idx[o] = row[sp];
+                    out_val[o] = acc;
+                }
+                ubase += (uint32_t)__popcll(uni[sp]);
+            }
+        }
+        }
+    }
+}
+
 hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitmaps,
                                const Arr64<const uint32_t *> &bounds, const Arr64<const float *> &src_values,
                                uint32_t n_in, bool single, uint32_t n_servers, uint32_t first_part,
@@ -344,29 +524,35 @@ hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitm
     uint32_t *counters = (uint32_t *)(ws + L.counters_off);
     zen_status_info *status = (zen_status_info *)(ws + L.status_off);
     const uint32_t n_chunks = (uint32_t)L.bm_chunks;
-    uint32_t *wave_tot = ctx->geo.row_dim == 1 ? (uint32_t *)(ws + L.bmwave_off) : nullptr;
-    uint32_t *uni_words = ctx->geo.row_dim == 1 ? (uint32_t *)(ws + L.bmuni_off) : nullptr;
+    const bool elem = ctx->geo.row_dim == 1;
+    uint32_t *wave_tot = elem ? (uint32_t *)(ws + L.bmwave_off) : nullptr;
+    uint64_t *tabs = elem ? (uint64_t *)(ws + L.bmtab_off) : nullptr;
     {
         ProfScope prof(ctx, K_BM_COUNT, s);
         bm_count_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, 0, s>>>(a, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt,
-                                                                         n_chunks, wave_tot, uni_words);
+                                                                         n_chunks, wave_tot, nullptr);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     {
         ProfScope prof(ctx, K_BM_SCAN, s);
-        bm_scan_kernel<<<n_servers, 1024, 0, s>>>(a, cnt, n_chunks, counters, outs);
+        bm_scan_kernel<<<n_servers, 1024, 0, s>>>(a, cnt, n_chunks, counters, outs, src_values, tabs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     {
         ProfScope prof(ctx, K_BM_MERGE, s);
-        const size_t lds = (size_t)(ZEN_MAX_BATCH + 1) * 4 * 4 +
-                           (ctx->geo.row_dim == 1 ? (size_t)BM_CHUNK_WORDS * 32 * 4 + 4 * 4 * ZEN_WAVE * 4
-                                                  : (size_t)(ZEN_MAX_BATCH + 1) * BM_CHUNK_WORDS * 2);
+        if (elem) {
+            const size_t lds_lanes = (size_t)(BM_THREADS / ZEN_WAVE) * (ZEN_WAVE * 33 * 4 + ZEN_WAVE * 8);   // a wave's 64 x 32 words, turned; its 64 pointers
+            bm_merge_lanes_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, lds_lanes, s>>>(
+                a, tabs, n_servers, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt, n_chunks, counters, outs,
+                out_values, status, wave_tot);
+            return hipGetLastError();
+        }
+        const size_t lds = (size_t)(ZEN_MAX_BATCH + 1) * 4 * 4 + (size_t)(ZEN_MAX_BATCH + 1) * BM_CHUNK_WORDS * 2;
         bm_merge_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, lds, s>>>(
             a, src_values, ctx->geo.row_dim, n_servers, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt,
-            n_chunks, counters, outs, out_values, status, wave_tot, uni_words);
+            n_chunks, counters, outs, out_values, status, nullptr, nullptr);
         return hipGetLastError();
     }
 }

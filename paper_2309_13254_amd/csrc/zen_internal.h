@@ -97,7 +97,7 @@ struct AggLayout {
     uint64_t bmcnt_off;      // bitmap merge: per server (ZEN_MAX_BATCH+1) x bm_chunks u32
     uint64_t bm_chunks;
     uint64_t bmwave_off;     // element-level bitmap merge: per server bm_chunks x (ZEN_MAX_BATCH+1) x 4 per-wave counts
-    uint64_t bmuni_off;      //                              per server bm_chunks x 256 union words
+    uint64_t bmtab_off;      //                              the parts' bitmap pointers [64] and value pointers [64]
     uint64_t table_cap;      // slots per server (power of two)
     uint32_t small_path;     // 1: one block per server sorts in LDS
     uint64_t total;
