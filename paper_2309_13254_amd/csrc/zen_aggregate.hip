@@ -396,6 +396,209 @@ agg_small_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t cap, uint32
     }
 }
 
+// ----------------------------------------------------------------------------------------------
+// Few incoming rows (<= FUSED_MAX_IN per server) of wide rows (a multiple of four floats, >= 256): merge and sums
+// in ONE launch.  Every block of a server builds the server's merged (index, part, position) sequence for itself
+// in LDS -- it is a few thousand integer operations, far less than a launch of its own and a round trip through
+// memory cost -- and then sums its share of the output rows, one wave per row, in ascending (part, position)
+// order with plain loads and one store per element.  Strictly ascending parts (what zen_encode sends), at most
+// SMALL_MERGE_MAX_PARTS of them, are merged by binary searches; anything else by a bitonic sort of 64-bit
+// (index, part, position) words.  Same sums in the same order as the table paths.
+// Status: only block (0, 0) writes the status block (zeros and a mark in `reserved`); every server's result
+// goes to its counters, which lie behind the status block, and are folded when the status is fetched.
+// ----------------------------------------------------------------------------------------------
+static constexpr uint32_t FUSED_MAX_IN = 2048;
+static constexpr int FUSED_THREADS = 1024;
+
+__global__ void __launch_bounds__(FUSED_THREADS)
+agg_fused_kernel(PartIdx src, uint32_t n_in, uint32_t max_in_rows, uint32_t row_dim, uint32_t n_servers,
+                 uint32_t *counters_base, AggOut outs, Arr64<const float *> src_values, Arr64<float *> out_values,
+                 zen_status_info *status)
+{
+    __shared__ uint64_t s_sorted[FUSED_MAX_IN];          // the merged sequence: index << 32 | part << 26 | position in the part
+    __shared__ uint32_t s_key[FUSED_MAX_IN];             // the parts' indices, part after part
+    __shared__ uint32_t s_rowstart[FUSED_MAX_IN + 1];    // first element of every output row's stretch
+    __shared__ uint32_t s_tmp[32];
+    __shared__ uint32_t s_pre[ZEN_MAX_BATCH + 1];
+    __shared__ uint32_t s_begin[ZEN_MAX_BATCH];
+    __shared__ uint32_t s_vbegin[ZEN_MAX_BATCH];
+    __shared__ const uint32_t *s_idx[ZEN_MAX_BATCH];
+    __shared__ const float *s_src[ZEN_MAX_BATCH];
+    const uint32_t server = blockIdx.y, D = row_dim;
+    uint32_t *counters = counters_base + server * 16;
+    if (blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
+        status->flags = 0;
+        status->reserved = ZEN_STATUS_IN_COUNTERS | (n_servers << 16);
+        status->needed_rows = 0;
+    }
+    // The parts' pointers go from the kernel arguments to LDS, lane w those of part w: three loads under way at
+    // once (the argument buffer lies in host memory; fetched one after the other, pointer by pointer, the
+    // arguments cost this kernel 50 us).
+    __shared__ const uint32_t *s_bounds[ZEN_MAX_BATCH];
+    if (threadIdx.x < ZEN_MAX_BATCH) {
+        s_src[threadIdx.x] = src_values.v[threadIdx.x];
+        s_idx[threadIdx.x] = src.indices[threadIdx.x];
+        s_bounds[threadIdx.x] = src.bounds[threadIdx.x];
+    }
+    __syncthreads();
+    uint32_t mine = 0;
+    if (threadIdx.x < n_in) {
+        const uint32_t *bnd = s_bounds[threadIdx.x];
+        const uint32_t vbegin = src.single ? 0u : bnd[src.server0 + server];
+        mine = src.single ? bnd[0] : bnd[src.server0 + server + 1] - vbegin;
+        s_begin[threadIdx.x] = vbegin;       // index lists only here: a part's indices and values start at the same row
+        s_vbegin[threadIdx.x] = vbegin;
+    }
+    uint32_t total_in;
+    const uint32_t pre = block_exclusive_scan(mine, s_tmp, &total_in);
+    if (threadIdx.x < n_in) s_pre[threadIdx.x] = pre;
+    if (threadIdx.x == 0) s_pre[n_in] = total_in;
+    __syncthreads();
+    if (total_in > max_in_rows || total_in > FUSED_MAX_IN) {       // uniform over the server's blocks
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            *outs.count[server] = 0;
+            counters[CNT_UNIQUE] = 0;
+            counters[CNT_SKIP] = 1;
+            counters[CNT_FLAGS] = 2u;
+            counters[CNT_NEEDED] = total_in;
+        }
+        return;
+    }
+    constexpr uint32_t EPT = FUSED_MAX_IN / FUSED_THREADS;         // elements per thread: 2
+    uint32_t key[EPT], part[EPT];
+    uint32_t bad = 0, invalid = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < EPT; ++q) {
+        const uint32_t e = q * FUSED_THREADS + threadIdx.x;
+        key[q] = ZEN_EMPTY_KEY;
+        part[q] = 0;
+        if (e < total_in) {
+            uint32_t lo = 0, hi = n_in;
+            while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (s_pre[mid] <= e) lo = mid; else hi = mid; }
+            part[q] = lo;
+            key[q] = s_idx[lo][s_begin[lo] + (e - s_pre[lo])];
+            invalid |= key[q] == ZEN_EMPTY_KEY ? 1u : 0u;
+        }
+        s_key[e] = key[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t q = 0; q < EPT; ++q) {
+        const uint32_t e = q * FUSED_THREADS + threadIdx.x;
+        if (e < total_in && e > s_pre[part[q]]) bad |= s_key[e - 1] >= key[q] ? 1u : 0u;
+    }
+    invalid = __syncthreads_or((int)invalid) ? 1u : 0u;
+    bad = (__syncthreads_or((int)bad) || invalid || n_in > SMALL_MERGE_MAX_PARTS) ? 1u : 0u;
+    uint32_t n_listed = total_in;                                   // elements with a valid index
+    if (!bad) {
+        // place in the merged sequence = place in the own part + the elements of every other part before it
+#pragma unroll
+        for (uint32_t q = 0; q < EPT; ++q) {
+            const uint32_t e = q * FUSED_THREADS + threadIdx.x;
+            if (e >= total_in) continue;
+            const uint32_t w = part[q], v = key[q], i = e - s_pre[w];
+            uint32_t pos = i;
+            for (uint32_t o = 0; o < n_in; ++o) {
+                if (o == w) continue;
+                uint32_t lo = s_pre[o], hi = s_pre[o + 1];
+                const uint32_t limit = o < w ? v + 1u : v;          // elements < v, and an equal one if o < w
+                while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (s_key[mid] < limit) lo = mid + 1; else hi = mid; }
+                pos += lo - s_pre[o];
+            }
+            s_sorted[pos] = ((uint64_t)v << 32) | (uint64_t)((w << 26) | i);
+        }
+        __syncthreads();
+    } else {
+        // any order, duplicates, many parts: sort the (index, part, position) words; invalid indices go last
+        uint32_t valid = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < EPT; ++q) {
+            const uint32_t e = q * FUSED_THREADS + threadIdx.x;
+            uint64_t word = ~0ull;
+            if (e < total_in && key[q] != ZEN_EMPTY_KEY) {
+                word = ((uint64_t)key[q] << 32) | (uint64_t)((part[q] << 26) | (e - s_pre[part[q]]));
+                ++valid;
+            }
+            s_sorted[e] = word;
+        }
+        block_exclusive_scan(valid, s_tmp, &n_listed);
+        __syncthreads();
+        // pairs with stride <= 64 touch one wave's own 128 elements only: no block barrier for those stages
+        for (uint32_t k = 2; k <= FUSED_MAX_IN; k <<= 1) {
+            for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+                if (j >= 128) __syncthreads();
+                const uint32_t t = threadIdx.x;
+                const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+                const bool up = (lo & k) == 0;
+                const uint64_t a = s_sorted[lo], b = s_sorted[hi];
+                if ((a > b) == up) { s_sorted[lo] = b; s_sorted[hi] = a; }
+                if (j == 128) __syncthreads();
+                else __builtin_amdgcn_wave_barrier();
+            }
+        }
+        __syncthreads();
+    }
+    // heads of equal-index stretches = output rows
+    const uint64_t cap_rows = outs.cap_rows[server];
+    uint32_t *out_idx = outs.indices[server];
+    const uint32_t a0 = min(threadIdx.x * EPT, n_listed), a1 = min(a0 + EPT, n_listed);
+    uint32_t heads = 0;
+    for (uint32_t a = a0; a < a1; ++a)
+        heads += (a == 0 || (uint32_t)(s_sorted[a] >> 32) != (uint32_t)(s_sorted[a - 1] >> 32)) ? 1u : 0u;
+    uint32_t U;
+    uint32_t u = block_exclusive_scan(heads, s_tmp, &U);
+    for (uint32_t a = a0; a < a1; ++a)
+        if (a == 0 || (uint32_t)(s_sorted[a] >> 32) != (uint32_t)(s_sorted[a - 1] >> 32)) s_rowstart[u++] = a;
+    if (threadIdx.x == 0) {
+        s_rowstart[U] = n_listed;
+        if (blockIdx.x == 0) {
+            *outs.count[server] = U;
+            counters[CNT_UNIQUE] = U;
+            counters[CNT_SKIP] = 0;
+            counters[CNT_FLAGS] = (invalid ? 4u : 0u) | ((uint64_t)U > cap_rows ? 1u : 0u);
+            counters[CNT_NEEDED] = (uint64_t)U > cap_rows ? U : 0u;
+        }
+    }
+    __syncthreads();
+    // sums: one wave per output row
+    const uint32_t rows = (uint64_t)U < cap_rows ? U : (uint32_t)cap_rows;
+    const uint32_t lane = lane_id(), nw = blockDim.x >> 6, V = D >> 2;
+    float *__restrict__ out = out_values.v[server];
+    for (uint32_t r = blockIdx.x * nw + (threadIdx.x >> 6); r < rows; r += gridDim.x * nw) {
+        const uint32_t r0 = s_rowstart[r], r1 = s_rowstart[r + 1];
+        if (lane == 0) out_idx[r] = (uint32_t)(s_sorted[r0] >> 32);
+        f32x4 *o4 = (f32x4 *)(out + (uint64_t)r * D);
+        for (uint32_t v0 = 0; v0 < V; v0 += 64 * 4) {
+            f32x4 acc[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (uint32_t k = r0; k < r1; k += 2) {              // two contributors' loads under way at a time
+                const uint32_t e0 = (uint32_t)s_sorted[k], w0 = e0 >> 26, i0 = e0 & 0x3FFFFFFu;
+                const bool two = k + 1 < r1;
+                const uint32_t e1 = two ? (uint32_t)s_sorted[k + 1] : e0, w1 = e1 >> 26, i1 = e1 & 0x3FFFFFFu;
+                const f32x4 *sa = (const f32x4 *)(s_src[w0] + (uint64_t)(s_vbegin[w0] + i0) * D);
+                const f32x4 *sb = (const f32x4 *)(s_src[w1] + (uint64_t)(s_vbegin[w1] + i1) * D);
+                f32x4 x[4], y[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool in = v0 + 64 * q + lane < V;
+                    x[q] = in ? sa[v0 + 64 * q + lane] : (f32x4){0.f, 0.f, 0.f, 0.f};
+                    y[q] = (in && two) ? sb[v0 + 64 * q + lane] : (f32x4){0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] += x[q];
+                if (two) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[q] += y[q];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (v0 + 64 * q + lane < V) o4[v0 + 64 * q + lane] = acc[q];
+        }
+    }
+}
+
 // Smallest contributor id strictly greater than `prev` (ids are distinct); ~0 if none.
 __device__ __forceinline__ uint64_t next_contrib(const uint64_t *list, uint32_t len, uint64_t prev, bool first)
 {
@@ -418,6 +621,11 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
     // rowstart / rowend: the contributor list of output row u is contrib[rowstart[u] .. rowend[u]) (a CSR array
     // serves as both, rowend = rowstart + 1); strides in u32 words; status: non-NULL when the servers' results
     // are still to be folded into the call's
+    // the parts' base pointers, lane w that of part w, in LDS: indexed by a contributor's part straight from the
+    // kernel arguments they would be fetched from the argument buffer in host memory, once per contributor
+    __shared__ const float *s_src[ZEN_MAX_BATCH];
+    if (threadIdx.x < ZEN_MAX_BATCH) s_src[threadIdx.x] = src_values.v[threadIdx.x];
+    __syncthreads();
     const uint32_t server = blockIdx.y;
     const uint32_t D = row_dim;
     if (status && blockIdx.x == 0 && server == 0 && threadIdx.x == 0) {
@@ -475,7 +683,7 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
                         e = next_contrib(contrib + r0, len, prev, k == 0);   // wave-uniform
                     }
                     prev = e;
-                    const f32x4 *s4 = (const f32x4 *)(src_values.v[(uint32_t)(e >> 32)] + (e & 0xFFFFFFFFull) * D);
+                    const f32x4 *s4 = (const f32x4 *)(s_src[(uint32_t)(e >> 32)] + (e & 0xFFFFFFFFull) * D);
                     f32x4 x[4];
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
@@ -499,7 +707,7 @@ agg_gather_kernel(Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_
             for (uint32_t k = 0; k < len; ++k) {
                 const uint64_t e = next_contrib(contrib + r0, len, prev, k == 0);
                 prev = e;
-                acc += src_values.v[(uint32_t)(e >> 32)][(e & 0xFFFFFFFFull) * D + c];
+                acc += s_src[(uint32_t)(e >> 32)][(e & 0xFFFFFFFFull) * D + c];
             }
             out[f] = acc;
         }
@@ -939,6 +1147,19 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
                                    first_part_id, outs, out_values, ws, L, s);
     }
 
+    if (L.small_path && !any_bitmap && (g.row_dim & 3u) == 0 && g.row_dim >= 256 && max_in_rows <= FUSED_MAX_IN) {
+        // few rows of wide rows: merge and sums in one launch
+#ifndef ZEN_FUSED_BLOCKS
+#define ZEN_FUSED_BLOCKS 256   // about one block per CU: 64 / 128 / 256 / 512 measured 37 / 33 / 31 / 46 us on the LM workload
+#endif
+        uint32_t bx = ZEN_FUSED_BLOCKS / n_servers;
+        if (bx < 1) bx = 1;
+        if (bx > 64) bx = 64;
+        ProfScope prof(ctx, K_AGG_SORT_SMALL, s);
+        agg_fused_kernel<<<dim3(bx, n_servers), FUSED_THREADS, 0, s>>>(src, n_in, (uint32_t)max_in_rows, g.row_dim, n_servers,
+                                                                       counters, outs, src_values, out_values, status);
+        return hipGetLastError();
+    }
     if (L.small_path) {
         uint32_t *dec_flags = any_bitmap ? (uint32_t *)(ws + L.decflags_off) : nullptr;
         if (any_bitmap) {

@@ -114,6 +114,13 @@ __global__ void status_fold_kernel(zen_status_info *status, zen_status_info *acc
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     zen_status_info a = *status;
+    if ((a.reserved & 0xFFFFu) == ZEN_STATUS_IN_COUNTERS) {   // the group's result lies in its servers' counters
+        const uint32_t n_servers = a.reserved >> 16, *counters = (const uint32_t *)status + 64;
+        for (uint32_t j = 0; j < n_servers && j < ZEN_MAX_BATCH; ++j) {
+            a.flags |= counters[j * 16 + 3];
+            a.needed_rows = a.needed_rows > counters[j * 16 + 4] ? a.needed_rows : counters[j * 16 + 4];
+        }
+    }
     if (!first) {
         a.flags |= acc->flags;
         a.needed_rows = a.needed_rows > acc->needed_rows ? a.needed_rows : acc->needed_rows;
@@ -520,6 +527,19 @@ zen_status zen_status_fetch(zen_ctx *ctx, const void *workspace, void *hip_strea
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(hipMemcpyAsync(&info, workspace, sizeof(info), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if ((info.reserved & 0xFFFFu) == ZEN_STATUS_IN_COUNTERS) {
+        // the one-launch aggregate leaves every server's result in its counters: fold them here
+        const uint32_t n_servers = info.reserved >> 16;
+        uint32_t counters[ZEN_MAX_BATCH * 16];
+        if (n_servers == 0 || n_servers > ZEN_MAX_BATCH) return ZEN_ERR_DEVICE;
+        HIP_TRY(hipMemcpyAsync(counters, (const char *)workspace + 256, (size_t)n_servers * 16 * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        info.reserved = 0;
+        for (uint32_t j = 0; j < n_servers; ++j) {
+            info.flags |= counters[j * 16 + 3];
+            if (counters[j * 16 + 4] > info.needed_rows) info.needed_rows = counters[j * 16 + 4];
+        }
+    }
     if (host_info) *host_info = info;
     ctx->last_flags = info.flags;
     ctx->last_needed_rows = info.needed_rows;

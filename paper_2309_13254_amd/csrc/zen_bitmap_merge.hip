@@ -29,10 +29,10 @@ __device__ __forceinline__ const uint32_t *part_words(const BmArgs &a, uint32_t 
 // cnt[server][row][chunk]: row w < n_in = set bits of part w in the chunk, row n_in = union bits.
 __global__ void __launch_bounds__(BM_THREADS)
 bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off, uint32_t *cnt, uint32_t n_chunks,
-                uint32_t *wave_tot, uint32_t *uni_words)
+                uint32_t *wave_tot)
 {
-    // wave_tot / uni_words (element-level merges, else NULL): the same counts per wave of the block,
-    // [server][chunk][row][4], and the union words, [server][chunk][256] -- the merge starts from them
+    // wave_tot (element-level merges, else NULL): the same counts per wave of the block, [server][chunk][row][4]:
+    // where each wave of the merge starts in every part's values and in the output
     __shared__ uint32_t s_c[ZEN_MAX_BATCH + 1];
     __shared__ uint32_t s_wt[(ZEN_MAX_BATCH + 1) * 4];   // the same per wave of the block
     const uint32_t chunk = blockIdx.x, server = blockIdx.y, p = a.first_part + server;
@@ -63,7 +63,6 @@ bm_count_kernel(BmArgs a, const uint32_t *dom_offsets, const uint32_t *word_off,
         if (su) atomicAdd(&s_c[a.n_in], su);
         s_wt[a.n_in * 4 + (threadIdx.x >> 6)] = su;
     }
-    if (uni_words) uni_words[((uint64_t)server * n_chunks + chunk) * BM_CHUNK_WORDS + threadIdx.x] = uni;
     __syncthreads();
     if (wt)
         for (uint32_t i = threadIdx.x; i < (a.n_in + 1) * 4; i += BM_THREADS) wt[i] = s_wt[i];
@@ -133,15 +132,13 @@ bm_scan_kernel(BmArgs a, uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_ba
     }
 }
 
-// Merge: one block per (chunk, server).  D == 1: one thread per bitmap word, private LDS
-// accumulators for the word's up-to-32 output elements.  D > 1: one wave per word, lane w holds
-// part w's word, rows are summed column block by column block in registers.
+// Merge of rows of several floats: one block per (chunk, server), one wave per word, lane w holds part w's
+// word, rows are summed column block by column block in registers.  (Element-level parts: bm_merge_lanes_kernel.)
 __global__ void __launch_bounds__(BM_THREADS)
 bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uint32_t n_servers,
                 const uint32_t *domain, const uint32_t *dom_offsets, const uint32_t *word_off,
                 const uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_base, AggOut outs,
-                Arr64<float *> out_values, zen_status_info *status, const uint32_t *wave_tot,
-                const uint32_t *uni_words)
+                Arr64<float *> out_values, zen_status_info *status)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t chunk = blockIdx.x, server = blockIdx.y, p = a.first_part + server;
@@ -167,123 +164,9 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
     const uint32_t ubase_chunk = pre[(uint64_t)n_in * n_chunks + chunk];
 
     uint32_t *s_wtot = smem;                       // [n_in + 1][4] per-wave totals of the chunk
-    float *s_acc = (float *)(smem + (ZEN_MAX_BATCH + 1) * 4);   // D == 1: [<= 8192] output elements of the chunk
 
     const uint32_t k = chunk * BM_CHUNK_WORDS + threadIdx.x;    // this thread's bitmap word
-    if (D == 1) {
-        // Wave-local tables: each wave owns 64 consecutive bitmap words and the contiguous range of
-        // output elements they produce.
-        uint32_t *s_word = (uint32_t *)(s_acc + BM_CHUNK_WORDS * 32) + wave * 4 * ZEN_WAVE;   // part's words
-        uint32_t *s_ex = s_word + ZEN_WAVE;      // exclusive count of the part's bits before each word
-        uint32_t *s_uni = s_ex + ZEN_WAVE;       // union words
-        uint32_t *s_uex = s_uni + ZEN_WAVE;      // exclusive count of union bits before each word
-        // pass A: the union word and every part's per-wave totals, as the count kernel left them
-        const uint32_t uni = uni_words[((uint64_t)server * n_chunks + chunk) * BM_CHUNK_WORDS + threadIdx.x];
-        {
-            const uint32_t *wt = wave_tot + ((uint64_t)server * n_chunks + chunk) * (ZEN_MAX_BATCH + 1) * 4;
-            for (uint32_t i = threadIdx.x; i < n_in * 4; i += BM_THREADS) s_wtot[i] = wt[i];
-        }
-        const uint32_t uc = __popc(uni);
-        const uint32_t uinc = wave_inclusive_scan(uc);
-        const uint32_t u_wave = __shfl(uinc, ZEN_WAVE - 1, ZEN_WAVE);      // output elements of this wave
-        if (lane == ZEN_WAVE - 1) s_wtot[n_in * 4 + wave] = uinc;
-        s_uni[lane] = uni;
-        s_uex[lane] = uinc - uc;
-        __syncthreads();
-        uint32_t ubase_wave = 0;                      // first output element of this wave, chunk-relative
-        for (uint32_t v = 0; v < wave; ++v) ubase_wave += s_wtot[n_in * 4 + v];
-        float *acc = s_acc + ubase_wave;
-        for (uint32_t i = lane; i < u_wave; i += ZEN_WAVE) acc[i] = 0.f;
-        // pass B: every part adds its values, in part order; the wave walks the part's values (a
-        // contiguous run) and finds each value's (word, bit) by searching the prefix tables
-        // lane w works out where part w's values for this wave start (one load for all parts, not one per part
-        // on the way)
-        uint32_t my_vbase = 0;
-        if (lane < n_in) {
-            my_vbase = pre[(uint64_t)lane * n_chunks + chunk];
-            for (uint32_t v = 0; v < wave; ++v) my_vbase += s_wtot[lane * 4 + v];
-        }
-        for (uint32_t w0 = 0; w0 < n_in; w0 += 8) {
-          uint32_t wd[8];
-#pragma unroll
-          for (uint32_t q = 0; q < 8; ++q)
-              wd[q] = (w0 + q < n_in && k < n_words) ? part_words(a, w0 + q, p, word_off)[k] : 0u;
-#pragma unroll
-          for (uint32_t q = 0; q < 8; ++q) {
-            const uint32_t w = w0 + q;
-            if (w >= n_in) break;
-            const uint32_t word = wd[q];
-            const uint32_t vbase = (uint32_t)__builtin_amdgcn_readlane((int)my_vbase, (int)w);   // every lane is active here
-            if (ballot(word != 0) == 0) continue;     // wave-uniform: the part has no row in these 64 words
-            const uint32_t c = __popc(word);
-            const uint32_t inc = wave_inclusive_scan(c);
-            const uint32_t t_wave = __shfl(inc, ZEN_WAVE - 1, ZEN_WAVE);
-            s_word[lane] = word;
-            s_ex[lane] = inc - c;
-            const float *vals = src_values.v[w] + vbase;
-            __builtin_amdgcn_wave_barrier();
-            for (uint32_t i = lane; i < t_wave; i += ZEN_WAVE) {
-                uint32_t lo = 0;
-#pragma unroll
-                for (uint32_t st = 32; st > 0; st >>= 1)
-                    if (s_ex[lo + st] <= i) lo += st;       // last word whose exclusive count <= i ...
-                // ... that is non-empty: words with zero bits share their successor's count
-                const uint32_t ww = s_word[lo];
-                uint32_t r = i - s_ex[lo], pos = 0;
-#pragma unroll
-                for (uint32_t sh = 16; sh > 0; sh >>= 1) {
-                    const uint32_t lowcnt = __popc((ww >> pos) & ((1u << sh) - 1u));
-                    if (r >= lowcnt) { r -= lowcnt; pos += sh; }
-                }
-                acc[s_uex[lo] + __popc(s_uni[lo] & ((1u << pos) - 1u))] += vals[i];
-            }
-            __builtin_amdgcn_wave_barrier();
-          }
-        }
-        // write out the wave's output range: indices from the sorted domain, values from LDS
-        const uint32_t k0 = chunk * BM_CHUNK_WORDS + wave * ZEN_WAVE;
-        const uint64_t nzu = ballot(uni != 0);
-        if ((uint32_t)__popcll(nzu) < 8 * ((u_wave + ZEN_WAVE - 1) / ZEN_WAVE)) {
-            uint64_t todo = nzu;
-            while (todo) {   // uniform; as above: two union words per trip, a lane per bit
-                const uint32_t wa = (uint32_t)__ffsll((unsigned long long)todo) - 1;
-                todo &= todo - 1;
-                uint32_t wb = ZEN_WAVE;
-                if (todo) { wb = (uint32_t)__ffsll((unsigned long long)todo) - 1; todo &= todo - 1; }
-                const uint32_t src = lane < 32 ? wa : wb, bit = lane & 31u;
-                if (src < ZEN_WAVE) {
-                    const uint32_t ww = s_uni[src];
-                    if ((ww >> bit) & 1u) {
-                        const uint32_t i = s_uex[src] + __popc(ww & ((1u << bit) - 1u));
-                        const uint64_t orow = (uint64_t)ubase_chunk + ubase_wave + i;
-                        if (orow < cap_rows) {
-                            out_idx[orow] = domain[d0 + (k0 + src) * 32 + bit];
-                            out_val[orow] = acc[i];
-                        }
-                    }
-                }
-            }
-            return;
-        }
-        for (uint32_t i = lane; i < u_wave; i += ZEN_WAVE) {
-            uint32_t lo = 0;
-#pragma unroll
-            for (uint32_t st = 32; st > 0; st >>= 1)
-                if (s_uex[lo + st] <= i) lo += st;
-            const uint32_t ww = s_uni[lo];
-            uint32_t r = i - s_uex[lo], pos = 0;
-#pragma unroll
-            for (uint32_t sh = 16; sh > 0; sh >>= 1) {
-                const uint32_t lowcnt = __popc((ww >> pos) & ((1u << sh) - 1u));
-                if (r >= lowcnt) { r -= lowcnt; pos += sh; }
-            }
-            const uint64_t orow = (uint64_t)ubase_chunk + ubase_wave + i;
-            if (orow < cap_rows) {
-                out_idx[orow] = domain[d0 + (k0 + lo) * 32 + pos];
-                out_val[orow] = acc[i];
-            }
-        }
-    } else {
+    {
         // per-part, per-word exclusive positions inside the chunk: s_pre[w][word] (u16, <= 8192)
         uint16_t *s_pre = (uint16_t *)(smem + (ZEN_MAX_BATCH + 1) * 4);     // [n_in + 1][256]
         for (uint32_t w = 0; w <= n_in; ++w) {
@@ -346,8 +229,9 @@ bm_merge_kernel(BmArgs a, Arr64<const float *> src_values, uint32_t row_dim, uin
 // parts are found by one ballot over the lanes, which each hold their own part's 64 bits), the part's mask is
 // broadcast as a scalar, lane b adds that part's value number (values before the span) + (set bits below b),
 // a coalesced load; the union is the OR of the scalars and lane b's output position the number of union bits
-// below it.  No search, no LDS, no atomics; values are added in ascending part order, the first one copied, so
-// every result is the same on every run and a row with one contributor keeps its bits.
+// below it.  No search, no accumulators in LDS, no atomics; values are added in ascending part order starting
+// from -0 (so the first one is copied: -0 + x = x), hence every result is the same on every run and a row with
+// one contributor keeps its bits (a signalling NaN comes out quiet).
 // A block takes a chunk of 256 words as the count kernel does, a wave 64 words = 32 spans.
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef const __attribute__((address_space(1))) float *gfloat_ptr;   // pointers known to be to global memory (they are
@@ -391,13 +275,12 @@ bm_merge_lanes_kernel(BmArgs a, const uint64_t *tabs, uint32_t n_servers, const 
 
     // lane w: where part w's words and values for this wave start
     uint64_t bmbase = 0;       // part w's first word of the wave (an address: lanes hand it round as two words)
-    uint64_t vbase = 0;        // part w's value array
-    uint32_t voff = 0;         // index of part w's first value at or after the current span
+    uint64_t vaddr = 0;        // address of part w's first value at or after the current span
     if (lane < n_in) {
         bmbase = (uint64_t)(uintptr_t)((const uint32_t *)(uintptr_t)tabs[lane] + (a.single ? 0u : word_off[p]) + k0);
-        vbase = tabs[ZEN_MAX_BATCH + lane];
-        voff = pre[(uint64_t)lane * n_chunks + chunk];
+        uint32_t voff = pre[(uint64_t)lane * n_chunks + chunk];
         for (uint32_t v = 0; v < wave; ++v) voff += wt[lane * 4 + v];
+        vaddr = tabs[ZEN_MAX_BATCH + lane] + 4ull * voff;
     }
     uint32_t ubase = pre[(uint64_t)n_in * n_chunks + chunk];         // first output row of this wave (uniform)
     for (uint32_t v = 0; v < wave; ++v) ubase += wt[n_in * 4 + v];
@@ -443,62 +326,52 @@ bm_merge_lanes_kernel(BmArgs a, const uint64_t *tabs, uint32_t n_servers, const 
         for (uint32_t grp = 0; grp < QW / (2 * GS); ++grp) {
             // groups of four spans: the value loads of all four are under way before any is consumed
             float v[GS][SLOTS];
-            uint32_t hm[GS], row[GS], voff_at[GS];
-            uint64_t mine[GS], uni[GS], rest[GS];
+            uint32_t row[GS];
+            uint64_t mine[GS], uni[GS], rest[GS], vaddr_at[GS];
 #pragma unroll
             for (uint32_t sp = 0; sp < GS; ++sp) {
-                const uint32_t wq = (grp * GS + sp) * 2;                               // the span's first word of the half
+                const uint32_t wq = (grp * GS + sp) * 2;                               // the span's first word of the quarter
                 mine[sp] = ((uint64_t)m[wq + 1] << 32) | m[wq];                        // part `lane`'s bits of this span
                 uint64_t active = ballot(mine[sp] != 0);                               // parts with a bit in the span
                 const uint32_t bitpos = (kw + qt * QW + wq) * 32 + lane;               // this lane's bit = row II_p[bitpos]
                 row[sp] = 0;
                 if (active != 0 && bitpos < n_dom) row[sp] = domain[d0 + bitpos];
-                hm[sp] = 0;
                 uni[sp] = 0;
-                voff_at[sp] = voff;
+                vaddr_at[sp] = vaddr;
 #pragma unroll
                 for (uint32_t j = 0; j < SLOTS; ++j) {                                 // the span's first eight parts
-                    v[sp][j] = 0.f;
+                    v[sp][j] = -0.0f;                                                  // x + (-0) = x for every x: an empty slot adds nothing
                     if (active) {                                                      // uniform
                         const uint32_t w = (uint32_t)__ffsll((unsigned long long)active) - 1;
                         active &= active - 1;
                         const uint64_t pm = readlane64(mine[sp], w);                  // part w's bits, a scalar
-                        const gfloat_ptr pv = (gfloat_ptr)(uintptr_t)readlane64(vbase, w) +
-                                              (uint32_t)__builtin_amdgcn_readlane((int)voff, (int)w);
+                        const gfloat_ptr pv = (gfloat_ptr)(uintptr_t)readlane64(vaddr, w);   // its first value of the span
                         uni[sp] |= pm;
-                        if ((pm >> lane) & 1ull) {
-                            hm[sp] |= 1u << j;
-                            v[sp][j] = pv[mbcnt(pm)];                                  // value number = values before + bits below
-                        }
+                        if (__builtin_amdgcn_inverse_ballot_w64(pm)) v[sp][j] = pv[mbcnt(pm)];   // + set bits below this lane
                     }
                 }
                 rest[sp] = active;
-                voff += (uint32_t)__popcll(mine[sp]);                                  // lanes beyond n_in hold no bits
+                vaddr += 4ull * (uint32_t)__popcll(mine[sp]);                          // lanes beyond n_in hold no bits
             }
 #pragma unroll
             for (uint32_t sp = 0; sp < GS; ++sp) {
                 if (uni[sp] == 0) continue;                                            // uniform
-                float acc = 0.f;
+                float acc = -0.0f;                                                     // (-0) + x = x: the first value is copied
 #pragma unroll
-                for (uint32_t j = 0; j < SLOTS; ++j)                                   // ascending part order; the first one is copied
-                    if ((hm[sp] >> j) & 1u) acc = (hm[sp] & ((1u << j) - 1u)) ? acc + v[sp][j] : v[sp][j];
-                bool seen = hm[sp] != 0;
+                for (uint32_t j = 0; j < SLOTS; ++j) acc += v[sp][j];                  // ascending part order
                 uint64_t active = rest[sp];
                 while (active) {                                                       // a span with more than eight parts
                     const uint32_t w = (uint32_t)__ffsll((unsigned long long)active) - 1;
                     active &= active - 1;
                     const uint64_t pm = readlane64(mine[sp], w);
-                    const gfloat_ptr pv = (gfloat_ptr)(uintptr_t)readlane64(vbase, w) +
-                                          (uint32_t)__builtin_amdgcn_readlane((int)voff_at[sp], (int)w);
+                    const gfloat_ptr pv = (gfloat_ptr)(uintptr_t)readlane64(vaddr_at[sp], w);
                     uni[sp] |= pm;
-                    if ((pm >> lane) & 1ull) {
-                        const float x = pv[mbcnt(pm)];
-                        acc = seen ? acc + x : x;
-                        seen = true;
-                    }
+                    float x = -0.0f;
+                    if (__builtin_amdgcn_inverse_ballot_w64(pm)) x = pv[mbcnt(pm)];
+                    acc += x;
                 }
                 const uint32_t o = ubase + mbcnt(uni[sp]);
-                if (((uni[sp] >> lane) & 1ull) && (uint64_t)o < cap_rows) {
+                if (__builtin_amdgcn_inverse_ballot_w64(uni[sp]) && (uint64_t)o < cap_rows) {
                     out_idx[o] = row[sp];
                     out_val[o] = acc;
                 }
@@ -530,7 +403,7 @@ hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitm
     {
         ProfScope prof(ctx, K_BM_COUNT, s);
         bm_count_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, 0, s>>>(a, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt,
-                                                                         n_chunks, wave_tot, nullptr);
+                                                                         n_chunks, wave_tot);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -552,7 +425,7 @@ hipError_t launch_bitmap_merge(zen_ctx *ctx, const Arr64<const uint32_t *> &bitm
         const size_t lds = (size_t)(ZEN_MAX_BATCH + 1) * 4 * 4 + (size_t)(ZEN_MAX_BATCH + 1) * BM_CHUNK_WORDS * 2;
         bm_merge_kernel<<<dim3(n_chunks, n_servers), BM_THREADS, lds, s>>>(
             a, src_values, ctx->geo.row_dim, n_servers, ctx->d_domain, ctx->d_dom_offsets, ctx->d_bm_word_off, cnt,
-            n_chunks, counters, outs, out_values, status, nullptr, nullptr);
+            n_chunks, counters, outs, out_values, status);
         return hipGetLastError();
     }
 }

@@ -78,6 +78,11 @@ struct AggOut {
     uint64_t cap_rows[ZEN_MAX_BATCH];
 };
 
+// Mark in the status block's `reserved` word (low 16 bits; the number of servers in the high 16): the call's flags
+// and rows needed are the OR / maximum of the servers' counters (words CNT_FLAGS = 3 and CNT_NEEDED = 4 of the 16
+// words per server that follow the 256-byte status region), not the status words themselves.
+#define ZEN_STATUS_IN_COUNTERS 0xA66Cu
+
 struct AggLayout {
     uint64_t status_off;     // zen_status_info
     uint64_t counters_off;   // per server: 16 u32 (0: unique count, 1: total rows in)

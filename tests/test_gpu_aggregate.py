@@ -237,3 +237,82 @@ def test_aggregate_batch_more_servers_than_one_launch_group(oracle, zen, fmt_bit
     assert U == ref_out[3].U and np.array_equal(idx, ref_out[3].indices[:5])
     U, idx, _ = G.aggregated_to_host(outs[99])
     assert U == ref_out[99].U and np.array_equal(idx, ref_out[99].indices)
+
+
+@pytest.mark.parametrize("ascending", [False, True])
+@pytest.mark.parametrize("n_in", [1, 9, 23])
+@pytest.mark.parametrize("D", [256, 260, 1024])
+def test_one_launch_merge_of_few_wide_rows(oracle, zen, D, n_in, ascending):
+    """At most 2,048 incoming rows of wide rows: merge and sums run in one launch (binary-search merge for ascending
+    parts, a sort otherwise).  Against the oracle, bit for bit against the multi-kernel table path, and with an
+    output capacity and a bound on the incoming rows that are too small."""
+    import gpu_util as G
+
+    rng = np.random.default_rng(7 * D + n_in + int(ascending))
+    R = 30000
+    ctx = zen.ZenContext(R, D, 4, 77)
+    parts_d, total = [], 0
+    for w in range(n_in):
+        c = int(rng.integers(0, 2000 // n_in))
+        idx = rng.integers(0, 1500, size=c).astype(np.uint32)          # heavy overlap, duplicates inside a part
+        if ascending:
+            idx = np.unique(idx)
+            c = idx.size
+        val = rng.standard_normal((max(c, 1), D)).astype(np.float32)[:c]
+        parts_d.append((G.to_dev(idx) if c else torch.empty(1, dtype=torch.int32, device="cuda"), None,
+                        torch.from_numpy(val).cuda() if c else torch.empty((1, D), device="cuda"),
+                        torch.tensor([c], dtype=torch.int32, device="cuda")))
+        total += c
+    assert 0 < total <= 2048
+    ref = oracle.aggregate([(G.u32(p[0])[:int(p[3].item())], p[2].cpu().numpy()[:int(p[3].item())]) for p in parts_d], R, D)
+    results = []
+    for max_in in (total, 2048, total * 40):                            # one launch twice, then the table path
+        out = zen.alloc_aggregated(ctx, total)
+        ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, max_in))
+        ws[: ws.numel() // 4 * 4].view(torch.int32).fill_(-1)
+        zen.zen_aggregate(ctx, parts_d, 1, out, max_in, ws)
+        assert zen.zen_status_fetch(ctx, ws) == (0, 0, 0)
+        results.append(G.aggregated_to_host(out))
+    U0, idx0, val0 = results[0]
+    assert U0 == ref.U and np.array_equal(idx0, ref.indices)
+    G.check_sums(val0, ref)
+    for U, idx, val in results[1:]:
+        assert U == U0 and np.array_equal(idx, idx0)
+        assert np.array_equal(val.view(np.uint32), val0.view(np.uint32))
+    if ref.U > 3:
+        # output capacity too small: flag, count = U, the first rows correct, nothing past the capacity
+        cap = ref.U // 2
+        guard_idx = torch.full((ref.U,), -2, dtype=torch.int32, device="cuda")
+        guard_val = torch.full((ref.U, D), 7.0, device="cuda")
+        out2 = zen.Aggregated(guard_idx, guard_val, torch.zeros(1, dtype=torch.int32, device="cuda"), cap)
+        ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, total))
+        zen.zen_aggregate(ctx, parts_d, 1, out2, total, ws)
+        st, flags, needed = zen.zen_status_fetch(ctx, ws)
+        assert st == zen.ZEN_ERR_CAPACITY and flags == 1 and needed == ref.U and zen.zen_last_overflow(ctx) == ref.U
+        assert int(out2.count.item()) == ref.U
+        assert np.array_equal(G.u32(guard_idx[:cap]), ref.indices[:cap])
+        assert np.array_equal(guard_val[:cap].cpu().numpy().view(np.uint32), val0[:cap].view(np.uint32))
+        assert torch.all(guard_idx[cap:] == -2) and torch.all(guard_val[cap:] == 7.0)
+        # bound on the incoming rows too small: table flag, nothing put out
+        out3 = zen.alloc_aggregated(ctx, total)
+        ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, total - 1))
+        zen.zen_aggregate(ctx, parts_d, 1, out3, total - 1, ws)
+        st, flags, needed = zen.zen_status_fetch(ctx, ws)
+        assert st == zen.ZEN_ERR_CAPACITY and flags == 2 and needed == total
+        assert int(out3.count.item()) == 0
+
+
+def test_one_launch_merge_flags_a_reserved_index(oracle, zen):
+    import gpu_util as G
+
+    D, R = 256, 1000
+    ctx = zen.ZenContext(R, D, 2, 5)
+    idx = np.array([3, 0xFFFFFFFF, 9], np.uint32)
+    part = (G.to_dev(idx), None, torch.ones((3, D), device="cuda"), torch.tensor([3], dtype=torch.int32, device="cuda"))
+    out = zen.alloc_aggregated(ctx, 8)
+    ws = zen.alloc_workspace(zen.zen_aggregate_workspace_bytes(ctx, 1, 8))
+    zen.zen_aggregate(ctx, [part, part], 0, out, 8, ws)
+    st, flags, _ = zen.zen_status_fetch(ctx, ws)
+    assert st == zen.ZEN_ERR_INVALID and flags == 4
+    U, idx_out, val = G.aggregated_to_host(out)
+    assert U == 2 and idx_out.tolist() == [3, 9] and np.all(val == 2.0)
