@@ -188,8 +188,10 @@ template <int PATH>
 __global__ void __launch_bounds__(DETECT_THREADS)
 detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_stride_words,
               uint32_t *hist_base, uint64_t hist_stride_words, uint32_t *tflag_base, uint64_t tflag_stride,
-              zen_status_info *reset_status, const uint32_t *min_mag, uint32_t seg_flags)
+              zen_status_info *reset_status, const uint32_t *min_mag, uint32_t seg_flags, const uint32_t *group_base)
 {
+    // group_base (element-level hash-bitmap contexts, else NULL): rows of every partition below each 512-row
+    // boundary -- the owners of a fully non-zero 512-row group are then two table rows' difference, not 512 hashes
     // seg_flags (element-level tiles of SEG_FLAG_WORDS * 32 mask words only): the tile's flag word says which of its
     // 32 segments hold a non-zero row, and only those segments' mask words are written -- for a consumer that
     // reads the mask through the flag word (the scatter).  Otherwise a non-empty tile's flag is all ones.
@@ -254,7 +256,39 @@ detect_kernel(Geometry g, GradPtrs grads, uint32_t *mask_base, uint64_t mask_str
         if ((flag_word >> ((i / SEG_FLAG_WORDS) & 31u)) & 1u) gmask[i] = s_mask[i];
     if (!hist_base) return;   // the one-block-per-worker partition path hashes the rows itself
     // owner histogram of the tile's non-zero rows: walk the mask words, most of them are zero
-    if (g.tile_words >= blockDim.x) {
+    if (PATH == 0 && group_base && (g.tile_words & 63u) == 0 && g.tile_words <= 1024 && (blockDim.x & 63u) == 0) {
+        // (long runs of non-zeros) a wave's 64 consecutive words are four groups of 512 rows; a group whose 16 words
+        // are all ones is only marked, and partition p's share of every stretch of marked groups is read off the table
+        __shared__ uint32_t s_full[2];                        // one bit per group of the tile (<= 64)
+        if (threadIdx.x < 2) s_full[threadIdx.x] = 0;
+        __syncthreads();
+        for (uint32_t wi = threadIdx.x; wi < g.tile_words; wi += blockDim.x) {
+            uint32_t word = s_mask[wi];
+            const uint64_t ones = ballot(word == 0xFFFFFFFFu);
+            const uint32_t l16 = lane_id() & ~15u;
+            if (((ones >> l16) & 0xFFFFull) == 0xFFFFull) {
+                const uint32_t gi = wi / GROUP_WORDS;
+                if ((lane_id() & 15u) == 0) atomicOr(&s_full[gi >> 5], 1u << (gi & 31u));
+                continue;
+            }
+            while (word) {
+                const uint32_t b = __ffs(word) - 1;
+                word &= word - 1;
+                atomicAdd(&s_hist[owner_of((uint32_t)(row0 + wi * 32 + b), g.seed, g.n_parts, g.pow2_mask)], 1u);
+            }
+        }
+        __syncthreads();
+        uint64_t m = ((uint64_t)s_full[1] << 32) | s_full[0];
+        const uint64_t G0 = row0 / ZEN_GROUP_ROWS;
+        while (m) {                                           // uniform: stretches of marked groups
+            const uint32_t g0 = (uint32_t)__ffsll((unsigned long long)m) - 1;
+            const uint64_t rest = ~(m >> g0);                 // first unmarked group at or after g0 (bit 64 - g0 and up are ones)
+            const uint32_t len = rest ? (uint32_t)__ffsll((unsigned long long)rest) - 1 : 64u - g0;
+            for (uint32_t p = threadIdx.x; p < g.n_parts; p += blockDim.x)
+                s_hist[p] += group_base[(G0 + g0 + len) * g.n_parts + p] - group_base[(G0 + g0) * g.n_parts + p];
+            m = (g0 + len >= 64u) ? 0ull : (m >> (g0 + len)) << (g0 + len);
+        }
+    } else if (g.tile_words >= blockDim.x) {
         for (uint32_t wi = threadIdx.x; wi < g.tile_words; wi += blockDim.x) {
             uint32_t word = s_mask[wi];
             while (word) {
@@ -1220,7 +1254,8 @@ hipError_t launch_detect(zen_ctx *ctx, const GradPtrs &grads, uint32_t batch, ch
     case P:                                                                                                \
         detect_kernel<P><<<grid, DETECT_THREADS, lds, s>>>(g, grads, mask, L.mask_stride / 4, hist,        \
                                                           L.hist_stride / 4, tflag, L.flag_stride / 4, rs, \
-                                                          min_mag, seg_flags ? 1u : 0u);                   \
+                                                          min_mag, seg_flags ? 1u : 0u,                    \
+                                                          (want_hist && g.bitmap) ? ctx->d_group_base : nullptr); \
         break;
     switch (path) {
         ZEN_DETECT_CASE(0) ZEN_DETECT_CASE(1) ZEN_DETECT_CASE(2) ZEN_DETECT_CASE(3) ZEN_DETECT_CASE(4)
