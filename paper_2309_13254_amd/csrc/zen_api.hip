@@ -63,6 +63,7 @@ EncodeLayout encode_layout(const Geometry &g, uint32_t batch)
     L.flag_off = off; off += L.flag_stride * batch;
     L.list_stride = align_up(2 * ((uint64_t)g.n_tiles + 1) * 4, 256);   // ids, their number, the listed tiles' flag words
     L.list_off = off; off += L.list_stride * batch;
+    L.slice_off = off; off += align_up((uint64_t)batch * ((g.n_tiles + 255) / 256) * (g.n_parts + 1) * 4, 256);
     L.total = off;
     return L;
 }

@@ -461,6 +461,156 @@ partition_scan_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_
 }
 
 // ----------------------------------------------------------------------------------------------
+// E4 over the whole chip, for workers with thousands of tiles: the tiles of a worker are cut into slices of
+// SLICE_TILES, a block per (slice, worker).  First launch: every slice's per-partition sums and its number of
+// non-empty tiles.  Second launch: every block adds up the sums of the slices before its own (and of all
+// slices: the offsets), turns its slice's histogram rows into output positions and lists its non-empty tiles
+// behind those of the slices before it.  Same results as partition_scan_kernel.
+// ----------------------------------------------------------------------------------------------
+static constexpr uint32_t SLICE_TILES = 256;
+static constexpr uint32_t SLICE_MIN_TILES = 2048;   // fewer tiles per worker: one block per worker does it in one launch
+
+// MODE 0: sums only (slice_sums[worker][slice][n_parts + 1], the last word = listed tiles of the slice);
+// MODE 1: positions, offsets, tile list.
+template <int MODE>
+__global__ void __launch_bounds__(SCAN_THREADS)
+partition_slice_kernel(Geometry g, EncodedPtrs outs, uint32_t *hist_base, uint64_t hist_stride_words,
+                       const uint32_t *tflag_base, uint64_t tflag_stride, uint32_t *tlist_base, uint64_t tlist_stride,
+                       uint32_t *slice_sums, zen_status_info *status)
+{
+    __shared__ uint32_t s_part[SCAN_THREADS];   // [grp][p] partial sums
+    __shared__ uint32_t s_alt[SCAN_THREADS];
+    __shared__ uint32_t s_off[ZEN_MAX_PARTS + 1];
+    __shared__ uint32_t s_base[ZEN_MAX_PARTS];  // rows of partition p in the slices before this one
+    __shared__ uint32_t s_flag[SLICE_TILES];
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t slice = blockIdx.x, n_slices = gridDim.x, worker = blockIdx.y;
+    uint32_t *hist = hist_base + worker * hist_stride_words;
+    const uint32_t *tflag = tflag_base + worker * tflag_stride;   // rows of empty tiles are undefined
+    uint32_t *sums = slice_sums + (uint64_t)worker * n_slices * (g.n_parts + 1);
+    const uint32_t n = g.n_parts;
+    const uint32_t T0 = slice * SLICE_TILES, T1 = min(T0 + SLICE_TILES, g.n_tiles);
+    const uint32_t n_groups = min((uint32_t)SCAN_THREADS / n, SLICE_TILES);   // >= 1 since n <= 1024
+    const uint32_t p = threadIdx.x % n, grp = threadIdx.x / n;
+    const bool active = grp < n_groups;
+    const uint32_t per = (SLICE_TILES + n_groups - 1) / n_groups;
+    const uint32_t t0 = active ? min(T0 + grp * per, T1) : 0;
+    const uint32_t t1 = active ? min(t0 + per, T1) : 0;
+
+    uint32_t listed_here = 0;
+    for (uint32_t i = threadIdx.x; i < SLICE_TILES; i += SCAN_THREADS) {
+        const uint32_t t = T0 + i;
+        const uint32_t f = t < T1 ? (g.sparse_mask ? tflag[t] : 0xFFFFFFFFu) : 0u;
+        s_flag[i] = f;
+        listed_here += f ? 1u : 0u;
+    }
+    __syncthreads();
+    auto tile_on = [&](uint32_t t) -> bool { return !(g.sparse_mask & 2u) || s_flag[t - T0] != 0; };   // has a histogram row?
+
+    uint32_t sum = 0;
+    for (uint32_t tb = t0; tb < t1; tb += 8) {
+        uint32_t h[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) {
+            const uint32_t t = tb + u;
+            h[u] = (t < t1 && tile_on(t)) ? hist[(uint64_t)t * n + p] : 0u;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) sum += h[u];
+    }
+    if (active) s_part[grp * n + p] = sum;
+    __syncthreads();
+    // inclusive scan over groups for each p (Hillis-Steele along the group axis, all p at once)
+    uint32_t *cur = s_part, *nxt = s_alt;
+    for (uint32_t d = 1; d < n_groups; d <<= 1) {
+        uint32_t v = 0;
+        if (active) v = cur[grp * n + p] + (grp >= d ? cur[(grp - d) * n + p] : 0u);
+        if (active) nxt[grp * n + p] = v;
+        __syncthreads();
+        uint32_t *t = cur; cur = nxt; nxt = t;
+    }
+    if (MODE == 0) {
+        if (threadIdx.x < n) sums[(uint64_t)slice * (n + 1) + threadIdx.x] = cur[(n_groups - 1) * n + threadIdx.x];
+        uint32_t total;
+        block_exclusive_scan(listed_here, s_tmp, &total);
+        if (threadIdx.x == 0) sums[(uint64_t)slice * (n + 1) + n] = total;
+        return;
+    }
+    // totals of all slices and of the slices before this one, per partition (thread p) and for the tile list
+    uint32_t tot_p = 0, before_p = 0;
+    if (threadIdx.x < n) {
+        for (uint32_t s0 = 0; s0 < n_slices; s0 += 8) {
+            uint32_t v[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) v[u] = s0 + u < n_slices ? sums[(uint64_t)(s0 + u) * (n + 1) + threadIdx.x] : 0u;
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                tot_p += v[u];
+                if (s0 + u < slice) before_p += v[u];
+            }
+        }
+        s_base[threadIdx.x] = before_p;
+    }
+    uint32_t listed_before = 0, listed_all = 0;    // (uniform: every thread adds up the same few words)
+    for (uint32_t s0 = 0; s0 < n_slices; ++s0) {
+        const uint32_t v = sums[(uint64_t)s0 * (n + 1) + n];
+        listed_all += v;
+        if (s0 < slice) listed_before += v;
+    }
+    uint32_t n_total;
+    const uint32_t off_p = block_exclusive_scan(tot_p, s_tmp, &n_total);
+    if (threadIdx.x < n) s_off[threadIdx.x] = off_p;
+    uint32_t my_prefix = 0;   // rows of partition p in the groups before mine
+    if (active) my_prefix = cur[grp * n + p] - sum;
+    if (threadIdx.x == 0) {
+        s_off[n] = n_total;
+        if (slice == 0 && (uint64_t)n_total > outs.cap_rows[worker]) {
+            atomicOr(&status->flags, 1u);
+            atomicMax((unsigned long long *)&status->needed_rows, (unsigned long long)n_total);
+        }
+    }
+    __syncthreads();
+    if (slice == 0)
+        for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) outs.offsets[worker][i] = s_off[i];
+    if (active) {
+        uint32_t run = s_off[p] + s_base[p] + my_prefix;
+        for (uint32_t tb = t0; tb < t1; tb += 8) {
+            uint32_t h[8];
+            bool on[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t t = tb + u;
+                on[u] = t < t1 && tile_on(t);
+                h[u] = on[u] ? hist[(uint64_t)t * n + p] : 0u;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                if (on[u]) hist[(uint64_t)(tb + u) * n + p] = run;
+                run += h[u];
+            }
+        }
+    }
+    if (tlist_base) {
+        uint32_t *tlist = tlist_base + worker * tlist_stride;
+        for (uint32_t i0 = 0; i0 < SLICE_TILES; i0 += blockDim.x) {       // one pass: SLICE_TILES <= blockDim.x
+            const uint32_t i = i0 + threadIdx.x;
+            const uint32_t f = i < SLICE_TILES ? s_flag[i] : 0u;
+            uint32_t total;
+            const uint32_t at = listed_before + block_exclusive_scan(f ? 1u : 0u, s_tmp, &total);
+            if (f) {
+                tlist[at] = T0 + i;
+                tlist[(g.n_tiles + 1) + at] = f;
+            }
+            listed_before += total;
+        }
+        if (slice == 0 && threadIdx.x == 0) {
+            tlist[g.n_tiles] = listed_all;
+            tlist[2 * g.n_tiles + 1] = 0;   // length of a second list a consumer may build in place of the flag words
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
 // E5 + E6 (+E7): blocks walk (tile, worker) pairs.  For every non-empty tile: expand the mask in
 // segments to an ascending row list in LDS, rank every row stably inside its partition, write the
 // index, copy the row's values, and (hash-bitmap format) set the row's bit.
@@ -1270,6 +1420,19 @@ hipError_t launch_partition_scan(zen_ctx *ctx, const EncodedPtrs &outs, uint32_t
 {
     const Geometry &g = ctx->geo;
     ProfScope prof(ctx, K_PARTITION_SCAN, s);
+    if (g.n_tiles >= SLICE_MIN_TILES) {
+        // many tiles per worker: slices of tiles over the whole chip, two launches
+        const uint32_t n_slices = (g.n_tiles + SLICE_TILES - 1) / SLICE_TILES;
+        partition_slice_kernel<0><<<dim3(n_slices, batch), SCAN_THREADS, 0, s>>>(
+            g, outs, (uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off), L.flag_stride / 4,
+            (uint32_t *)(ws + L.list_off), L.list_stride / 4, (uint32_t *)(ws + L.slice_off), (zen_status_info *)(ws + L.status_off));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        partition_slice_kernel<1><<<dim3(n_slices, batch), SCAN_THREADS, 0, s>>>(
+            g, outs, (uint32_t *)(ws + L.hist_off), L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off), L.flag_stride / 4,
+            (uint32_t *)(ws + L.list_off), L.list_stride / 4, (uint32_t *)(ws + L.slice_off), (zen_status_info *)(ws + L.status_off));
+        return hipGetLastError();
+    }
     partition_scan_kernel<<<batch, SCAN_THREADS, 0, s>>>(g, outs, (uint32_t *)(ws + L.hist_off),
                                                          L.hist_stride / 4, (const uint32_t *)(ws + L.flag_off),
                                                          L.flag_stride / 4,

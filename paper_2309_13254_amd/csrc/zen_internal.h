@@ -47,6 +47,7 @@ struct EncodeLayout {
     uint64_t list_off;       // per worker: 2 * (n_tiles + 1) u32: ascending ids of the flagged tiles, their number (at n_tiles),
                              //             then the listed tiles' flag words
     uint64_t list_stride;
+    uint64_t slice_off;      // all workers: per (worker, slice of 256 tiles) n_parts + 1 u32, the sliced partition scan's sums
     uint64_t total;
 };
 
