@@ -978,6 +978,64 @@ rs_scatter_kernel(const uint32_t *in_base, uint32_t *out_base, uint64_t uniq_str
     }
 }
 
+// One radix pass in ONE launch, for servers with few blocks of keys (<= RS_FUSED_MAX_BLOCKS): every block counts the
+// digits of all of the server's keys itself (a hundred KB out of the L2) -- the totals per digit and, of the keys
+// before its own, the counts per digit -- which is all that the histogram, scan and scatter launches passed
+// between them, and then ranks and writes its own keys.  Three launches per sort instead of nine; the launches,
+// not the keys, were what the sort of a few ten thousand keys cost.
+static constexpr uint32_t RS_FUSED_MAX_BLOCKS = 32;
+
+__global__ void __launch_bounds__(AGG_THREADS)
+rs_pass_kernel(const uint32_t *in_base, uint32_t *out_base, uint64_t uniq_stride, const uint32_t *counters_base,
+               uint32_t shift)
+{
+    __shared__ uint32_t s_tot[256];       // keys of the server per digit
+    __shared__ uint32_t s_run[256];       // first the keys before this block's per digit, then running output positions
+    __shared__ uint32_t s_cnt[4 * 256];
+    __shared__ uint32_t s_tmp[32];
+    const uint32_t server = blockIdx.y;
+    const uint32_t U = counters_base[server * 16 + CNT_UNIQUE];
+    const uint32_t n_blocks = (U + RS_BLOCK_KEYS - 1) / RS_BLOCK_KEYS;
+    if (blockIdx.x >= n_blocks) return;
+    const uint32_t *in = in_base + (uint64_t)server * uniq_stride;
+    uint32_t *out = out_base + (uint64_t)server * uniq_stride;
+    s_tot[threadIdx.x] = 0;
+    s_run[threadIdx.x] = 0;
+    for (uint32_t i = threadIdx.x; i < 4 * 256; i += blockDim.x) s_cnt[i] = 0;
+    __syncthreads();
+    const uint32_t k0 = blockIdx.x * RS_BLOCK_KEYS;
+    constexpr uint32_t RD = 24;           // loads under way per thread: the count is a chain of round trips otherwise
+    for (uint32_t i0 = 0; i0 < U; i0 += RD * AGG_THREADS) {
+        uint32_t key[RD];
+#pragma unroll
+        for (uint32_t u = 0; u < RD; ++u) {
+            const uint32_t i = i0 + u * AGG_THREADS + threadIdx.x;
+            key[u] = i < U ? in[i] : 0u;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < RD; ++u) {
+            const uint32_t i = i0 + u * AGG_THREADS + threadIdx.x;
+            if (i < U) {
+                const uint32_t d = (key[u] >> shift) & 255u;
+                atomicAdd(&s_tot[d], 1u);
+                if (i < k0) atomicAdd(&s_run[d], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t total;
+    const uint32_t first = block_exclusive_scan(s_tot[threadIdx.x], s_tmp, &total);   // keys with a smaller digit
+    s_run[threadIdx.x] += first;
+    __syncthreads();
+    for (int it = 0; it < RS_ITEMS; ++it) {
+        const uint32_t i = k0 + it * AGG_THREADS + threadIdx.x;
+        const bool valid = i < U;
+        const uint32_t key = valid ? in[i] : 0u;
+        const uint32_t pos = block_stable_rank(valid, (key >> shift) & 255u, 8, 256, s_run, s_cnt);
+        if (valid) out[pos] = key;
+    }
+}
+
 // A3, large tables, last step: sorted unique keys -> out_indices, *count, and each key's rank.
 __global__ void __launch_bounds__(AGG_THREADS)
 agg_finalize_kernel(uint32_t seed, const uint32_t *sorted_base, uint64_t uniq_stride, const uint32_t *keys_base,
@@ -1247,6 +1305,13 @@ hipError_t launch_aggregate(zen_ctx *ctx, const PartIdx &src,
         while (key_bits < 32 && (1ull << key_bits) < g.n_rows) ++key_bits;
         uint32_t *a = uniq, *b = uniq + L.uniq_cap;
         for (uint32_t shift = 0; shift < key_bits; shift += 8) {
+            if (L.sort_blocks <= RS_FUSED_MAX_BLOCKS) {
+                ProfScope prof(ctx, K_RS_SCATTER, s);
+                rs_pass_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(a, b, ustride, counters, shift);
+                ZEN_LAUNCH_CHECK();
+                uint32_t *t = a; a = b; b = t;
+                continue;
+            }
             {
                 ProfScope prof(ctx, K_RS_HIST, s);
                 rs_hist_kernel<<<dim3((uint32_t)L.sort_blocks, n_servers), AGG_THREADS, 0, s>>>(a, ustride, counters, shift,
