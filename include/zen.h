@@ -381,8 +381,8 @@ zen_status zen_hash_many(const uint32_t *idx, uint64_t count, uint32_t seed, uin
  * which hardware HBM byte counters are scaled when the library is profiled. */
 zen_status zen_calibration_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream);
 
-/* Plain streaming READ of `bytes` (multiple of 16, src 16-byte aligned) with 16-byte loads: no stores (sink, a
- * device array of 64 words, is written only if the OR of everything read is all ones), no LDS.  Not part of
+/* Plain streaming READ of `bytes` (multiple of 16, src 16-byte aligned) with 16-byte loads: no LDS and next to no stores
+ * (sink, a device array of 64 words, gets one word from a wave whose lanes each OR what they read to all ones).  Not part of
  * the method: it measures what a read-only stream reaches in a given launch shape -- the rate the dense scan of
  * zen_encode is held against -- and is a second kernel of known traffic for the byte counters.
  * host_shape == NULL: the dense scan's own shape (256 threads, 8 loads in flight, a 128 KiB tile per block,

@@ -8,8 +8,9 @@ namespace zen {
 
 // Block b reads the vectors [b * vec_per_block, (b + 1) * vec_per_block) and then strides on by the grid: with one
 // block per range that is a tile per block (the dense scan's shape), with fewer blocks a persistent grid.  UNROLL
-// 16-byte loads per thread are in flight at a time.  The OR of everything read is formed so that no load can be
-// dropped; it is stored only if it is all ones, which finite floats never are.
+// 16-byte loads per thread are in flight at a time.  Each lane ORs everything it reads, so that no load can be
+// dropped; a wave stores one word only if every lane of it ended at all ones, which data with any bit clear
+// throughout never does and other data does at most once per wave.
 template <int THREADS, int UNROLL, bool NT>
 __global__ void __launch_bounds__(THREADS)
 read_kernel(const u32x4 *__restrict__ src, uint64_t n_vec, uint64_t vec_per_block, uint32_t *sink)
