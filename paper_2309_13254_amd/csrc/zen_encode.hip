@@ -700,9 +700,21 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             if (i < g.tile_words && seg_written(nxt_flag, i)) mw[q] = wmask[(uint64_t)nxt_tile * g.tile_words + i];
         }
     }
+    // element-level, at most one partition per thread: the tile's positions and bit ranges are fetched a tile ahead too
+    const bool pf_part = ELEM && n <= SCATTER_THREADS;
+    const uint32_t *whist = hist_base + worker * hist_stride_words;
+    uint32_t pf_h = 0, pf_b0 = 0, pf_b1 = 0;
+    if (pf_part && threadIdx.x < n && k < n_visit) {
+        pf_h = whist[(uint64_t)nxt_tile * n + threadIdx.x];
+        if (bitmap) {
+            pf_b0 = bt.tile_base[(uint64_t)nxt_tile * n + threadIdx.x];
+            pf_b1 = bt.tile_base[(uint64_t)(nxt_tile + 1) * n + threadIdx.x];
+        }
+    }
     for (; k < n_visit; k += gridDim.x) {
         const uint32_t tile = nxt_tile, tile_flag = nxt_flag;
         const uint32_t *gmask = wmask + (uint64_t)tile * g.tile_words;
+        const uint32_t cur_h = pf_h, cur_b0 = pf_b0, cur_b1 = pf_b1;
         if (ELEM) {
             __syncthreads();                                   // the barrier between tiles
             // The tile's mask goes to LDS with a row count per 16-word group: empty groups then cost neither a
@@ -739,6 +751,13 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                     mw[q] = (i < g.tile_words && seg_written(nxt_flag, i)) ? wmask[(uint64_t)nxt_tile * g.tile_words + i] : 0u;
                 }
             }
+            if (pf_part && threadIdx.x < n && k + gridDim.x < n_visit) {
+                pf_h = whist[(uint64_t)nxt_tile * n + threadIdx.x];
+                if (bitmap) {
+                    pf_b0 = bt.tile_base[(uint64_t)nxt_tile * n + threadIdx.x];
+                    pf_b1 = bt.tile_base[(uint64_t)(nxt_tile + 1) * n + threadIdx.x];
+                }
+            }
             __syncthreads();
         } else {
             nxt_tile = nxt2_tile;
@@ -753,9 +772,10 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             }
         }
 
-        const uint32_t *ghist = hist_base + worker * hist_stride_words + (uint64_t)tile * n;
+        const uint32_t *ghist = whist + (uint64_t)tile * n;
         const uint64_t row0 = (uint64_t)tile * g.tile_rows;
-        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_run[i] = ghist[i];
+        if (pf_part) { if (threadIdx.x < n) s_run[threadIdx.x] = cur_h; }
+        else for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s_run[i] = ghist[i];
 
         if (bitmap) {
             // per-partition bit ranges of this tile and their LDS placement (what follows meets a barrier
@@ -765,7 +785,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
                 if (threadIdx.x < ZEN_WAVE) {
                     const uint32_t p = threadIdx.x;
                     uint32_t b0 = 0, b1 = 0;
-                    if (p < n) { b0 = tb0[p]; b1 = tb1[p]; }
+                    if (p < n) { b0 = pf_part ? cur_b0 : tb0[p]; b1 = pf_part ? cur_b1 : tb1[p]; }
                     const uint32_t wcnt = b1 > b0 ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0;
                     const uint32_t inc = wave_inclusive_scan(wcnt);
                     if (p < n) { s_b0[p] = b0; s_b1[p] = b1; s_boff[p] = inc - wcnt; }
@@ -777,7 +797,7 @@ scatter_kernel(Geometry g, GradPtrs grads, EncodedPtrs outs, const uint32_t *mas
             const uint32_t p0 = min(threadIdx.x * per, n), p1 = min(p0 + per, n);
             uint32_t mine = 0;
             for (uint32_t p = p0; p < p1; ++p) {
-                const uint32_t b0 = tb0[p], b1 = tb1[p];
+                const uint32_t b0 = pf_part ? cur_b0 : tb0[p], b1 = pf_part ? cur_b1 : tb1[p];   // (then per = 1: p = threadIdx.x)
                 s_b0[p] = b0;
                 s_b1[p] = b1;
                 mine += b1 > b0 ? ((b1 - 1) >> 5) - (b0 >> 5) + 1 : 0;
