@@ -26,8 +26,9 @@ stats_kernel(Geometry g, uint32_t W, const uint32_t *mask_base, uint64_t mask_st
     if (threadIdx.x < ZEN_MAX_BATCH) {
         s_nnz[threadIdx.x] = 0;
         s_uni[threadIdx.x] = 0;
-        // element-level inputs: mask words of an empty tile were never written
-        s_flag[threadIdx.x] = threadIdx.x < W && (!g.sparse_mask || tflag_base[threadIdx.x * tflag_stride + tile]);
+        // the tile's flag word: bit s says that the s-th stretch of 32 mask words was written (all ones where the
+        // scan keeps no flags; mask words of an empty tile, or of an empty stretch, were never written)
+        s_flag[threadIdx.x] = threadIdx.x >= W ? 0u : !g.sparse_mask ? 0xFFFFFFFFu : tflag_base[threadIdx.x * tflag_stride + tile];
     }
     __syncthreads();
     const uint64_t row0 = (uint64_t)tile * g.tile_rows;
@@ -38,7 +39,7 @@ stats_kernel(Geometry g, uint32_t W, const uint32_t *mask_base, uint64_t mask_st
 #pragma unroll
         for (uint32_t w = 0; w < ZEN_MAX_BATCH; ++w) {
             m[w] = 0;
-            if (w < W && wi < g.tile_words && s_flag[w])
+            if (w < W && wi < g.tile_words && ((s_flag[w] >> ((wi >> 5) & 31u)) & 1u))
                 m[w] = mask_base[w * mask_stride_words + (uint64_t)tile * g.tile_words + wi];
         }
         // the word's rows and the even partition(s) they fall into
@@ -151,7 +152,7 @@ zen_status zen_sparsity_count(zen_ctx *ctx, const float *const *host_grads, uint
     char *ws = (char *)workspace;
     StatsOut out{(unsigned long long *)host_out->nnz, (unsigned long long *)host_out->union_prefix,
                  (unsigned long long *)host_out->overlap, (unsigned long long *)host_out->even_split};
-    HIP_TRY(launch_detect(ctx, grads, n_workers, ws, L, true, false, s));
+    HIP_TRY(launch_detect(ctx, grads, n_workers, ws, L, true, false, s, nullptr, true));   // masks by stretch: fewer words written
     stats_zero_kernel<<<64, 256, 0, s>>>(out, n_workers, g.n_parts);
     HIP_TRY(hipGetLastError());
     {
