@@ -157,13 +157,12 @@ agg_insert_kernel(PartIdx src, uint32_t n_in, uint32_t seed, uint32_t *keys_base
     }
 }
 
-// The parts' value arrays as a table in memory (kernel arguments can only be indexed uniformly without a loop
-// over the distinct indices: constant indices here, one thread each).
+// The parts' value arrays as a table in memory, thread w the pointer of part w: one load per thread from the
+// argument buffer, all under way at once (fetched pointer by pointer with constant indices they come one after
+// the other, and the argument buffer lies in host memory).
 __device__ __forceinline__ void write_src_table(const Arr64<const float *> &src_values, const float **src_tab)
 {
-#pragma unroll
-    for (uint32_t w = 0; w < ZEN_MAX_BATCH; ++w)
-        if (threadIdx.x == w) src_tab[w] = src_values.v[w];
+    if (threadIdx.x < ZEN_MAX_BATCH) src_tab[threadIdx.x] = src_values.v[threadIdx.x];
 }
 
 // ----------------------------------------------------------------------------------------------

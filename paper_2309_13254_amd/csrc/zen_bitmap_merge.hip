@@ -77,15 +77,11 @@ bm_scan_kernel(BmArgs a, uint32_t *cnt, uint32_t n_chunks, uint32_t *counters_ba
                Arr64<const float *> src_values, uint64_t *tabs)
 {
     // tabs (element-level merges, else NULL): the parts' bitmap pointers [64] and value pointers [64] as tables in
-    // memory for the merge, whose lanes differ in the part they read (kernel arguments can only be indexed
-    // uniformly: constant indices here, one thread each)
-    if (tabs && blockIdx.x == 0) {
-#pragma unroll
-        for (uint32_t w = 0; w < ZEN_MAX_BATCH; ++w)
-            if (threadIdx.x == w) {
-                tabs[w] = (uint64_t)(uintptr_t)a.bitmap[w];
-                tabs[ZEN_MAX_BATCH + w] = (uint64_t)(uintptr_t)src_values.v[w];
-            }
+    // memory for the merge, whose lanes differ in the part they read (thread w copies part w's: one load per
+    // thread from the argument buffer, all under way at once)
+    if (tabs && blockIdx.x == 0 && threadIdx.x < ZEN_MAX_BATCH) {
+        tabs[threadIdx.x] = (uint64_t)(uintptr_t)a.bitmap[threadIdx.x];
+        tabs[ZEN_MAX_BATCH + threadIdx.x] = (uint64_t)(uintptr_t)src_values.v[threadIdx.x];
     }
     __shared__ uint32_t s_flags;
     const uint32_t server = blockIdx.x, p = a.first_part + server;
