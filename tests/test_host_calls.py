@@ -59,3 +59,15 @@ def test_bad_arguments_are_refused_on_the_host(zen):
         zen.zen_scheme_times(6, [1.0, 2.0, 3.0], 0.1, 1.0, 1.0)                                           # n not a power of two
     assert [zen.zen_status_str(s) for s in range(5)] == ["ok", "invalid argument", "capacity exceeded",
                                                          "out of memory / workspace too small", "HIP call failed"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's share; asked for more it says so and exits without touching a GPU."""
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
